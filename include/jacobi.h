@@ -1,0 +1,200 @@
+/*
+ * libjacobi - Jacobi relaxation on a block-decomposed Cartesian grid, on one
+ * AMD MI355X (gfx950).  C ABI; no C++ or framework types cross this boundary.
+ *
+ * The computation is the data-parallel part of the Jacobi proxy application of
+ * the paper (Sec. VI-C): the domain is cut into cuboid blocks ("tiles" here;
+ * the paper wraps each in a mobile object and treats it as a task, Sec. II on
+ * over-decomposition).  One iteration is
+ *     1. halo exchange  - every tile's edge cells are packed, moved to the face
+ *                         neighbours and unpacked into their halo cells;
+ *     2. Jacobi update  - once a tile has all its halos, every interior point
+ *                         becomes the mean of its 2d face neighbours;
+ * repeated a fixed number of times.  A residual norm (not in the paper; added
+ * so convergence can be observed) is available as a third operation.
+ *
+ * Arithmetic (the paper gives none; these choices are part of the contract):
+ *     2-D:  new = 0.25 * ((W + E) + (S + N))
+ *     3-D:  new = C6 * (((x- + x+) + (y- + y+)) + (z- + z+)),  C6 = fl(1/6)
+ *     residual(u) = sqrt( sum_interior ( sum_nbrs u - 2d*u )^2 ), sum in fp64.
+ * Device code is built with FP contraction off, so an fp64 grid is bit-identical
+ * to a straightforward CPU loop using the same expression.
+ *
+ * Conventions
+ *   - Row-major, last index (x) fastest.  dims/tiles arrays are ordered slowest
+ *     to fastest: {Ny, Nx} or {Nz, Ny, Nx}.
+ *   - "padded global array": (N+2) per dim; padded index 0 and N+1 hold the
+ *     Dirichlet boundary ring, 1..N the interior.
+ *   - "grid": the library's tile-major device buffer of jacobi_grid_bytes()
+ *     bytes, 256-byte aligned, allocated and owned by the CALLER (device memory).
+ *     Its layout is described by jacobi_get_layout(); move data in and out with
+ *     jacobi_scatter()/jacobi_gather().
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Unless stated, calls only enqueue work on `stream` and return at once.
+ *   - Every function returns a jacobi_status (0 = OK) and never throws or exits.
+ *     Arguments are validated before any device call, so argument errors are
+ *     reported identically on a machine without a GPU.
+ *   - A plan may be used by one host thread at a time; plans are independent.
+ */
+#ifndef JACOBI_H
+#define JACOBI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct jacobi_plan jacobi_plan; /* opaque */
+
+enum jacobi_dtype { JACOBI_F64 = 0, JACOBI_F32 = 1 };
+
+enum jacobi_status {
+    JACOBI_OK = 0,
+    JACOBI_EINVAL = 1,  /* null pointer, ndim not 2/3, dim <= 0, tiles <= 0, bad dtype,
+                           in == out, iters < 0, unknown option, tile too large */
+    JACOBI_ENOTDIV = 2, /* dims[d] % tiles[d] != 0 */
+    JACOBI_ENOMEM = 3,  /* host or device allocation failed */
+    JACOBI_EHIP = 4     /* a HIP call failed; text in jacobi_last_error() */
+};
+
+/*
+ * Tile-major grid layout (all counts in ELEMENTS of the plan's dtype).
+ * Tile t = (tz*Ty + ty)*Tx + tx starts at t*tile_stride.  Inside a tile:
+ *   - cell (k, i, c), with k in [0, nplanes), i in [0, th+2), c in [0, tw), lives at
+ *     (k*(th+2) + i)*pitch + c.  i = 0 and th+1 are the y halo rows; in 3-D k = 0 and
+ *     td+1 are the z halo planes (2-D: nplanes = 1, k = 0).  Rows are padded to
+ *     `pitch` (a multiple of 128 bytes) so every row starts on a cache-line boundary;
+ *     columns [tw, pitch) are padding with unspecified contents.
+ *   - the x halos are NOT stored beside the rows but in two dense arrays:
+ *     x- halo of row (k, i) at xhalo_offset + k*(th+2) + i,
+ *     x+ halo of row (k, i) at xhalo_offset + xhalo_pitch + k*(th+2) + i.
+ * A halo cell holds either a copy of the neighbouring tile's edge cell (refreshed
+ * by halo_exchange) or, on the domain boundary, the Dirichlet value.
+ */
+typedef struct jacobi_layout {
+    int32_t ndim;          /* 2 or 3 */
+    int32_t dtype;         /* jacobi_dtype */
+    int64_t dims[3];       /* interior extents, slowest->fastest; dims[0] = 1 in 2-D */
+    int64_t tiles[3];      /* tile counts Tz, Ty, Tx; Tz = 1 in 2-D */
+    int64_t tile[3];       /* tile interior extents td, th, tw; td = 1 in 2-D */
+    int64_t ntiles;
+    int64_t nplanes;       /* td + 2 in 3-D, 1 in 2-D */
+    int64_t pitch;         /* elements between consecutive rows */
+    int64_t plane;         /* elements between consecutive planes = (th+2)*pitch */
+    int64_t xhalo_offset;  /* start of the x- halo array inside a tile */
+    int64_t xhalo_pitch;   /* distance from the x- to the x+ halo array */
+    int64_t tile_stride;   /* elements between consecutive tiles */
+    int64_t grid_bytes;    /* ntiles * tile_stride * sizeof(element) */
+} jacobi_layout;
+
+/*
+ * jacobi_create: describe a block-decomposed domain (paper Sec. VI-C: "a 3D domain
+ * which is decomposed into cuboids"; 2-D is the same with one dimension fewer).
+ *   plan   out, host pointer; receives a new plan the caller frees with jacobi_destroy.
+ *   ndim   2 or 3.
+ *   dims   host array[ndim], interior points per dim, slowest->fastest, each > 0.
+ *   tiles  host array[ndim], tile counts per dim, each > 0 and dividing dims[d].
+ *   dtype  JACOBI_F64 or JACOBI_F32.
+ * Touches no device; device scratch for the residual is allocated on first use.
+ * Errors: EINVAL, ENOTDIV, ENOMEM.
+ */
+int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64_t *tiles,
+                  int dtype);
+
+/* Frees the plan and any device scratch it owns (synchronises the device if it owns any).
+ * NULL is accepted. */
+int jacobi_destroy(jacobi_plan *plan);
+
+/* Bytes the caller must allocate (device memory) for one grid; 0 if plan is NULL. */
+size_t jacobi_grid_bytes(const jacobi_plan *plan);
+
+/* Copies the layout description into *layout (host memory).  EINVAL on NULL. */
+int jacobi_get_layout(const jacobi_plan *plan, jacobi_layout *layout);
+
+/*
+ * jacobi_scatter / jacobi_gather: move a padded global array (DEVICE memory,
+ * prod(dims[d]+2) elements, row-major) into / out of a tile-major grid.
+ * scatter fills every cell of every tile, halos included (inter-tile halos get the
+ * neighbour's value, boundary halos the Dirichlet ring).  gather writes the interior
+ * of every tile and the boundary halos back to the global array (the whole padded
+ * array is rewritten; inter-tile halo copies are ignored).  Asynchronous on `stream`.
+ * Errors: EINVAL (null), EHIP.
+ */
+int jacobi_scatter(jacobi_plan *plan, const void *global_padded_dev, void *grid, void *stream);
+int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, void *stream);
+
+/*
+ * jacobi_sweep: `iters` Jacobi iterations (paper Sec. VI-C: per iteration, exchange
+ * halos, unpack, and "once all halos have been received" update the block).
+ *   in, out  two distinct device grids.  `in` holds the current field: tile interiors
+ *            and Dirichlet boundary halos must be valid; inter-tile halos need not be
+ *            (they are exchanged before the first update).  `out` may hold anything.
+ *   iters    >= 0.  0 is a no-op (*final = in).
+ *   final    nullable host pointer; receives the grid holding the result:
+ *            `out` if iters is odd, `in` if even (the two buffers ping-pong).
+ * First copies the Dirichlet boundary halos in -> out so both buffers carry them, then
+ * for each iteration: halo exchange on the source buffer, update into the other buffer.
+ * With option "fused" = 1 the update kernel itself writes each tile's fresh edge
+ * cells into the neighbours' halos of the destination buffer (pack, transfer and
+ * unpack fused into the update's epilogue), and only the first iteration needs a
+ * separate exchange; results are identical.
+ * After return, the inter-tile halos of the result are unspecified (stale or fresh
+ * depending on the option); call halo_exchange if they are needed.
+ * Asynchronous on `stream`; allocates nothing; does not synchronise.
+ * Errors: EINVAL (null, in == out, iters < 0), EHIP.
+ */
+int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final);
+
+/*
+ * halo_exchange: for every pair of face-adjacent tiles, copy each tile's edge cells
+ * into the other's halo cells, in place in `grid` (paper Sec. VI-C: pack, transfer,
+ * unpack - on one device the three collapse into one gather-scatter copy).
+ * Idempotent; Dirichlet boundary halos are not touched; a single-tile plan launches
+ * nothing.  Asynchronous on `stream`.  Errors: EINVAL, EHIP.
+ */
+int halo_exchange(jacobi_plan *plan, void *grid, void *stream);
+
+/*
+ * residual_norm: exchanges halos of `grid`, then writes
+ *     sqrt( sum over all interior points of (sum of face neighbours - 2d*u)^2 )
+ * to *result_dev (a DEVICE double).  The sum is accumulated in fp64 in a fixed
+ * two-stage order (per-wavefront shuffle tree -> LDS -> per-workgroup partial -> one
+ * final workgroup), so it is bit-reproducible from run to run.  Uses plan-owned
+ * device scratch, allocated (with a device synchronisation) on the first call.
+ * Asynchronous on `stream` otherwise.  Errors: EINVAL, ENOMEM, EHIP.
+ */
+int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *stream);
+
+/* Same, but delivers the value to HOST memory and synchronises `stream` first. */
+int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void *stream);
+
+/*
+ * Options (all int64).  Unknown key or out-of-range value -> EINVAL.
+ *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
+ *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
+ *                    through; 0 = choose from the shape (default 0)
+ *   "nontemporal"    0 | 1   streaming loads/stores bypassing cache allocation (default 0)
+ *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
+ *                    made by jacobi_sweep (read with jacobi_profile_read)
+ */
+int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value);
+int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);
+
+/*
+ * With option "profile" = 1: waits for the recorded events, returns the summed
+ * duration (milliseconds) and number of update-kernel launches since the last read,
+ * and resets the record.  At most 8192 launches are recorded between reads; later
+ * ones are not timed (and not counted).  Errors: EINVAL, EHIP.
+ */
+int jacobi_profile_read(jacobi_plan *plan, double *update_ms_total, int64_t *update_launches);
+
+/* Text of the calling thread's most recent error ("" if none).  Valid until the next
+ * failing call on this thread. */
+const char *jacobi_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JACOBI_H */

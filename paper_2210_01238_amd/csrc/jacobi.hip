@@ -1,0 +1,418 @@
+// C-ABI host side of libjacobi: plan/layout bookkeeping, argument validation and kernel
+// launches for the block-decomposed Jacobi iteration (paper Sec. VI-C).  Declarations and
+// the contract of every entry point are in include/jacobi.h.
+#include "jacobi.h"
+#include "jacobi_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using jk::Geo;
+using jk::StripParams;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *msg)
+{
+    g_err = msg;
+    return code;
+}
+int fail_hip(hipError_t e, const char *what)
+{
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return JACOBI_EHIP;
+}
+#define HIP_TRY(expr)                                        \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return fail_hip(e_, #expr);    \
+    } while (0)
+
+constexpr int MAX_PROFILE_EVENTS = 8192;
+constexpr int MAX_COPY_BLOCKS = 1 << 20;
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+struct jacobi_plan {
+    jacobi_layout lay;
+    Geo geo;
+    size_t esize;
+    // options
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 0, profile = 0;
+    // residual scratch (device), sized for the residual launch
+    double *partial = nullptr;
+    int64_t partial_cap = 0;
+    // profiling events around update launches
+    std::vector<hipEvent_t> ev;   // pairs: 2*i start, 2*i+1 stop
+    int64_t ev_used = 0;
+};
+
+namespace {
+
+// How the update / residual kernels cut the tiles into strips (see jacobi_kernels.h).
+StripParams make_strips(const jacobi_plan *p)
+{
+    const Geo &g = p->geo;
+    const int nv = 16 / (int)p->esize;
+    StripParams sp;
+    sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * nv);
+    const int extent = g.ndim == 3 ? g.td : g.th;       // marching direction
+    const int64_t lanes_of_work = (int64_t)g.ntiles * sp.nseg * (g.ndim == 3 ? g.th : 1);
+    int R = (int)p->rows_per_strip;
+    if (R <= 0) {
+        // aim for >= 8192 strips (32 wavefronts on each of 256 CUs) while keeping the border
+        // re-read (2 rows per strip) small: between 8 and 64 rows per strip
+        const int64_t want = 8192;
+        int64_t r = (int64_t)extent * lanes_of_work / want;
+        R = (int)(r < 8 ? 8 : r > 64 ? 64 : r);
+    }
+    if (R > extent) R = extent;
+    sp.R = R;
+    sp.nblk = (int)ceil_div(extent, R);
+    sp.nstrips = lanes_of_work * sp.nblk;
+    sp.fused = (int)p->fused;
+    return sp;
+}
+
+template <typename T, int MODE>
+int launch_sweep_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStream_t st)
+{
+    const StripParams sp = make_strips(p);
+    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+    const dim3 grid((unsigned)nwg), block(jk::WG);
+    constexpr int U = 4;
+    const bool nt = p->nontemporal != 0;
+    if (p->geo.ndim == 2) {
+        if (nt) hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U, true>), grid, block, 0, st, p->geo, sp, src, dst, partial);
+        else    hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U, false>), grid, block, 0, st, p->geo, sp, src, dst, partial);
+    } else {
+        if (nt) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, U, true>), grid, block, 0, st, p->geo, sp, src, dst, partial);
+        else    hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, U, false>), grid, block, 0, st, p->geo, sp, src, dst, partial);
+    }
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+int launch_update(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
+{
+    return p->lay.dtype == JACOBI_F64
+               ? launch_sweep_t<double, jk::MODE_UPDATE>(p, (const double *)src, (double *)dst, nullptr, st)
+               : launch_sweep_t<float, jk::MODE_UPDATE>(p, (const float *)src, (float *)dst, nullptr, st);
+}
+
+template <typename T, int FMODE>
+int launch_faces_t(jacobi_plan *p, const T *src, T *dst, hipStream_t st)
+{
+    const Geo &g = p->geo;
+    // largest face, in cells, including its edge cells (the boundary copy covers those too)
+    const int64_t pd = g.nplanes, ph = g.rows;
+    int64_t max_face = pd * ph;                                    // x faces
+    if (pd * g.tw > max_face) max_face = pd * g.tw;                // y faces
+    if (g.ndim == 3 && ph * g.tw > max_face) max_face = ph * g.tw; // z faces
+    const int chunks = (int)ceil_div(max_face, jk::FACE_CHUNK);
+    const int64_t nitems = (int64_t)g.ntiles * 2 * g.ndim * chunks;
+    const int64_t nblk = nitems < MAX_COPY_BLOCKS ? nitems : MAX_COPY_BLOCKS;
+    hipLaunchKernelGGL((jk::face_copy_kernel<T, FMODE>), dim3((unsigned)nblk), dim3(jk::WG), 0, st, g, src, dst,
+                       chunks, (long long)nitems);
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+int launch_exchange(jacobi_plan *p, void *grid, hipStream_t st)
+{
+    if (p->geo.ntiles == 1) return JACOBI_OK;   // no neighbours, nothing to copy
+    return p->lay.dtype == JACOBI_F64
+               ? launch_faces_t<double, jk::FACE_EXCHANGE>(p, (const double *)grid, (double *)grid, st)
+               : launch_faces_t<float, jk::FACE_EXCHANGE>(p, (const float *)grid, (float *)grid, st);
+}
+
+int launch_boundary_sync(jacobi_plan *p, const void *in, void *out, hipStream_t st)
+{
+    return p->lay.dtype == JACOBI_F64
+               ? launch_faces_t<double, jk::FACE_BOUNDARY>(p, (const double *)in, (double *)out, st)
+               : launch_faces_t<float, jk::FACE_BOUNDARY>(p, (const float *)in, (float *)out, st);
+}
+
+template <typename T, bool GATHER>
+int launch_sg_t(jacobi_plan *p, const T *from, T *to, hipStream_t st)
+{
+    const Geo &g = p->geo;
+    const long long GP = p->lay.dims[2] + 2, GQ = (p->lay.dims[1] + 2) * GP;
+    const int chunks = (int)ceil_div((int64_t)g.tw + 2, jk::WG);
+    const int64_t nitems = (int64_t)g.ntiles * g.nplanes * g.rows * chunks;
+    const int64_t nblk = nitems < MAX_COPY_BLOCKS ? nitems : MAX_COPY_BLOCKS;
+    hipLaunchKernelGGL((jk::scatter_gather_kernel<T, GATHER>), dim3((unsigned)nblk), dim3(jk::WG), 0, st, g, from, to,
+                       GP, GQ, chunks, (long long)nitems);
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+int ensure_partials(jacobi_plan *p, int64_t need)
+{
+    if (p->partial_cap >= need) return JACOBI_OK;
+    if (p->partial) {
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipFree(p->partial));
+        p->partial = nullptr;
+        p->partial_cap = 0;
+    }
+    hipError_t e = hipMalloc((void **)&p->partial, (size_t)need * sizeof(double));
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return fail(JACOBI_ENOMEM, "device allocation of residual scratch failed");
+    }
+    if (e != hipSuccess) return fail_hip(e, "hipMalloc(residual scratch)");
+    p->partial_cap = need;
+    return JACOBI_OK;
+}
+
+int residual_common(jacobi_plan *p, void *grid, double *result_dev, hipStream_t st)
+{
+    const StripParams sp = make_strips(p);
+    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    // one extra slot holds the result for the host variant
+    int rc = ensure_partials(p, nwg + 1);
+    if (rc) return rc;
+    rc = launch_exchange(p, grid, st);
+    if (rc) return rc;
+    rc = p->lay.dtype == JACOBI_F64
+             ? launch_sweep_t<double, jk::MODE_RESIDUAL>(p, (const double *)grid, (double *)grid, p->partial, st)
+             : launch_sweep_t<float, jk::MODE_RESIDUAL>(p, (const float *)grid, (float *)grid, p->partial, st);
+    if (rc) return rc;
+    double *out = result_dev ? result_dev : p->partial + nwg;
+    hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, p->partial, (long long)nwg, out);
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+int64_t *option_slot(jacobi_plan *p, const char *key)
+{
+    if (!strcmp(key, "fused")) return &p->fused;
+    if (!strcmp(key, "rows_per_strip")) return &p->rows_per_strip;
+    if (!strcmp(key, "nontemporal")) return &p->nontemporal;
+    if (!strcmp(key, "profile")) return &p->profile;
+    return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *jacobi_last_error(void) { return g_err.c_str(); }
+
+int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64_t *tiles, int dtype)
+{
+    if (!plan) return fail(JACOBI_EINVAL, "plan is NULL");
+    *plan = nullptr;
+    if (!dims || !tiles) return fail(JACOBI_EINVAL, "dims or tiles is NULL");
+    if (ndim != 2 && ndim != 3) return fail(JACOBI_EINVAL, "ndim must be 2 or 3");
+    if (dtype != JACOBI_F64 && dtype != JACOBI_F32) return fail(JACOBI_EINVAL, "unknown dtype");
+    for (int d = 0; d < ndim; ++d) {
+        if (dims[d] <= 0) return fail(JACOBI_EINVAL, "dims must be positive");
+        if (tiles[d] <= 0) return fail(JACOBI_EINVAL, "tiles must be positive");
+    }
+    for (int d = 0; d < ndim; ++d)
+        if (dims[d] % tiles[d]) return fail(JACOBI_ENOTDIV, "dims[d] is not a multiple of tiles[d]");
+
+    jacobi_plan *p = new (std::nothrow) jacobi_plan();
+    if (!p) return fail(JACOBI_ENOMEM, "host allocation failed");
+    jacobi_layout &L = p->lay;
+    memset(&L, 0, sizeof(L));
+    L.ndim = ndim;
+    L.dtype = dtype;
+    p->esize = dtype == JACOBI_F64 ? 8 : 4;
+    L.dims[0] = L.tiles[0] = L.tile[0] = 1;
+    for (int d = 0; d < ndim; ++d) {
+        const int s = 3 - ndim + d;
+        L.dims[s] = dims[d];
+        L.tiles[s] = tiles[d];
+        L.tile[s] = dims[d] / tiles[d];
+    }
+    const int64_t line = 128 / (int64_t)p->esize;   // elements per 128-byte cache line
+    L.ntiles = L.tiles[0] * L.tiles[1] * L.tiles[2];
+    L.nplanes = ndim == 3 ? L.tile[0] + 2 : 1;
+    L.pitch = round_up(L.tile[2], line);
+    L.plane = (L.tile[1] + 2) * L.pitch;
+    L.xhalo_offset = L.nplanes * L.plane;
+    L.xhalo_pitch = round_up(L.nplanes * (L.tile[1] + 2), line);
+    L.tile_stride = L.xhalo_offset + 2 * L.xhalo_pitch;
+    L.grid_bytes = L.ntiles * L.tile_stride * (int64_t)p->esize;
+
+    const int64_t lim = 0x7fffffffLL;
+    if (L.tile_stride > lim || L.ntiles > lim || L.dims[0] + 2 > lim || L.dims[1] + 2 > lim || L.dims[2] + 2 > lim) {
+        delete p;
+        return fail(JACOBI_EINVAL, "tile or tile count too large (32-bit index limit inside a tile)");
+    }
+    Geo &g = p->geo;
+    g.ndim = ndim;
+    g.Tz = (int)L.tiles[0]; g.Ty = (int)L.tiles[1]; g.Tx = (int)L.tiles[2];
+    g.td = (int)L.tile[0];  g.th = (int)L.tile[1];  g.tw = (int)L.tile[2];
+    g.rows = g.th + 2;
+    g.nplanes = (int)L.nplanes;
+    g.z0 = ndim == 3 ? 1 : 0;
+    g.pitch = (int)L.pitch;
+    g.ntiles = (int)L.ntiles;
+    g.plane = L.plane;
+    g.xoff = L.xhalo_offset;
+    g.hpitch = L.xhalo_pitch;
+    g.tile_stride = L.tile_stride;
+    *plan = p;
+    return JACOBI_OK;
+}
+
+int jacobi_destroy(jacobi_plan *plan)
+{
+    if (!plan) return JACOBI_OK;
+    int rc = JACOBI_OK;
+    if (plan->partial || !plan->ev.empty()) {
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) rc = fail_hip(e, "hipDeviceSynchronize");
+        if (plan->partial) (void)hipFree(plan->partial);
+        for (hipEvent_t ev : plan->ev) (void)hipEventDestroy(ev);
+    }
+    delete plan;
+    return rc;
+}
+
+size_t jacobi_grid_bytes(const jacobi_plan *plan) { return plan ? (size_t)plan->lay.grid_bytes : 0; }
+
+int jacobi_get_layout(const jacobi_plan *plan, jacobi_layout *layout)
+{
+    if (!plan || !layout) return fail(JACOBI_EINVAL, "plan or layout is NULL");
+    *layout = plan->lay;
+    return JACOBI_OK;
+}
+
+int jacobi_scatter(jacobi_plan *plan, const void *global_padded_dev, void *grid, void *stream)
+{
+    if (!plan || !global_padded_dev || !grid) return fail(JACOBI_EINVAL, "NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    return plan->lay.dtype == JACOBI_F64
+               ? launch_sg_t<double, false>(plan, (const double *)global_padded_dev, (double *)grid, st)
+               : launch_sg_t<float, false>(plan, (const float *)global_padded_dev, (float *)grid, st);
+}
+
+int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, void *stream)
+{
+    if (!plan || !global_padded_dev || !grid) return fail(JACOBI_EINVAL, "NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    return plan->lay.dtype == JACOBI_F64
+               ? launch_sg_t<double, true>(plan, (const double *)grid, (double *)global_padded_dev, st)
+               : launch_sg_t<float, true>(plan, (const float *)grid, (float *)global_padded_dev, st);
+}
+
+int halo_exchange(jacobi_plan *plan, void *grid, void *stream)
+{
+    if (!plan || !grid) return fail(JACOBI_EINVAL, "NULL argument");
+    return launch_exchange(plan, grid, (hipStream_t)stream);
+}
+
+int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final)
+{
+    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
+    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
+    if (final) *final = in;
+    if (iters == 0) return JACOBI_OK;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (plan->profile && plan->ev.empty()) {
+        plan->ev.reserve(2 * MAX_PROFILE_EVENTS);
+        for (int i = 0; i < 2 * MAX_PROFILE_EVENTS; ++i) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            plan->ev.push_back(e);
+        }
+    }
+
+    int rc = launch_boundary_sync(plan, in, out, st);
+    if (rc) return rc;
+    void *src = in, *dst = out;
+    for (int k = 0; k < iters; ++k) {
+        // halos of src must be current before the update reads them; in fused mode the previous
+        // update already wrote them, so only the very first source buffer needs the copy kernel
+        if (!plan->fused || k == 0) {
+            rc = launch_exchange(plan, src, st);
+            if (rc) return rc;
+        }
+        const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
+        if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
+        rc = launch_update(plan, src, dst, st);
+        if (rc) return rc;
+        if (timed) {
+            HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));
+            ++plan->ev_used;
+        }
+        void *t = src; src = dst; dst = t;
+    }
+    if (final) *final = src;
+    return JACOBI_OK;
+}
+
+int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *stream)
+{
+    if (!plan || !grid || !result_dev) return fail(JACOBI_EINVAL, "NULL argument");
+    return residual_common(plan, grid, result_dev, (hipStream_t)stream);
+}
+
+int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void *stream)
+{
+    if (!plan || !grid || !result_host) return fail(JACOBI_EINVAL, "NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    int rc = residual_common(plan, grid, nullptr, st);
+    if (rc) return rc;
+    const StripParams sp = make_strips(plan);
+    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    HIP_TRY(hipMemcpyAsync(result_host, plan->partial + nwg, sizeof(double), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    return JACOBI_OK;
+}
+
+int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
+{
+    if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
+    int64_t *slot = option_slot(plan, key);
+    if (!slot) return fail(JACOBI_EINVAL, "unknown option");
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : 1;
+    if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
+    *slot = value;
+    return JACOBI_OK;
+}
+
+int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value)
+{
+    if (!plan || !key || !value) return fail(JACOBI_EINVAL, "NULL argument");
+    int64_t *slot = option_slot(const_cast<jacobi_plan *>(plan), key);
+    if (!slot) return fail(JACOBI_EINVAL, "unknown option");
+    *value = *slot;
+    return JACOBI_OK;
+}
+
+int jacobi_profile_read(jacobi_plan *plan, double *update_ms_total, int64_t *update_launches)
+{
+    if (!plan || !update_ms_total || !update_launches) return fail(JACOBI_EINVAL, "NULL argument");
+    double tot = 0.0;
+    for (int64_t i = 0; i < plan->ev_used; ++i) {
+        HIP_TRY(hipEventSynchronize(plan->ev[2 * i + 1]));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, plan->ev[2 * i], plan->ev[2 * i + 1]));
+        tot += ms;
+    }
+    *update_ms_total = tot;
+    *update_launches = plan->ev_used;
+    plan->ev_used = 0;
+    return JACOBI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,480 @@
+// Device code for the block-decomposed Jacobi iteration (paper Sec. VI-C) on gfx950.
+//
+// Work decomposition.  The paper's unit of work is a block (tile) = one task; on one
+// MI355X a tile is far too coarse (and, with thousands of small tiles, too fine) to be
+// a launch, so every kernel here covers ALL tiles in one launch and splits each tile
+// into "strips": a strip is the part of a tile one 64-lane wavefront marches through,
+//   2-D: 64*NV consecutive columns x R consecutive rows,
+//   3-D: 64*NV consecutive columns of one row x R consecutive planes,
+// with NV elements (16 bytes) per lane, so every wavefront load/store is one contiguous,
+// 16-byte-per-lane, cache-line-aligned 1 KiB access.  The marching direction keeps the
+// previous/current/next row (plane) in registers, so the two neighbours along it cost
+// no memory traffic; the x neighbours come from the adjacent lanes through the LDS
+// crossbar (ds_bpermute via __shfl) and, at the ends of the wavefront, from one extra
+// 8-byte load (the neighbouring strip's cell or the tile's dense x-halo array).
+//
+// Workgroups (4 wavefronts = 4 consecutive strips) are renumbered so that each of the
+// 8 XCDs works through one contiguous eighth of the strip list: neighbouring strips
+// re-read each other's border rows, and this keeps those re-reads inside one XCD's L2.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace jk {
+
+constexpr int WAVE = 64;
+constexpr int WAVES_PER_WG = 4;
+constexpr int WG = WAVE * WAVES_PER_WG;
+constexpr int NUM_XCD = 8;
+
+// Geometry of a plan, passed to kernels by value.
+struct Geo {
+    int ndim;
+    int Tz, Ty, Tx;   // tile counts
+    int td, th, tw;   // tile interior extents (td = 1 in 2-D)
+    int rows;         // th + 2
+    int nplanes;      // td + 2 (3-D) or 1 (2-D)
+    int z0;           // index of the first interior plane: 1 (3-D) or 0 (2-D)
+    int pitch;        // elements per row, multiple of 128 bytes
+    int ntiles;
+    long long plane;        // rows * pitch
+    long long xoff;         // x- halo array offset inside a tile
+    long long hpitch;       // x- -> x+ halo array distance
+    long long tile_stride;  // elements per tile
+};
+
+__device__ __forceinline__ long long main_off(const Geo &g, int k, int i, int c)
+{
+    return ((long long)k * g.rows + i) * g.pitch + c;
+}
+__device__ __forceinline__ long long xm_off(const Geo &g, int k, int i)
+{
+    return g.xoff + (long long)k * g.rows + i;
+}
+__device__ __forceinline__ long long xp_off(const Geo &g, int k, int i)
+{
+    return g.xoff + g.hpitch + (long long)k * g.rows + i;
+}
+
+template <typename T> struct Vec;
+template <> struct Vec<double> {
+    static constexpr int N = 2;
+    typedef double type __attribute__((ext_vector_type(2)));
+};
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    typedef float type __attribute__((ext_vector_type(4)));
+};
+
+template <typename T> struct Coef;
+template <> struct Coef<double> {
+    static constexpr double quarter = 0.25, sixth = 1.0 / 6.0, four = 4.0, six = 6.0;
+};
+template <> struct Coef<float> {
+    static constexpr float quarter = 0.25f, sixth = 1.0f / 6.0f, four = 4.0f, six = 6.0f;
+};
+
+template <bool NT, typename V> __device__ __forceinline__ V ldv(const V *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT, typename V> __device__ __forceinline__ void stv(V *p, V v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Workgroup renumbering: hardware hands consecutive workgroup ids to the XCDs round-robin;
+// give XCD x the contiguous range of logical ids it would get if the list were cut in 8.
+__device__ __forceinline__ long long xcd_logical_wg()
+{
+    const long long n = gridDim.x, b = blockIdx.x;
+    const long long x = b % NUM_XCD, q = n / NUM_XCD, r = n % NUM_XCD;
+    const long long start = x * q + (x < r ? x : r);
+    return start + b / NUM_XCD;
+}
+
+// Sum over the 64 lanes in a fixed butterfly order (same bits on every run).
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);
+    return v;
+}
+
+// Workgroup sum: wavefront shuffle tree -> one LDS slot per wavefront -> fixed-order add.
+// Every thread of the workgroup must call it; the result is valid in thread 0.
+__device__ __forceinline__ double wg_sum(double v, double *lds /* WAVES_PER_WG (or more) slots */)
+{
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    v = wave_sum(v);
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    double s = 0.0;
+    if (threadIdx.x == 0) {
+        const int nw = blockDim.x / WAVE;
+        for (int w = 0; w < nw; ++w) s += lds[w];
+    }
+    return s;
+}
+
+enum Mode { MODE_UPDATE = 0, MODE_RESIDUAL = 1 };
+
+struct StripParams {
+    int R;               // rows (2-D) / planes (3-D) per strip
+    int nseg;            // column segments per row = ceil(pitch / (64*NV))
+    int nblk;            // strips along the marching direction = ceil(extent / R)
+    long long nstrips;   // total
+    int fused;           // update mode: push edge cells into neighbour halos of dst
+};
+
+// ------------------------------------------------------------------------------------
+// 2-D: 5-point update (or residual) of every tile.  new = 0.25*((W+E)+(S+N)).
+// ------------------------------------------------------------------------------------
+template <typename T, int MODE, int U, bool NT>
+__global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
+                                                     const T *__restrict__ src, T *__restrict__ dst,
+                                                     double *__restrict__ partial)
+{
+    using V = typename Vec<T>::type;
+    constexpr int NV = Vec<T>::N;
+    __shared__ double red[WAVES_PER_WG];
+
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    const long long lwg = xcd_logical_wg();
+    const long long s = lwg * WAVES_PER_WG + wave;
+    double acc = 0.0;
+
+    if (s < sp.nstrips) {
+        const int per_tile = sp.nblk * sp.nseg;
+        const int t = (int)(s / per_tile);
+        const int rem = (int)(s - (long long)t * per_tile);
+        const int rb = rem / sp.nseg, seg = rem - rb * sp.nseg;
+        const int ty = t / g.Tx, tx = t - ty * g.Tx;
+        const int r0 = 1 + rb * sp.R;
+        const int r1 = min(g.th, r0 + sp.R - 1);
+        const int col0 = (seg * WAVE + lane) * NV;
+        const bool active = col0 < g.pitch;   // pitch is a multiple of NV: no straddling
+        const int last = g.tw - 1;
+        const bool has_last = active && col0 <= last && last < col0 + NV;
+        const int jlast = last - col0;
+        const bool w_lane = active && lane == 0;
+        const bool w_halo = col0 == 0;        // W neighbour of column 0 is the x- halo
+        const bool e_lane = has_last || (active && lane == WAVE - 1 && col0 + NV < g.pitch);
+
+        const T *tsrc = src + (long long)t * g.tile_stride;
+        T *tdst = dst + (long long)t * g.tile_stride;
+        // neighbour tiles of dst that receive this strip's edge cells (fused mode)
+        const bool push = MODE == MODE_UPDATE && sp.fused;
+        T *dst_ym = (push && ty > 0) ? tdst - (long long)g.Tx * g.tile_stride : nullptr;
+        T *dst_yp = (push && ty < g.Ty - 1) ? tdst + (long long)g.Tx * g.tile_stride : nullptr;
+        T *dst_xm = (push && tx > 0 && col0 == 0 && active) ? tdst - g.tile_stride : nullptr;
+        T *dst_xp = (push && tx < g.Tx - 1 && has_last) ? tdst + g.tile_stride : nullptr;
+
+        V prev = V(0), cur = V(0);
+        if (active) {
+            prev = ldv<NT>((const V *)(tsrc + main_off(g, 0, r0 - 1, col0)));
+            cur = ldv<NT>((const V *)(tsrc + main_off(g, 0, r0, col0)));
+        }
+        for (int r = r0; r <= r1; r += U) {
+            V nx[U];
+            T ew[U], ee[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int rn = min(r + u + 1, g.th + 1);   // clamped: stays inside the tile
+                nx[u] = active ? ldv<NT>((const V *)(tsrc + main_off(g, 0, rn, col0))) : V(0);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int rc = min(r + u, g.th + 1);
+                ew[u] = T(0);
+                ee[u] = T(0);
+                if (w_lane) ew[u] = w_halo ? tsrc[xm_off(g, 0, rc)] : tsrc[main_off(g, 0, rc, col0 - 1)];
+                if (e_lane) ee[u] = has_last ? tsrc[xp_off(g, 0, rc)] : tsrc[main_off(g, 0, rc, col0 + NV)];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int rr = r + u;
+                T left = __shfl_up(cur[NV - 1], 1, WAVE);
+                T right = __shfl_down(cur[0], 1, WAVE);
+                if (lane == 0) left = ew[u];
+                if (lane == WAVE - 1) right = ee[u];
+                if (rr <= r1) {
+                    V out;
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) {
+                        const T w = j == 0 ? left : cur[j - 1];
+                        T e = j == NV - 1 ? right : cur[j + 1];
+                        if (has_last && j == jlast) e = ee[u];
+                        const T we = w + e;
+                        const T sn = prev[j] + nx[u][j];
+                        if constexpr (MODE == MODE_UPDATE) {
+                            out[j] = Coef<T>::quarter * (we + sn);
+                        } else {
+                            const T res = (we + sn) - Coef<T>::four * cur[j];
+                            const double rd = (double)res;
+                            if (col0 + j <= last) acc += rd * rd;
+                        }
+                    }
+                    if constexpr (MODE == MODE_UPDATE) {
+                        if (active) {
+                            stv<NT>((V *)(tdst + main_off(g, 0, rr, col0)), out);
+                            if (push) {
+                                if (rr == 1 && dst_ym) *(V *)(dst_ym + main_off(g, 0, g.th + 1, col0)) = out;
+                                if (rr == g.th && dst_yp) *(V *)(dst_yp + main_off(g, 0, 0, col0)) = out;
+                                if (dst_xm) dst_xm[xp_off(g, 0, rr)] = out[0];
+                                if (dst_xp) dst_xp[xm_off(g, 0, rr)] = out[jlast];
+                            }
+                        }
+                    }
+                }
+                prev = cur;
+                cur = nx[u];
+            }
+        }
+    }
+    if constexpr (MODE == MODE_RESIDUAL) {
+        const double tot = wg_sum(acc, red);
+        if (threadIdx.x == 0) partial[lwg] = tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// 3-D: 7-point update (or residual).  new = C6*(((x- + x+)+(y- + y+))+(z- + z+)).
+// A wavefront owns one row (i) x 64*NV columns and marches through R planes keeping
+// planes k-1, k, k+1 of its row in registers; rows i-1 and i+1 of plane k are loaded
+// (they are the "current" rows of the neighbouring wavefronts, so they come from cache).
+// ------------------------------------------------------------------------------------
+template <typename T, int MODE, int U, bool NT>
+__global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
+                                                     const T *__restrict__ src, T *__restrict__ dst,
+                                                     double *__restrict__ partial)
+{
+    using V = typename Vec<T>::type;
+    constexpr int NV = Vec<T>::N;
+    __shared__ double red[WAVES_PER_WG];
+
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    const long long lwg = xcd_logical_wg();
+    const long long s = lwg * WAVES_PER_WG + wave;
+    double acc = 0.0;
+
+    if (s < sp.nstrips) {
+        // strip order: tile -> plane block -> row -> column segment
+        const long long per_tile = (long long)sp.nblk * g.th * sp.nseg;
+        const int t = (int)(s / per_tile);
+        int rem = (int)(s - (long long)t * per_tile);
+        const int kb = rem / (g.th * sp.nseg);
+        rem -= kb * g.th * sp.nseg;
+        const int i = 1 + rem / sp.nseg, seg = rem % sp.nseg;
+        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+        const int k0 = 1 + kb * sp.R;
+        const int k1 = min(g.td, k0 + sp.R - 1);
+        const int col0 = (seg * WAVE + lane) * NV;
+        const bool active = col0 < g.pitch;
+        const int last = g.tw - 1;
+        const bool has_last = active && col0 <= last && last < col0 + NV;
+        const int jlast = last - col0;
+        const bool w_lane = active && lane == 0;
+        const bool w_halo = col0 == 0;
+        const bool e_lane = has_last || (active && lane == WAVE - 1 && col0 + NV < g.pitch);
+
+        const T *tsrc = src + (long long)t * g.tile_stride;
+        T *tdst = dst + (long long)t * g.tile_stride;
+        const bool push = MODE == MODE_UPDATE && sp.fused;
+        const long long zs = (long long)g.Ty * g.Tx * g.tile_stride, ys = (long long)g.Tx * g.tile_stride;
+        T *dst_zm = (push && tz > 0) ? tdst - zs : nullptr;
+        T *dst_zp = (push && tz < g.Tz - 1) ? tdst + zs : nullptr;
+        T *dst_ym = (push && ty > 0 && i == 1) ? tdst - ys : nullptr;
+        T *dst_yp = (push && ty < g.Ty - 1 && i == g.th) ? tdst + ys : nullptr;
+        T *dst_xm = (push && tx > 0 && col0 == 0 && active) ? tdst - g.tile_stride : nullptr;
+        T *dst_xp = (push && tx < g.Tx - 1 && has_last) ? tdst + g.tile_stride : nullptr;
+
+        V below = V(0), cur = V(0);
+        if (active) {
+            below = ldv<NT>((const V *)(tsrc + main_off(g, k0 - 1, i, col0)));
+            cur = ldv<NT>((const V *)(tsrc + main_off(g, k0, i, col0)));
+        }
+        for (int k = k0; k <= k1; k += U) {
+            V up[U], ym[U], yp[U];
+            T ew[U], ee[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kn = min(k + u + 1, g.td + 1);
+                const int kc = min(k + u, g.td + 1);
+                up[u] = ym[u] = yp[u] = V(0);
+                if (active) {
+                    up[u] = ldv<NT>((const V *)(tsrc + main_off(g, kn, i, col0)));
+                    ym[u] = *(const V *)(tsrc + main_off(g, kc, i - 1, col0));
+                    yp[u] = *(const V *)(tsrc + main_off(g, kc, i + 1, col0));
+                }
+                ew[u] = T(0);
+                ee[u] = T(0);
+                if (w_lane) ew[u] = w_halo ? tsrc[xm_off(g, kc, i)] : tsrc[main_off(g, kc, i, col0 - 1)];
+                if (e_lane) ee[u] = has_last ? tsrc[xp_off(g, kc, i)] : tsrc[main_off(g, kc, i, col0 + NV)];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kk = k + u;
+                T left = __shfl_up(cur[NV - 1], 1, WAVE);
+                T right = __shfl_down(cur[0], 1, WAVE);
+                if (lane == 0) left = ew[u];
+                if (lane == WAVE - 1) right = ee[u];
+                if (kk <= k1) {
+                    V out;
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) {
+                        const T w = j == 0 ? left : cur[j - 1];
+                        T e = j == NV - 1 ? right : cur[j + 1];
+                        if (has_last && j == jlast) e = ee[u];
+                        const T xx = w + e;
+                        const T yy = ym[u][j] + yp[u][j];
+                        const T zz = below[j] + up[u][j];
+                        if constexpr (MODE == MODE_UPDATE) {
+                            out[j] = Coef<T>::sixth * ((xx + yy) + zz);
+                        } else {
+                            const T res = ((xx + yy) + zz) - Coef<T>::six * cur[j];
+                            const double rd = (double)res;
+                            if (col0 + j <= last) acc += rd * rd;
+                        }
+                    }
+                    if constexpr (MODE == MODE_UPDATE) {
+                        if (active) {
+                            stv<NT>((V *)(tdst + main_off(g, kk, i, col0)), out);
+                            if (push) {
+                                if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
+                                if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
+                                if (dst_ym) *(V *)(dst_ym + main_off(g, kk, g.th + 1, col0)) = out;
+                                if (dst_yp) *(V *)(dst_yp + main_off(g, kk, 0, col0)) = out;
+                                if (dst_xm) dst_xm[xp_off(g, kk, i)] = out[0];
+                                if (dst_xp) dst_xp[xm_off(g, kk, i)] = out[jlast];
+                            }
+                        }
+                    }
+                }
+                below = cur;
+                cur = up[u];
+            }
+        }
+    }
+    if constexpr (MODE == MODE_RESIDUAL) {
+        const double tot = wg_sum(acc, red);
+        if (threadIdx.x == 0) partial[lwg] = tot;
+    }
+}
+
+// Final stage of the residual: one workgroup adds the per-workgroup partials in a fixed
+// order (thread t takes t, t+1024, ...; then shuffle tree + LDS) and writes the sqrt.
+__global__ __launch_bounds__(1024) void residual_final_kernel(const double *__restrict__ partial,
+                                                              long long n, double *__restrict__ result)
+{
+    __shared__ double red[16];
+    double acc = 0.0;
+    for (long long i = threadIdx.x; i < n; i += blockDim.x) acc += partial[i];
+    const double tot = wg_sum(acc, red);
+    if (threadIdx.x == 0) *result = sqrt(tot);
+}
+
+// ------------------------------------------------------------------------------------
+// Face copies.  A face of a tile is one of its 2*ndim halo faces (0: x-, 1: x+, 2: y-,
+// 3: y+, 4: z-, 5: z+), interior extent only (edges/corners are never read by the
+// stencils).  EXCHANGE: for faces with a neighbouring tile, halo <- neighbour's edge cells
+// (pack + transfer + unpack in one gather-scatter copy), within one grid.  BOUNDARY: for
+// faces on the domain boundary, copy the Dirichlet halo cells from `src` grid to `dst` grid.
+// Work item = (tile, face, chunk of 4*WG cells); workgroups stride over the item list.
+// ------------------------------------------------------------------------------------
+enum FaceMode { FACE_EXCHANGE = 0, FACE_BOUNDARY = 1 };
+constexpr int FACE_CHUNK = 4 * WG;
+
+template <typename T, int FMODE>
+__global__ __launch_bounds__(WG) void face_copy_kernel(Geo g, const T *__restrict__ src, T *__restrict__ dst,
+                                                       int chunks_per_face, long long nitems)
+{
+    const int nfaces = 2 * g.ndim;
+    for (long long item = blockIdx.x; item < nitems; item += gridDim.x) {
+        const int chunk = (int)(item % chunks_per_face);
+        const long long tf = item / chunks_per_face;
+        const int face = (int)(tf % nfaces), t = (int)(tf / nfaces);
+        const int axis = face >> 1, hi = face & 1;   // axis 0: x, 1: y, 2: z
+        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+        const int tc = axis == 0 ? tx : axis == 1 ? ty : tz;
+        const int Tn = axis == 0 ? g.Tx : axis == 1 ? g.Ty : g.Tz;
+        const bool has_nbr = hi ? tc < Tn - 1 : tc > 0;
+        if ((FMODE == FACE_EXCHANGE) != has_nbr) continue;
+
+        const long long tstep = axis == 0 ? 1 : axis == 1 ? g.Tx : (long long)g.Ty * g.Tx;
+        const T *stile = src + ((long long)t + (FMODE == FACE_EXCHANGE ? (hi ? tstep : -tstep) : 0)) * g.tile_stride;
+        T *dtile = dst + (long long)t * g.tile_stride;
+
+        // face cells are indexed (a, b) with b fastest.  EXCHANGE copies the interior extent of
+        // the face; BOUNDARY the full padded extent (face plus its edges and corners), so the
+        // destination grid carries the complete Dirichlet ring.
+        constexpr int X = FMODE == FACE_BOUNDARY ? 1 : 0;   // extend by the halo cells
+        const int nb = axis == 0 ? g.th + 2 * X : g.tw;
+        const int na = axis == 2 ? g.th + 2 * X : (X ? g.nplanes : g.td);
+        const int k_first = X ? 0 : g.z0, i_first = X ? 0 : 1;
+        const long long n = (long long)na * nb;
+        const long long base = (long long)chunk * FACE_CHUNK;
+        for (int q = 0; q < 4; ++q) {
+            const long long e = base + q * WG + threadIdx.x;
+            if (e >= n) break;
+            const int a = (int)(e / nb), b = (int)(e - (long long)a * nb);
+            long long so, dofs;
+            if (axis == 0) {          // (a, b) = (plane, row)
+                const int k = k_first + a, i = i_first + b;
+                dofs = hi ? xp_off(g, k, i) : xm_off(g, k, i);
+                so = FMODE == FACE_BOUNDARY ? dofs : main_off(g, k, i, hi ? 0 : g.tw - 1);
+            } else if (axis == 1) {   // (a, b) = (plane, column)
+                const int k = k_first + a;
+                dofs = main_off(g, k, hi ? g.th + 1 : 0, b);
+                so = FMODE == FACE_BOUNDARY ? dofs : main_off(g, k, hi ? 1 : g.th, b);
+            } else {                  // (a, b) = (row, column)
+                const int i = i_first + a;
+                dofs = main_off(g, hi ? g.td + 1 : 0, i, b);
+                so = FMODE == FACE_BOUNDARY ? dofs : main_off(g, hi ? 1 : g.td, i, b);
+            }
+            dtile[dofs] = stile[so];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Scatter / gather between a padded global array and the tile-major grid.
+// Work item = (tile, padded plane, padded row, chunk of WG columns); one thread per padded
+// cell, column index cc in [-1, tw].  Workgroups stride over the item list.
+// ------------------------------------------------------------------------------------
+template <typename T, bool GATHER>
+__global__ __launch_bounds__(WG) void scatter_gather_kernel(Geo g, const T *__restrict__ from, T *__restrict__ to,
+                                                            long long GP, long long GQ, int chunks_per_row,
+                                                            long long nitems)
+{
+    for (long long item = blockIdx.x; item < nitems; item += gridDim.x) {
+        const int chunk = (int)(item % chunks_per_row);
+        long long rest = item / chunks_per_row;
+        const int i = (int)(rest % g.rows);
+        rest /= g.rows;
+        const int k = (int)(rest % g.nplanes), t = (int)(rest / g.nplanes);
+        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+        const int cc = chunk * WG + (int)threadIdx.x - 1;
+        if (cc > g.tw) continue;
+        const long long toff = (long long)t * g.tile_stride +
+                               (cc < 0 ? xm_off(g, k, i) : cc == g.tw ? xp_off(g, k, i) : main_off(g, k, i, cc));
+        const long long gk = g.ndim == 3 ? (long long)tz * g.td + k : 0;
+        const long long gi = (long long)ty * g.th + i, gj = (long long)tx * g.tw + cc + 1;
+        const long long goff = gk * GQ + gi * GP + gj;
+        if constexpr (!GATHER) {
+            to[toff] = from[goff];
+        } else {
+            // a padded cell of the tile is written back if it is interior to the tile, or lies on
+            // the domain boundary; copies of neighbouring tiles' cells are skipped
+            const bool in_k = g.ndim == 2 || (k >= 1 && k <= g.td) || (k == 0 && tz == 0) ||
+                              (k == g.td + 1 && tz == g.Tz - 1);
+            const bool in_i = (i >= 1 && i <= g.th) || (i == 0 && ty == 0) || (i == g.th + 1 && ty == g.Ty - 1);
+            const bool in_c = (cc >= 0 && cc < g.tw) || (cc < 0 && tx == 0) || (cc == g.tw && tx == g.Tx - 1);
+            if (in_k && in_i && in_c) to[goff] = from[toff];
+        }
+    }
+}
+
+}  // namespace jk

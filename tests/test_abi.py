@@ -1,0 +1,99 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, computes the documented layout, and reports argument errors before any
+device call (so these run on a machine without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def J():
+    import paper_2210_01238_amd as J
+    return J
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "jacobi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_header_and_exports_agree(J):
+    decl = declared_functions()
+    assert sorted(J.EXPORTS) == decl
+    raw = ctypes.CDLL(J.LIB_PATH)
+    for name in decl:
+        assert hasattr(raw, name), name
+
+
+def test_core_entry_points_present(J):
+    for name in ("jacobi_create", "jacobi_sweep", "halo_exchange", "residual_norm"):
+        assert name in J.EXPORTS
+
+
+def test_layout_2d(J):
+    p = J.jacobi_create((16384, 16384), (8, 8), J.JACOBI_F64)
+    L = J.jacobi_get_layout(p)
+    assert (L.ndim, L.ntiles, L.nplanes) == (2, 64, 1)
+    assert list(L.tile) == [1, 2048, 2048] and list(L.tiles) == [1, 8, 8]
+    assert L.pitch == 2048 and L.plane == 2050 * 2048 and L.xhalo_offset == L.plane
+    assert L.xhalo_pitch % 16 == 0 and L.xhalo_pitch >= 2050
+    assert L.tile_stride == L.xhalo_offset + 2 * L.xhalo_pitch
+    assert L.grid_bytes == 64 * L.tile_stride * 8 == J.jacobi_grid_bytes(p)
+    assert (L.pitch * 8) % 128 == 0 and (L.tile_stride * 8) % 128 == 0
+    J.jacobi_destroy(p)
+
+
+def test_layout_ragged_and_f32_and_3d(J):
+    p = J.jacobi_create((30, 100), (3, 4), J.JACOBI_F32)
+    L = J.jacobi_get_layout(p)
+    assert list(L.tile) == [1, 10, 25] and L.pitch == 32 and L.dtype == J.JACOBI_F32
+    assert L.grid_bytes == 12 * L.tile_stride * 4
+    J.jacobi_destroy(p)
+    p = J.jacobi_create((512, 512, 512), (4, 4, 4), J.JACOBI_F64)
+    L = J.jacobi_get_layout(p)
+    assert L.nplanes == 130 and L.plane == 130 * 128 and L.xhalo_offset == 130 * L.plane
+    assert L.xhalo_pitch >= 130 * 130
+    J.jacobi_destroy(p)
+
+
+@pytest.mark.parametrize("dims,tiles,dtype,code", [
+    ((10, 10), (3, 2), 0, 2), ((0, 10), (1, 1), 0, 1), ((10, 10), (0, 1), 0, 1),
+    ((10, 10), (1, 1), 7, 1), ((10,), (1,), 0, 1), ((4, 4, 4, 4), (1, 1, 1, 1), 0, 1),
+    ((-5, 10), (1, 1), 0, 1), ((8, 8, 9), (2, 2, 2), 1, 2),
+])
+def test_create_rejects(J, dims, tiles, dtype, code):
+    with pytest.raises(J.JacobiError) as e:
+        J.jacobi_create(dims, tiles, dtype)
+    assert e.value.code == code and J.jacobi_last_error() != ""
+
+
+def test_null_and_argument_errors_without_device(J):
+    raw = J.binding.lib
+    assert raw.jacobi_create(None, 2, None, None, 0) == J.binding.JACOBI_EINVAL
+    h = ctypes.c_void_p()
+    d = (ctypes.c_int64 * 2)(8, 8)
+    assert raw.jacobi_create(ctypes.byref(h), 2, d, None, 0) == 1 and not h.value
+    p = J.jacobi_create((8, 8), (2, 2))
+    # argument validation happens before any HIP call
+    for call in (lambda: J.jacobi_sweep(p, 0, 256, 1), lambda: J.jacobi_sweep(p, 256, 256, 1),
+                 lambda: J.jacobi_sweep(p, 256, 512, -1), lambda: J.halo_exchange(p, 0),
+                 lambda: J.residual_norm(p, 0, 256), lambda: J.residual_norm(p, 256, 0),
+                 lambda: J.jacobi_scatter(p, 0, 256), lambda: J.jacobi_gather(p, 256, 0),
+                 lambda: J.jacobi_set_option(p, "no_such_option", 1),
+                 lambda: J.jacobi_set_option(p, "fused", 2),
+                 lambda: J.jacobi_set_option(p, "rows_per_strip", 5000),
+                 lambda: J.jacobi_get_option(p, "bogus")):
+        with pytest.raises(J.JacobiError) as e:
+            call()
+        assert e.value.code == 1
+    assert J.jacobi_sweep(p, 256, 512, 0) == 256          # zero iterations: no-op, result in `in`
+    J.jacobi_set_option(p, "fused", 0)
+    assert J.jacobi_get_option(p, "fused") == 0
+    assert J.jacobi_grid_bytes(None) == 0
+    J.jacobi_destroy(p)
+    J.jacobi_destroy(None)

@@ -1,0 +1,215 @@
+"""GPU parity: the HIP library (called through its C ABI) against the CPU oracle,
+element by element on the same seeded inputs.  fp64 grids must be bit-identical
+(both sides evaluate 0.25*((W+E)+(S+N)) / C6*(((x-+x+)+(y-+y+))+(z-+z+)) with FP
+contraction off); fp32 grids within 1e-5*max|u|; residual norms within 1e-12
+relative (fp64 grids) / 1e-5 (fp32 grids) because the summation order differs."""
+import numpy as np
+import pytest
+
+import jacobi_inputs as gen
+from parity_util import interior, random_padded, read_tile_cell
+
+pytestmark = pytest.mark.gpu
+
+RES_RTOL = {np.dtype(np.float64): 1e-12, np.dtype(np.float32): 1e-5}
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2210_01238_amd import harness
+    return harness
+
+
+def run_case(H, oracle, a, tiles, iters, res_every=0, **opts):
+    r = H.JacobiRun([n - 2 for n in a.shape], tiles, a.dtype, **opts)
+    try:
+        r.load(a)
+        res = r.run(iters, res_every)
+        out = r.fetch()
+    finally:
+        r.close()
+    ref, ref_res = oracle.run(a, iters, res_every)
+    return out, res, ref, ref_res
+
+
+def check(out, res, ref, ref_res):
+    dt = out.dtype
+    if dt == np.float64:
+        assert np.array_equal(out, ref), f"max diff {np.max(np.abs(out - ref))}"
+    else:
+        assert np.max(np.abs(out.astype(np.float64) - ref)) <= 1e-5 * np.max(np.abs(ref))
+    assert len(res) == len(ref_res)
+    for g, o in zip(res, ref_res):
+        assert abs(g - o) <= RES_RTOL[np.dtype(dt)] * max(o, 1e-300), (g, o)
+
+
+CASES_2D = [
+    # (interior dims, tiles, iters, residual_every)
+    ((256, 256), (1, 1), 20, 5),        # one tile, two column segments
+    ((96, 200), (3, 2), 13, 4),         # tw = 100: ragged row (pitch 112), several tiles
+    ((64, 1030), (2, 2), 9, 3),         # tw = 515: 5 column segments, ragged last one
+    ((48, 48), (48, 48), 7, 7),         # 1x1 tiles: every cell is a tile edge
+    ((40, 36), (1, 36), 6, 2),          # tiles one column wide
+    ((36, 40), (36, 1), 6, 2),          # tiles one row high
+    ((300, 70), (1, 1), 11, 11),        # tall single tile, odd sizes
+    ((512, 512), (4, 4), 50, 10),       # 4x4 tiles of 128^2
+    ((1024, 1024), (8, 8), 25, 5),      # 64 tiles of 128^2 (fine-grained tasking shape)
+    ((2, 2), (1, 1), 5, 1),
+    ((1, 1), (1, 1), 3, 1),
+]
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+@pytest.mark.parametrize("dims,tiles,iters,every", CASES_2D)
+def test_2d_fp64_bit_exact(H, oracle_mod, dims, tiles, iters, every, fused):
+    a = random_padded(dims, seed=sum(dims) + iters)
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, fused=fused))
+
+
+CASES_3D = [
+    ((24, 20, 36), (2, 2, 3), 9, 3),
+    ((16, 16, 16), (1, 1, 1), 8, 4),
+    ((6, 10, 130), (3, 5, 1), 5, 5),    # tw = 130: two column segments, ragged
+    ((8, 8, 8), (8, 8, 8), 4, 2),       # 1x1x1 tiles
+    ((128, 128, 128), (4, 4, 4), 12, 4),  # 64 tiles of 32^3
+    ((70, 33, 20), (1, 1, 1), 6, 3),
+    ((1, 1, 1), (1, 1, 1), 2, 1),
+]
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+@pytest.mark.parametrize("dims,tiles,iters,every", CASES_3D)
+def test_3d_fp64_bit_exact(H, oracle_mod, dims, tiles, iters, every, fused):
+    a = random_padded(dims, seed=sum(dims) + iters)
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, fused=fused))
+
+
+@pytest.mark.parametrize("dims,tiles,iters,every", [
+    ((96, 200), (3, 2), 13, 4), ((512, 512), (4, 4), 50, 10), ((24, 20, 36), (2, 2, 3), 9, 3),
+    ((64, 64, 64), (2, 2, 2), 10, 5), ((40, 1000), (2, 1), 8, 4),
+])
+@pytest.mark.parametrize("fused", [0, 1])
+def test_fp32_within_tolerance(H, oracle_mod, dims, tiles, iters, every, fused):
+    a = random_padded(dims, dtype=np.float32, seed=7)
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, fused=fused))
+
+
+@pytest.mark.parametrize("opts", [
+    dict(rows_per_strip=1), dict(rows_per_strip=3), dict(rows_per_strip=7, fused=0),
+    dict(rows_per_strip=4096), dict(nontemporal=1), dict(nontemporal=1, fused=0, rows_per_strip=5),
+])
+def test_options_do_not_change_results(H, oracle_mod, opts):
+    a = random_padded((150, 260), seed=3)
+    check(*run_case(H, oracle_mod, a, (3, 2), 10, 5, **opts))
+    b = random_padded((20, 18, 40), seed=4)
+    check(*run_case(H, oracle_mod, b, (2, 3, 2), 6, 3, **opts))
+
+
+def test_c1_workload_and_stored_values(H, oracle_mod):
+    from test_oracle_pins import read_golden_c1
+    w = gen.WORKLOADS["C1"]
+    a = gen.generate(w)
+    out, res, ref, ref_res = run_case(H, oracle_mod, a, w.tiles, w.iters, w.residual_every)
+    check(out, res, ref, ref_res)
+    gres, pts = read_golden_c1()
+    assert abs(res[0] - gres) <= 1e-12 * gres
+    for (i, j), v in pts.items():
+        assert out[i, j] == v
+    assert np.all(out[101:-1, 1:-1] == 0.0) and np.array_equal(out, out[:, ::-1])
+
+
+def test_harmonic_lattice_fixed_point_on_gpu(H, oracle_mod):
+    a = gen.lattice_field((130, 258), "i2-j2")
+    out, res, ref, _ = run_case(H, oracle_mod, a, (4, 2), 6, 3)
+    assert np.array_equal(out, a) and res == [0.0, 0.0]
+
+
+def test_halo_exchange_fills_halos_and_is_idempotent(H):
+    import torch
+    dims, tiles = (24, 40), (3, 4)
+    a = random_padded(dims, seed=11)
+    r = H.JacobiRun(dims, tiles)
+    try:
+        r.load(a)
+        lay = H.B.jacobi_get_layout(r.plan)
+        th, tw, Tx = lay.tile[1], lay.tile[2], lay.tiles[2]
+        # poison every inter-tile halo cell, then exchange
+        raw = r.cur.view(torch.float64)
+        host = raw.cpu().numpy().copy()
+        for t in range(lay.ntiles):
+            ty, tx = divmod(t, Tx)
+            base = t * lay.tile_stride
+            if ty > 0:
+                host[base: base + tw] = np.nan
+            if ty < tiles[0] - 1:
+                host[base + (th + 1) * lay.pitch: base + (th + 1) * lay.pitch + tw] = np.nan
+            if tx > 0:
+                host[base + lay.xhalo_offset + 1: base + lay.xhalo_offset + 1 + th] = np.nan
+            if tx < Tx - 1:
+                o = base + lay.xhalo_offset + lay.xhalo_pitch
+                host[o + 1: o + 1 + th] = np.nan
+        raw.copy_(torch.from_numpy(host))
+        r.exchange()
+        once = raw.cpu().numpy().copy()
+        r.exchange()
+        twice = raw.cpu().numpy().copy()
+        for t in range(lay.ntiles):
+            ty, tx = divmod(t, Tx)
+            for i in range(1, th + 1):
+                for c in (-1, tw):
+                    assert read_tile_cell(once, lay, t, 0, i, c) == a[ty * th + i, tx * tw + c + 1]
+            for c in range(tw):
+                for i in (0, th + 1):
+                    assert read_tile_cell(once, lay, t, 0, i, c) == a[ty * th + i, tx * tw + c + 1]
+        # idempotent on every cell that holds data (padding may hold anything, but is not rewritten)
+        assert np.array_equal(once, twice, equal_nan=True)
+        assert np.array_equal(r.fetch(), a)
+    finally:
+        r.close()
+
+
+def test_scatter_gather_roundtrip_3d_f32(H):
+    dims, tiles = (6, 10, 36), (3, 2, 2)
+    a = random_padded(dims, dtype=np.float32, seed=5)
+    r = H.JacobiRun(dims, tiles, np.float32)
+    try:
+        r.load(a)
+        assert np.array_equal(r.fetch(), a)
+    finally:
+        r.close()
+
+
+def test_residual_is_run_to_run_reproducible_and_device_variant_agrees(H, oracle_mod):
+    import torch
+    a = random_padded((512, 384), seed=21)
+    r = H.JacobiRun((512, 384), (4, 3))
+    try:
+        r.load(a)
+        r.sweep(3)
+        v1 = r.residual()
+        v2 = r.residual()
+        out = torch.zeros(1, dtype=torch.float64, device="cuda")
+        r.residual_async(out)
+        torch.cuda.synchronize()
+        assert v1 == v2 == float(out.item())
+        u, _ = oracle_mod.run(a, 3)
+        assert abs(v1 - oracle_mod.residual(u)) <= 1e-12 * v1
+    finally:
+        r.close()
+
+
+def test_split_calls_equal_one_call(H, oracle_mod):
+    """Every jacobi_sweep call must refresh stale halos itself."""
+    a = random_padded((96, 96), seed=8)
+    ref, _ = oracle_mod.run(a, 7)
+    for fused in (0, 1):
+        r = H.JacobiRun((96, 96), (3, 3), fused=fused)
+        try:
+            r.load(a)
+            for n in (1, 2, 1, 3):
+                r.sweep(n)
+            assert np.array_equal(r.fetch(), ref)
+        finally:
+            r.close()
