@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Throughput of the block-decomposed Jacobi hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+
+Workload (default C3): 2-D 5-point Jacobi, 16384 x 16384 fp64 interior, 8 x 8 tiles of
+2048 x 2048 with halo exchange every iteration, boundary x^2 - y^2 on the unit square,
+interior uniform in [-1, 1) (seeded, synthetic), residual norm every 10 iterations.
+
+One STEP = one residual period of the workload = `residual_every` Jacobi iterations
+(each: halo pack/unpack between all neighbouring tiles + 5-point update of every tile)
+followed by one residual-norm reduction.  The default K = 20 steps is the workload's
+whole schedule (200 iterations, 20 residuals).  Inputs are resident in device memory
+before the clock starts; nothing is copied to the host inside the timed region.
+
+Prints ONE JSON line.  `value` = interior points x iterations / wall time of the K timed
+steps (GLUP/s: 1e9 lattice-point updates per second), everything included.
+`roofline` describes the dominant kernel (the update sweep): algorithmic bytes per launch
+divided by its mean launch duration, measured with HIP events around every update launch
+in a second pass over the same K steps, against the 8 TB/s HBM peak.
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload on this
+machine's host cores (a baseline for context, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published peak
+
+
+def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
+    """Bytes one update launch must move: every tile reads its interior plus the face
+    halo cells once and writes its interior once (16 B per point in fp64 plus the halo
+    ring); with the fused halo push it also writes one copy of every inter-tile edge cell."""
+    import math
+    tile = [d // t for d, t in zip(w.dims, w.tiles)]
+    ntiles = math.prod(w.tiles)
+    interior = math.prod(tile)
+    faces = sum(2 * interior // s for s in tile)          # halo cells read per tile
+    total = ntiles * esize * (2 * interior + faces)
+    if fused:
+        pairs_cells = 0
+        for d in range(len(tile)):
+            pairs = (w.tiles[d] - 1) * (ntiles // w.tiles[d])
+            pairs_cells += 2 * pairs * (interior // tile[d])
+        total += esize * pairs_cells
+    return total
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], help="key=value passed to jacobi_set_option")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (tiles of one device stand in for a node's share "
+              "of blocks); --gpus N with N > 1 is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import jacobi_inputs as gen
+    from paper_2210_01238_amd import harness
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU path", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+
+    w = gen.WORKLOADS[args.workload]
+    every = w.residual_every
+    K, W = args.steps, args.warmup
+
+    t0 = time.perf_counter()
+    a = gen.generate(w)
+    t_gen = time.perf_counter() - t0
+    run = harness.JacobiRun(w.dims, w.tiles)
+    for kv in args.option:
+        k, v = kv.split("=")
+        run.set_option(k, int(v))
+    fused = bool(harness.B.jacobi_get_option(run.plan, "fused"))
+    run.load(a)
+    res_dev = torch.zeros(max(K, W, 1), dtype=torch.float64, device="cuda")
+
+    def steps(n: int) -> None:
+        for i in range(n):
+            run.sweep(every)
+            run.residual_async(res_dev[i:i + 1])
+
+    # warm-up (untimed), then K timed steps from the same initial field
+    steps(W)
+    run.load(a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    steps(K)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    residuals = res_dev[:K].cpu().tolist()
+
+    lups = float(w.points) * every * K
+    glups = lups / elapsed / 1e9
+
+    # second pass over the same K steps with a HIP event pair around every update launch
+    run.load(a)
+    run.set_option("profile", 1)
+    torch.cuda.synchronize()
+    steps(K)
+    torch.cuda.synchronize()
+    upd_ms, upd_n = harness.B.jacobi_profile_read(run.plan)
+    run.set_option("profile", 0)
+    esize = 8
+    bytes_per_launch = algorithmic_bytes_per_update(w, esize, fused)
+    avg_ms = upd_ms / max(upd_n, 1)
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if upd_n else 0.0
+
+    out = {
+        "metric": "Jacobi GLUP/s (lattice updates/sec) + % of HBM roofline, 1 MI355X",
+        "value": round(glups, 3),
+        "unit": "GLUP/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(elapsed / K * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {len(w.dims)}-D Jacobi {'x'.join(map(str, w.dims))} fp64, "
+                        f"{'x'.join(map(str, w.tiles))} tiles, halo exchange every iteration, "
+                        f"residual every {every} iterations",
+            "iterations_per_step": every,
+            "iterations_timed": every * K,
+            "residual_calls_timed": K,
+            "fused_halo_push": fused,
+            "options": args.option,
+            "last_residual": residuals[-1] if residuals else None,
+            "input_generation_s": round(t_gen, 2),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "sweep2d_kernel<double, update>" if len(w.dims) == 2 else "sweep3d_kernel<double, update>",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "bytes_per_launch": bytes_per_launch,
+            "avg_launch_ms": round(avg_ms, 5),
+            "launches_timed": upd_n,
+            "whole_step_frac": round((16.0 * glups) / HBM_PEAK_GBS, 4),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        n_steps_cpu = min(K, 16) if K > 0 else 1
+        t0 = time.perf_counter()
+        oracle.run(a, every * n_steps_cpu, every)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(float(w.points) * every * n_steps_cpu / t_cpu / 1e9, 4),
+            "unit": "GLUP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"first {n_steps_cpu} steps ({every * n_steps_cpu} iterations + {n_steps_cpu} residual norms) "
+                      f"of the same {w.name} field, full grid; update loops on all threads, residual sums serial; "
+                      f"{t_cpu:.1f} s",
+        }
+    run.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
