@@ -35,6 +35,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
 
+# HBM-side bytes per update launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+# counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md.
+# Valid only for the library's default options on that workload; otherwise reported as null.
+MEASURED_TRAFFIC_BYTES = {"C3": 4575656121}
+
 
 def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
     """Bytes one update launch must move: every tile reads its interior plus the face
@@ -126,6 +131,18 @@ def main() -> int:
     avg_ms = upd_ms / max(upd_n, 1)
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if upd_n else 0.0
 
+    # practical ceiling: a plain streaming copy of one grid into the other (same bytes in and out)
+    src_g, dst_g = run.cur, run.other()
+    st = int(torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        harness.B.jacobi_stream_copy(dst_g.data_ptr(), src_g.data_ptr(), run.nbytes, st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        harness.B.jacobi_stream_copy(dst_g.data_ptr(), src_g.data_ptr(), run.nbytes, st)
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * run.nbytes * 20 / (time.perf_counter() - t0) / 1e9
+
     out = {
         "metric": "Jacobi GLUP/s (lattice updates/sec) + % of HBM roofline, 1 MI355X",
         "value": round(glups, 3),
@@ -158,11 +175,12 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if not args.option else None,
             "bytes_per_launch": bytes_per_launch,
             "avg_launch_ms": round(avg_ms, 5),
             "launches_timed": upd_n,
             "whole_step_frac": round((16.0 * glups) / HBM_PEAK_GBS, 4),
+            "stream_copy_gbs": round(copy_gbs, 1),
         },
     }
 

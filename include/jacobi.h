@@ -90,8 +90,8 @@ typedef struct jacobi_layout {
 } jacobi_layout;
 
 /*
- * jacobi_create: describe a block-decomposed domain (paper Sec. VI-C: "a 3D domain
- * which is decomposed into cuboids"; 2-D is the same with one dimension fewer).
+ * jacobi_create: describe a block-decomposed domain (paper Sec. VI-C: the proxy's 3-D
+ * domain is cut into cuboids; 2-D is the same with one dimension fewer).
  *   plan   out, host pointer; receives a new plan the caller frees with jacobi_destroy.
  *   ndim   2 or 3.
  *   dims   host array[ndim], interior points per dim, slowest->fastest, each > 0.
@@ -127,7 +127,7 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
 
 /*
  * jacobi_sweep: `iters` Jacobi iterations (paper Sec. VI-C: per iteration, exchange
- * halos, unpack, and "once all halos have been received" update the block).
+ * halos, unpack, and update a block only after all of its halos have arrived).
  *   in, out  two distinct device grids.  `in` holds the current field: tile interiors
  *            and Dirichlet boundary halos must be valid; inter-tile halos need not be
  *            (they are exchanged before the first update).  `out` may hold anything.
@@ -175,9 +175,15 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
  *                    through; 0 = choose from the shape (default 0)
- *   "nontemporal"    0 | 1   streaming loads/stores bypassing cache allocation (default 0)
+ *   "nontemporal"    0..3    bit 0: streaming (non-temporal) loads of the marching rows,
+ *                    bit 1: streaming stores of the results (default 2)
+ *   "unroll"         0 | 1 | 2 | 4 | 8  rows (planes) whose loads a wavefront issues back to
+ *                    back before computing; 0 = the whole strip, up to 8 (default 0)
+ *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
+ *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
  *                    made by jacobi_sweep (read with jacobi_profile_read)
+ * None of the options changes any result bit.
  */
 int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value);
 int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);
@@ -189,6 +195,15 @@ int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);
  * ones are not timed (and not counted).  Errors: EINVAL, EHIP.
  */
 int jacobi_profile_read(jacobi_plan *plan, double *update_ms_total, int64_t *update_launches);
+
+/*
+ * Measurement aid, not part of the method: a plain streaming device-to-device copy kernel
+ * (16 bytes per lane).  Its throughput is the practical ceiling the update kernel is
+ * compared with, and its known size calibrates hardware HBM byte counters.
+ * dst/src: device pointers, 16-byte aligned, not overlapping; bytes: multiple of 16.
+ * Asynchronous on `stream`.  Errors: EINVAL, EHIP.
+ */
+int jacobi_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* Text of the calling thread's most recent error ("" if none).  Valid until the next
  * failing call on this thread. */

@@ -22,7 +22,7 @@ EXPORTS = (
     "jacobi_create", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
     "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "halo_exchange", "residual_norm",
     "residual_norm_host", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
-    "jacobi_last_error",
+    "jacobi_last_error", "jacobi_stream_copy",
 )
 
 
@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
     lib.jacobi_set_option.argtypes = [vp, ctypes.c_char_p, i64]
     lib.jacobi_get_option.argtypes = [vp, ctypes.c_char_p, P(i64)]
     lib.jacobi_profile_read.argtypes = [vp, P(ctypes.c_double), P(i64)]
+    lib.jacobi_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.jacobi_last_error.argtypes = []
     lib.jacobi_last_error.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -153,3 +154,7 @@ def jacobi_profile_read(plan: int) -> Tuple[float, int]:
     ms, n = ctypes.c_double(), ctypes.c_int64()
     _check(lib.jacobi_profile_read(plan, ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value
+
+
+def jacobi_stream_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib.jacobi_stream_copy(dst, src, nbytes, stream))

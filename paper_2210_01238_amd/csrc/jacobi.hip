@@ -48,7 +48,7 @@ struct jacobi_plan {
     Geo geo;
     size_t esize;
     // options
-    int64_t fused = 1, rows_per_strip = 0, nontemporal = 0, profile = 0;
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8;
     // residual scratch (device), sized for the residual launch
     double *partial = nullptr;
     int64_t partial_cap = 0;
@@ -70,17 +70,18 @@ StripParams make_strips(const jacobi_plan *p)
     const int64_t lanes_of_work = (int64_t)g.ntiles * sp.nseg * (g.ndim == 3 ? g.th : 1);
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
-        // aim for >= 8192 strips (32 wavefronts on each of 256 CUs) while keeping the border
-        // re-read (2 rows per strip) small: between 8 and 64 rows per strip
-        const int64_t want = 8192;
-        int64_t r = (int64_t)extent * lanes_of_work / want;
-        R = (int)(r < 8 ? 8 : r > 64 ? 64 : r);
+        // Short strips whose loads are all issued at once stream best (the chip then walks
+        // through memory as one narrow front); 8 rows keeps the border re-read at 2 rows in 10.
+        // Small problems get shorter strips so that there are enough wavefronts to fill the chip.
+        R = 8;
+        while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < 4096) R /= 2;
     }
     if (R > extent) R = extent;
     sp.R = R;
     sp.nblk = (int)ceil_div(extent, R);
     sp.nstrips = lanes_of_work * sp.nblk;
     sp.fused = (int)p->fused;
+    sp.xcd_chunk = (int)p->xcd_chunk;
     return sp;
 }
 
@@ -91,15 +92,30 @@ int launch_sweep_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStr
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     const dim3 grid((unsigned)nwg), block(jk::WG);
-    constexpr int U = 4;
-    const bool nt = p->nontemporal != 0;
-    if (p->geo.ndim == 2) {
-        if (nt) hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U, true>), grid, block, 0, st, p->geo, sp, src, dst, partial);
-        else    hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U, false>), grid, block, 0, st, p->geo, sp, src, dst, partial);
-    } else {
-        if (nt) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, U, true>), grid, block, 0, st, p->geo, sp, src, dst, partial);
-        else    hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, U, false>), grid, block, 0, st, p->geo, sp, src, dst, partial);
+    const int nt = (int)p->nontemporal;
+    const bool d3 = p->geo.ndim == 3;
+#define JK_LAUNCH(U_, NT_)                                                                                           \
+    do {                                                                                                             \
+        if (d3) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, U_, NT_>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
+        else    hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, NT_>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
+    } while (0)
+#define JK_LAUNCH_NT(U_)                                                                     \
+    switch (nt) {                                                                            \
+    case 1: JK_LAUNCH(U_, 1); break;                                                         \
+    case 2: JK_LAUNCH(U_, 2); break;                                                         \
+    case 3: JK_LAUNCH(U_, 3); break;                                                         \
+    default: JK_LAUNCH(U_, 0); break;                                                        \
     }
+    int unroll = (int)p->unroll;
+    if (unroll <= 0) unroll = sp.R >= 8 ? 8 : sp.R >= 4 ? 4 : sp.R >= 2 ? 2 : 1;   // all of a short strip at once
+    switch (unroll) {
+    case 1: JK_LAUNCH_NT(1); break;
+    case 2: JK_LAUNCH_NT(2); break;
+    case 8: JK_LAUNCH_NT(8); break;
+    default: JK_LAUNCH_NT(4); break;
+    }
+#undef JK_LAUNCH_NT
+#undef JK_LAUNCH
     HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
@@ -202,6 +218,8 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "rows_per_strip")) return &p->rows_per_strip;
     if (!strcmp(key, "nontemporal")) return &p->nontemporal;
     if (!strcmp(key, "profile")) return &p->profile;
+    if (!strcmp(key, "unroll")) return &p->unroll;
+    if (!strcmp(key, "xcd_chunk")) return &p->xcd_chunk;
     return nullptr;
 }
 
@@ -384,8 +402,10 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 8 : slot == &plan->nontemporal ? 3 : slot == &plan->xcd_chunk ? (1 << 20) : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
+    if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+        return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4 or 8");
     *slot = value;
     return JACOBI_OK;
 }
@@ -396,6 +416,20 @@ int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value)
     int64_t *slot = option_slot(const_cast<jacobi_plan *>(plan), key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
     *value = *slot;
+    return JACOBI_OK;
+}
+
+int jacobi_stream_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src) return fail(JACOBI_EINVAL, "NULL argument");
+    if (bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return fail(JACOBI_EINVAL, "bytes and pointers must be multiples of 16");
+    if (bytes == 0) return JACOBI_OK;
+    const long long n16 = (long long)(bytes / 16);
+    const long long nblk = (n16 + jk::WG - 1) / jk::WG;
+    if (nblk > 0x7fffffffLL) return fail(JACOBI_EINVAL, "copy too large for one launch");
+    hipLaunchKernelGGL(jk::stream_copy_kernel, dim3((unsigned)nblk), dim3(jk::WG), 0, (hipStream_t)stream,
+                       (const uint4 *)src, (uint4 *)dst, n16);
+    HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
 

@@ -13,9 +13,9 @@
 // crossbar (ds_bpermute via __shfl) and, at the ends of the wavefront, from one extra
 // 8-byte load (the neighbouring strip's cell or the tile's dense x-halo array).
 //
-// Workgroups (4 wavefronts = 4 consecutive strips) are renumbered so that each of the
-// 8 XCDs works through one contiguous eighth of the strip list: neighbouring strips
-// re-read each other's border rows, and this keeps those re-reads inside one XCD's L2.
+// Workgroups (4 wavefronts = 4 consecutive strips) walk the strip list, which is in memory
+// order, so the chip as a whole streams through the grid front to back; see
+// xcd_logical_wg() for how runs of workgroups are pinned to one XCD's L2.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -85,14 +85,22 @@ template <bool NT, typename V> __device__ __forceinline__ void stv(V *p, V v)
     else *p = v;
 }
 
-// Workgroup renumbering: hardware hands consecutive workgroup ids to the XCDs round-robin;
-// give XCD x the contiguous range of logical ids it would get if the list were cut in 8.
-__device__ __forceinline__ long long xcd_logical_wg()
+// Workgroup renumbering.  The hardware hands consecutive workgroup ids to the 8 XCDs
+// round-robin, and each XCD has its own L2.  Strips that are neighbours in a tile re-read each
+// other's border rows, which only hits in L2 if both run on the same XCD; on the other hand HBM
+// is fastest when the whole chip walks through memory as one compact front.  Compromise: cut
+// the strip list into groups of 8*G workgroups; inside a group XCD x takes the G consecutive
+// logical ids [x*G, (x+1)*G).  G = 1 is the identity (one front, no L2 sharing); a large G gives
+// every XCD a long private run (8 fronts).  The tail that does not fill a group is left as is.
+__device__ __forceinline__ long long xcd_logical_wg(int G)
 {
-    const long long n = gridDim.x, b = blockIdx.x;
-    const long long x = b % NUM_XCD, q = n / NUM_XCD, r = n % NUM_XCD;
-    const long long start = x * q + (x < r ? x : r);
-    return start + b / NUM_XCD;
+    const long long b = blockIdx.x;
+    if (G <= 1) return b;
+    const long long span = (long long)NUM_XCD * G;
+    const long long full = ((long long)gridDim.x / span) * span;
+    if (b >= full) return b;
+    const long long grp = b / span, within = b - grp * span;
+    return grp * span + (within % NUM_XCD) * G + within / NUM_XCD;
 }
 
 // Sum over the 64 lanes in a fixed butterfly order (same bits on every run).
@@ -127,12 +135,13 @@ struct StripParams {
     int nblk;            // strips along the marching direction = ceil(extent / R)
     long long nstrips;   // total
     int fused;           // update mode: push edge cells into neighbour halos of dst
+    int xcd_chunk;       // G of xcd_logical_wg(): consecutive workgroups one XCD takes
 };
 
 // ------------------------------------------------------------------------------------
 // 2-D: 5-point update (or residual) of every tile.  new = 0.25*((W+E)+(S+N)).
 // ------------------------------------------------------------------------------------
-template <typename T, int MODE, int U, bool NT>
+template <typename T, int MODE, int U, int NT>
 __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
                                                      double *__restrict__ partial)
@@ -142,7 +151,7 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
     __shared__ double red[WAVES_PER_WG];
 
     const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
-    const long long lwg = xcd_logical_wg();
+    const long long lwg = xcd_logical_wg(sp.xcd_chunk);
     const long long s = lwg * WAVES_PER_WG + wave;
     double acc = 0.0;
 
@@ -174,8 +183,8 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 
         V prev = V(0), cur = V(0);
         if (active) {
-            prev = ldv<NT>((const V *)(tsrc + main_off(g, 0, r0 - 1, col0)));
-            cur = ldv<NT>((const V *)(tsrc + main_off(g, 0, r0, col0)));
+            prev = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, r0 - 1, col0)));
+            cur = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, r0, col0)));
         }
         for (int r = r0; r <= r1; r += U) {
             V nx[U];
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int rn = min(r + u + 1, g.th + 1);   // clamped: stays inside the tile
-                nx[u] = active ? ldv<NT>((const V *)(tsrc + main_off(g, 0, rn, col0))) : V(0);
+                nx[u] = active ? ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, rn, col0))) : V(0);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -219,7 +228,7 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
                     }
                     if constexpr (MODE == MODE_UPDATE) {
                         if (active) {
-                            stv<NT>((V *)(tdst + main_off(g, 0, rr, col0)), out);
+                            stv<(NT & 2) != 0>((V *)(tdst + main_off(g, 0, rr, col0)), out);
                             if (push) {
                                 if (rr == 1 && dst_ym) *(V *)(dst_ym + main_off(g, 0, g.th + 1, col0)) = out;
                                 if (rr == g.th && dst_yp) *(V *)(dst_yp + main_off(g, 0, 0, col0)) = out;
@@ -246,7 +255,7 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 // planes k-1, k, k+1 of its row in registers; rows i-1 and i+1 of plane k are loaded
 // (they are the "current" rows of the neighbouring wavefronts, so they come from cache).
 // ------------------------------------------------------------------------------------
-template <typename T, int MODE, int U, bool NT>
+template <typename T, int MODE, int U, int NT>
 __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
                                                      double *__restrict__ partial)
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
     __shared__ double red[WAVES_PER_WG];
 
     const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
-    const long long lwg = xcd_logical_wg();
+    const long long lwg = xcd_logical_wg(sp.xcd_chunk);
     const long long s = lwg * WAVES_PER_WG + wave;
     double acc = 0.0;
 
@@ -293,8 +302,8 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
 
         V below = V(0), cur = V(0);
         if (active) {
-            below = ldv<NT>((const V *)(tsrc + main_off(g, k0 - 1, i, col0)));
-            cur = ldv<NT>((const V *)(tsrc + main_off(g, k0, i, col0)));
+            below = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0 - 1, i, col0)));
+            cur = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0, i, col0)));
         }
         for (int k = k0; k <= k1; k += U) {
             V up[U], ym[U], yp[U];
@@ -305,7 +314,7 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                 const int kc = min(k + u, g.td + 1);
                 up[u] = ym[u] = yp[u] = V(0);
                 if (active) {
-                    up[u] = ldv<NT>((const V *)(tsrc + main_off(g, kn, i, col0)));
+                    up[u] = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, kn, i, col0)));
                     ym[u] = *(const V *)(tsrc + main_off(g, kc, i - 1, col0));
                     yp[u] = *(const V *)(tsrc + main_off(g, kc, i + 1, col0));
                 }
@@ -341,7 +350,7 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                     }
                     if constexpr (MODE == MODE_UPDATE) {
                         if (active) {
-                            stv<NT>((V *)(tdst + main_off(g, kk, i, col0)), out);
+                            stv<(NT & 2) != 0>((V *)(tdst + main_off(g, kk, i, col0)), out);
                             if (push) {
                                 if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
                                 if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
@@ -475,6 +484,16 @@ __global__ __launch_bounds__(WG) void scatter_gather_kernel(Geo g, const T *__re
             if (in_k && in_i && in_c) to[goff] = from[toff];
         }
     }
+}
+
+// Plain streaming copy, 16 bytes per lane, one element per thread, workgroups in memory
+// order (the fastest simple copy on this chip): the practical bandwidth ceiling the update
+// kernel is compared with, and the known-size dispatch used to calibrate HBM counters.
+__global__ __launch_bounds__(WG) void stream_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                         long long n16)
+{
+    const long long i = (long long)blockIdx.x * WG + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
 }
 
 }  // namespace jk

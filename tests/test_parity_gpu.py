@@ -97,8 +97,9 @@ def test_fp32_within_tolerance(H, oracle_mod, dims, tiles, iters, every, fused):
 
 
 @pytest.mark.parametrize("opts", [
-    dict(rows_per_strip=1), dict(rows_per_strip=3), dict(rows_per_strip=7, fused=0),
-    dict(rows_per_strip=4096), dict(nontemporal=1), dict(nontemporal=1, fused=0, rows_per_strip=5),
+    dict(rows_per_strip=1), dict(rows_per_strip=3, unroll=2), dict(rows_per_strip=7, fused=0, unroll=4),
+    dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=3, fused=0, rows_per_strip=5),
+    dict(xcd_chunk=1), dict(xcd_chunk=3, unroll=1), dict(xcd_chunk=1000),
 ])
 def test_options_do_not_change_results(H, oracle_mod, opts):
     a = random_padded((150, 260), seed=3)
