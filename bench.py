@@ -67,6 +67,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-residual", action="store_true",
+                    help="compute every residual with the stand-alone reduction pass")
     ap.add_argument("--option", action="append", default=[], help="key=value passed to jacobi_set_option")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -97,13 +99,21 @@ def main() -> int:
         k, v = kv.split("=")
         run.set_option(k, int(v))
     fused = bool(harness.B.jacobi_get_option(run.plan, "fused"))
+    fuse_residual = not args.separate_residual
     run.load(a)
     res_dev = torch.zeros(max(K, W, 1), dtype=torch.float64, device="cuda")
 
     def steps(n: int) -> None:
+        # Step i = `every` iterations, then the residual norm of the field they produced.  The
+        # norm of step i's result is computed inside the first update of step i+1 (same pass over
+        # memory); only the last step needs the stand-alone reduction.  n residuals in total.
         for i in range(n):
-            run.sweep(every)
-            run.residual_async(res_dev[i:i + 1])
+            if i == 0 or not fuse_residual:
+                run.sweep(every)
+            else:
+                run.sweep_residual(every, res_dev[i - 1:i])
+            if i == n - 1 or not fuse_residual:
+                run.residual_async(res_dev[i:i + 1])
 
     # warm-up (untimed), then K timed steps from the same initial field
     steps(W)
@@ -164,6 +174,7 @@ def main() -> int:
             "iterations_timed": every * K,
             "residual_calls_timed": K,
             "fused_halo_push": fused,
+            "residual_fused_into_update": fuse_residual,
             "options": args.option,
             "last_residual": residuals[-1] if residuals else None,
             "input_generation_s": round(t_gen, 2),

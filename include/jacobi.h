@@ -148,6 +148,20 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
 int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final);
 
 /*
+ * jacobi_sweep_residual: jacobi_sweep that also delivers residual_norm(in) - the norm of the
+ * field BEFORE the first of the `iters` iterations - to *residual_in_dev (a DEVICE double).
+ * The terms sum_nbrs u - 2d*u of the source grid are exactly what the first update already
+ * holds in registers, so the norm costs no extra pass over memory (a stand-alone
+ * residual_norm reads the whole grid once more).  A caller that wants the residual after
+ * every k-th iteration gets it from the NEXT call's first update.  Same value as
+ * residual_norm(in) up to summation order; same fixed-order reduction; uses the plan's
+ * device scratch (allocated, with a device synchronisation, on first use).
+ * iters >= 1.  Errors: EINVAL, ENOMEM, EHIP.
+ */
+int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, void *stream,
+                          void **final, double *residual_in_dev);
+
+/*
  * halo_exchange: for every pair of face-adjacent tiles, copy each tile's edge cells
  * into the other's halo cells, in place in `grid` (paper Sec. VI-C: pack, transfer,
  * unpack - on one device the three collapse into one gather-scatter copy).
@@ -178,7 +192,10 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "nontemporal"    0..3    bit 0: streaming (non-temporal) loads of the marching rows,
  *                    bit 1: streaming stores of the results (default 2)
  *   "unroll"         0 | 1 | 2 | 4 | 8  rows (planes) whose loads a wavefront issues back to
- *                    back before computing; 0 = the whole strip, up to 8 (default 0)
+ *                    back before computing; 0 = choose: 2-D the whole strip, up to 8; 3-D 2
+ *                    (3-D accepts at most 4) (default 0)
+ *   "rows_per_wave"  0 | 1 | 2 | 4  3-D: rows of a plane one wavefront keeps in registers
+ *                    (0 = 4 where the tile allows; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch

@@ -48,7 +48,7 @@ struct jacobi_plan {
     Geo geo;
     size_t esize;
     // options
-    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8;
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0;
     // residual scratch (device), sized for the residual launch
     double *partial = nullptr;
     int64_t partial_cap = 0;
@@ -59,21 +59,39 @@ struct jacobi_plan {
 
 namespace {
 
-// How the update / residual kernels cut the tiles into strips (see jacobi_kernels.h).
-StripParams make_strips(const jacobi_plan *p)
+// How the update / residual kernels cut the tiles into strips (see jacobi_kernels.h), and
+// which compiled variant runs them.
+struct SweepConfig {
+    StripParams sp;
+    int rows_per_wave;   // 3-D only: rows one wavefront keeps in registers (1, 2 or 4)
+    int unroll;          // rows (2-D) / planes (3-D) whose loads are issued back to back
+};
+
+SweepConfig make_config(const jacobi_plan *p, int mode)
 {
     const Geo &g = p->geo;
     const int nv = 16 / (int)p->esize;
-    StripParams sp;
+    const bool d3 = g.ndim == 3;
+    SweepConfig c;
+    StripParams &sp = c.sp;
     sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * nv);
-    const int extent = g.ndim == 3 ? g.td : g.th;       // marching direction
-    const int64_t lanes_of_work = (int64_t)g.ntiles * sp.nseg * (g.ndim == 3 ? g.th : 1);
+    c.rows_per_wave = 1;
+    if (d3) {
+        int rw = (int)p->rows_per_wave;
+        if (rw <= 0) rw = g.th >= 4 ? 4 : g.th >= 2 ? 2 : 1;
+        c.rows_per_wave = rw;
+    }
+    const int extent = d3 ? g.td : g.th;       // marching direction
+    const int64_t lanes_of_work =
+        (int64_t)g.ntiles * sp.nseg * (d3 ? ceil_div(g.th, c.rows_per_wave) : 1);
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
         // Short strips whose loads are all issued at once stream best (the chip then walks
         // through memory as one narrow front); 8 rows keeps the border re-read at 2 rows in 10.
         // Small problems get shorter strips so that there are enough wavefronts to fill the chip.
-        R = 8;
+        // The read-only residual pass has no writes to keep apart from its reads and prefers
+        // taller strips (fewer border re-reads): 16 rows, all in flight.
+        R = d3 ? 16 : mode == jk::MODE_RESIDUAL ? 16 : 8;
         while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < 4096) R /= 2;
     }
     if (R > extent) R = extent;
@@ -82,40 +100,66 @@ StripParams make_strips(const jacobi_plan *p)
     sp.nstrips = lanes_of_work * sp.nblk;
     sp.fused = (int)p->fused;
     sp.xcd_chunk = (int)p->xcd_chunk;
-    return sp;
+    int u = (int)p->unroll;
+    if (d3) {
+        if (u <= 0) u = 2;
+        if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
+    } else if (u <= 0) {
+        u = R >= 16 ? 16 : R >= 8 ? 8 : R >= 4 ? 4 : R >= 2 ? 2 : 1;   // all of a short strip at once
+    }
+    c.unroll = u;
+    return c;
 }
 
 template <typename T, int MODE>
 int launch_sweep_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStream_t st)
 {
-    const StripParams sp = make_strips(p);
+    const SweepConfig c = make_config(p, MODE);
+    const StripParams &sp = c.sp;
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     const dim3 grid((unsigned)nwg), block(jk::WG);
     const int nt = (int)p->nontemporal;
-    const bool d3 = p->geo.ndim == 3;
-#define JK_LAUNCH(U_, NT_)                                                                                           \
-    do {                                                                                                             \
-        if (d3) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, U_, NT_>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
-        else    hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, NT_>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
+#define JK_ARGS grid, block, 0, st, p->geo, sp, src, dst, partial
+    if (p->geo.ndim == 2) {
+#define JK_2D(U_)                                                                                  \
+    switch (nt) {                                                                                  \
+    case 1: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 1>), JK_ARGS); break;              \
+    case 2: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 2>), JK_ARGS); break;              \
+    case 3: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 3>), JK_ARGS); break;              \
+    default: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 0>), JK_ARGS); break;             \
+    }
+        switch (c.unroll) {
+        case 1: JK_2D(1); break;
+        case 2: JK_2D(2); break;
+        case 8: JK_2D(8); break;
+        case 16: JK_2D(16); break;
+        default: JK_2D(4); break;
+        }
+#undef JK_2D
+    } else {
+        // 3-D: non-temporal loads are never useful (every row is re-read as a neighbour), so
+        // only the store bit of the option is honoured
+#define JK_3D(RW_, U_)                                                                             \
+    do {                                                                                           \
+        if (nt & 2) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, RW_, U_, 2>), JK_ARGS);        \
+        else        hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, RW_, U_, 0>), JK_ARGS);        \
     } while (0)
-#define JK_LAUNCH_NT(U_)                                                                     \
-    switch (nt) {                                                                            \
-    case 1: JK_LAUNCH(U_, 1); break;                                                         \
-    case 2: JK_LAUNCH(U_, 2); break;                                                         \
-    case 3: JK_LAUNCH(U_, 3); break;                                                         \
-    default: JK_LAUNCH(U_, 0); break;                                                        \
+#define JK_3D_U(RW_)                                                                               \
+    switch (c.unroll) {                                                                            \
+    case 1: JK_3D(RW_, 1); break;                                                                  \
+    case 4: JK_3D(RW_, 4); break;                                                                  \
+    default: JK_3D(RW_, 2); break;                                                                 \
     }
-    int unroll = (int)p->unroll;
-    if (unroll <= 0) unroll = sp.R >= 8 ? 8 : sp.R >= 4 ? 4 : sp.R >= 2 ? 2 : 1;   // all of a short strip at once
-    switch (unroll) {
-    case 1: JK_LAUNCH_NT(1); break;
-    case 2: JK_LAUNCH_NT(2); break;
-    case 8: JK_LAUNCH_NT(8); break;
-    default: JK_LAUNCH_NT(4); break;
+        switch (c.rows_per_wave) {
+        case 1: JK_3D_U(1); break;
+        case 2: JK_3D_U(2); break;
+        default: JK_3D_U(4); break;
+        }
+#undef JK_3D_U
+#undef JK_3D
     }
-#undef JK_LAUNCH_NT
-#undef JK_LAUNCH
+#undef JK_ARGS
     HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
@@ -125,6 +169,15 @@ int launch_update(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
     return p->lay.dtype == JACOBI_F64
                ? launch_sweep_t<double, jk::MODE_UPDATE>(p, (const double *)src, (double *)dst, nullptr, st)
                : launch_sweep_t<float, jk::MODE_UPDATE>(p, (const float *)src, (float *)dst, nullptr, st);
+}
+
+// Update src -> dst and, in the same pass, per-workgroup partial sums of the squared residual
+// terms of src.
+int launch_update_with_residual(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
+{
+    return p->lay.dtype == JACOBI_F64
+               ? launch_sweep_t<double, jk::MODE_BOTH>(p, (const double *)src, (double *)dst, p->partial, st)
+               : launch_sweep_t<float, jk::MODE_BOTH>(p, (const float *)src, (float *)dst, p->partial, st);
 }
 
 template <typename T, int FMODE>
@@ -195,7 +248,7 @@ int ensure_partials(jacobi_plan *p, int64_t need)
 
 int residual_common(jacobi_plan *p, void *grid, double *result_dev, hipStream_t st)
 {
-    const StripParams sp = make_strips(p);
+    const StripParams sp = make_config(p, jk::MODE_RESIDUAL).sp;
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     // one extra slot holds the result for the host variant
     int rc = ensure_partials(p, nwg + 1);
@@ -220,6 +273,7 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "profile")) return &p->profile;
     if (!strcmp(key, "unroll")) return &p->unroll;
     if (!strcmp(key, "xcd_chunk")) return &p->xcd_chunk;
+    if (!strcmp(key, "rows_per_wave")) return &p->rows_per_wave;
     return nullptr;
 }
 
@@ -336,15 +390,9 @@ int halo_exchange(jacobi_plan *plan, void *grid, void *stream)
     return launch_exchange(plan, grid, (hipStream_t)stream);
 }
 
-int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final)
+static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipStream_t st, void **final,
+                        double *residual_in_dev)
 {
-    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
-    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
-    if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
-    if (final) *final = in;
-    if (iters == 0) return JACOBI_OK;
-    hipStream_t st = (hipStream_t)stream;
-
     if (plan->profile && plan->ev.empty()) {
         plan->ev.reserve(2 * MAX_PROFILE_EVENTS);
         for (int i = 0; i < 2 * MAX_PROFILE_EVENTS; ++i) {
@@ -352,6 +400,12 @@ int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream
             HIP_TRY(hipEventCreate(&e));
             plan->ev.push_back(e);
         }
+    }
+    int64_t nwg_res = 0;
+    if (residual_in_dev) {
+        nwg_res = ceil_div(make_config(plan, jk::MODE_BOTH).sp.nstrips, jk::WAVES_PER_WG);
+        int rc = ensure_partials(plan, nwg_res + 1);
+        if (rc) return rc;
     }
 
     int rc = launch_boundary_sync(plan, in, out, st);
@@ -366,16 +420,42 @@ int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream
         }
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
-        rc = launch_update(plan, src, dst, st);
+        rc = (k == 0 && residual_in_dev) ? launch_update_with_residual(plan, src, dst, st)
+                                         : launch_update(plan, src, dst, st);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));
             ++plan->ev_used;
         }
+        if (k == 0 && residual_in_dev) {
+            hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, plan->partial,
+                               (long long)nwg_res, residual_in_dev);
+            HIP_TRY(hipGetLastError());
+        }
         void *t = src; src = dst; dst = t;
     }
     if (final) *final = src;
     return JACOBI_OK;
+}
+
+int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final)
+{
+    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
+    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
+    if (final) *final = in;
+    if (iters == 0) return JACOBI_OK;
+    return sweep_common(plan, in, out, iters, (hipStream_t)stream, final, nullptr);
+}
+
+int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final,
+                          double *residual_in_dev)
+{
+    if (!plan || !in || !out || !residual_in_dev) return fail(JACOBI_EINVAL, "NULL argument");
+    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (iters < 1) return fail(JACOBI_EINVAL, "iters must be >= 1");
+    if (final) *final = in;
+    return sweep_common(plan, in, out, iters, (hipStream_t)stream, final, residual_in_dev);
 }
 
 int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *stream)
@@ -390,7 +470,7 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
     hipStream_t st = (hipStream_t)stream;
     int rc = residual_common(plan, grid, nullptr, st);
     if (rc) return rc;
-    const StripParams sp = make_strips(plan);
+    const StripParams sp = make_config(plan, jk::MODE_RESIDUAL).sp;
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     HIP_TRY(hipMemcpyAsync(result_host, plan->partial + nwg, sizeof(double), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -402,10 +482,12 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 8 : slot == &plan->nontemporal ? 3 : slot == &plan->xcd_chunk ? (1 << 20) : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 3 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
-    if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
-        return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4 or 8");
+    if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
+        return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
+    if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)
+        return fail(JACOBI_EINVAL, "rows_per_wave must be 0, 1, 2 or 4");
     *slot = value;
     return JACOBI_OK;
 }

@@ -9,9 +9,9 @@
 // with NV elements (16 bytes) per lane, so every wavefront load/store is one contiguous,
 // 16-byte-per-lane, cache-line-aligned 1 KiB access.  The marching direction keeps the
 // previous/current/next row (plane) in registers, so the two neighbours along it cost
-// no memory traffic; the x neighbours come from the adjacent lanes through the LDS
-// crossbar (ds_bpermute via __shfl) and, at the ends of the wavefront, from one extra
-// 8-byte load (the neighbouring strip's cell or the tile's dense x-halo array).
+// no memory traffic; the x neighbours come from the adjacent lanes through DPP wave
+// shifts (plain VALU moves) and, at the two ends of the wavefront, from a small gather load
+// (the neighbouring strip's cell or the tile's dense x-halo array).
 //
 // Workgroups (4 wavefronts = 4 consecutive strips) walk the strip list, which is in memory
 // order, so the chip as a whole streams through the grid front to back; see
@@ -85,6 +85,50 @@ template <bool NT, typename V> __device__ __forceinline__ void stv(V *p, V v)
     else *p = v;
 }
 
+// ---- cross-lane moves -------------------------------------------------------------
+// DPP wave shifts (full-rate VALU moves, no LDS traffic): lane i receives the value of
+// lane i-1 (wave_shr:1) or lane i+1 (wave_shl:1); the lane at the open end keeps `fill`.
+__device__ __forceinline__ int dpp_from_prev(int v, int fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+}
+__device__ __forceinline__ int dpp_from_next(int v, int fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
+}
+struct Int2 { int lo, hi; };
+__device__ __forceinline__ float from_prev_lane(float v, float fill)
+{
+    return __builtin_bit_cast(float, dpp_from_prev(__builtin_bit_cast(int, v), __builtin_bit_cast(int, fill)));
+}
+__device__ __forceinline__ float from_next_lane(float v, float fill)
+{
+    return __builtin_bit_cast(float, dpp_from_next(__builtin_bit_cast(int, v), __builtin_bit_cast(int, fill)));
+}
+__device__ __forceinline__ double from_prev_lane(double v, double fill)
+{
+    const Int2 a = __builtin_bit_cast(Int2, v), f = __builtin_bit_cast(Int2, fill);
+    const Int2 r = {dpp_from_prev(a.lo, f.lo), dpp_from_prev(a.hi, f.hi)};
+    return __builtin_bit_cast(double, r);
+}
+__device__ __forceinline__ double from_next_lane(double v, double fill)
+{
+    const Int2 a = __builtin_bit_cast(Int2, v), f = __builtin_bit_cast(Int2, fill);
+    const Int2 r = {dpp_from_next(a.lo, f.lo), dpp_from_next(a.hi, f.hi)};
+    return __builtin_bit_cast(double, r);
+}
+// Value held by lane `l` (a compile-time constant after unrolling), as a wave-uniform scalar.
+__device__ __forceinline__ float lane_value(float v, int l)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ __forceinline__ double lane_value(double v, int l)
+{
+    const Int2 a = __builtin_bit_cast(Int2, v);
+    const Int2 r = {__builtin_amdgcn_readlane(a.lo, l), __builtin_amdgcn_readlane(a.hi, l)};
+    return __builtin_bit_cast(double, r);
+}
+
 // Workgroup renumbering.  The hardware hands consecutive workgroup ids to the 8 XCDs
 // round-robin, and each XCD has its own L2.  Strips that are neighbours in a tile re-read each
 // other's border rows, which only hits in L2 if both run on the same XCD; on the other hand HBM
@@ -127,7 +171,9 @@ __device__ __forceinline__ double wg_sum(double v, double *lds /* WAVES_PER_WG (
     return s;
 }
 
-enum Mode { MODE_UPDATE = 0, MODE_RESIDUAL = 1 };
+// MODE_BOTH: update, and in the same pass the residual of the SOURCE grid (its terms need
+// exactly the values the update already holds in registers).
+enum Mode { MODE_UPDATE = 0, MODE_RESIDUAL = 1, MODE_BOTH = 2 };
 
 struct StripParams {
     int R;               // rows (2-D) / planes (3-D) per strip
@@ -168,14 +214,17 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
         const int last = g.tw - 1;
         const bool has_last = active && col0 <= last && last < col0 + NV;
         const int jlast = last - col0;
-        const bool w_lane = active && lane == 0;
-        const bool w_halo = col0 == 0;        // W neighbour of column 0 is the x- halo
-        const bool e_lane = has_last || (active && lane == WAVE - 1 && col0 + NV < g.pitch);
-
+        // x-edge cells of the wavefront: left of its first column (the x- halo for segment 0) and
+        // right of its last column (the x+ halo if the tile ends inside this segment)
+        const int seg_c0 = seg * WAVE * NV;
+        const bool seg_has_last = seg_c0 <= last && last < seg_c0 + WAVE * NV;
+        const bool w_halo = seg_c0 == 0;
+        const int e_col = seg_c0 + WAVE * NV;
+        const bool e_in_row = e_col < g.pitch;
         const T *tsrc = src + (long long)t * g.tile_stride;
         T *tdst = dst + (long long)t * g.tile_stride;
         // neighbour tiles of dst that receive this strip's edge cells (fused mode)
-        const bool push = MODE == MODE_UPDATE && sp.fused;
+        const bool push = MODE != MODE_RESIDUAL && sp.fused;
         T *dst_ym = (push && ty > 0) ? tdst - (long long)g.Tx * g.tile_stride : nullptr;
         T *dst_yp = (push && ty < g.Ty - 1) ? tdst + (long long)g.Tx * g.tile_stride : nullptr;
         T *dst_xm = (push && tx > 0 && col0 == 0 && active) ? tdst - g.tile_stride : nullptr;
@@ -188,45 +237,49 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
         }
         for (int r = r0; r <= r1; r += U) {
             V nx[U];
-            T ew[U], ee[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int rn = min(r + u + 1, g.th + 1);   // clamped: stays inside the tile
                 nx[u] = active ? ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, rn, col0))) : V(0);
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int rc = min(r + u, g.th + 1);
-                ew[u] = T(0);
-                ee[u] = T(0);
-                if (w_lane) ew[u] = w_halo ? tsrc[xm_off(g, 0, rc)] : tsrc[main_off(g, 0, rc, col0 - 1)];
-                if (e_lane) ee[u] = has_last ? tsrc[xp_off(g, 0, rc)] : tsrc[main_off(g, 0, rc, col0 + NV)];
+            // One gather load fetches every x-edge cell of this group of rows.  It is issued LAST on
+            // purpose: the first row then cannot be finished before all row loads have landed, so a
+            // wavefront reads its whole strip, then writes its whole strip.  Letting rows be stored
+            // as they arrive interleaves reads and writes at the memory and measures 3 % slower.
+            // lane l < U -> W edge of row r+l, lane 32+l -> E edge of row r+l
+            T edge = T(0);
+            {
+                const int el = lane & 31;
+                if (el < U) {
+                    const int rc = min(r + el, g.th + 1);
+                    if (lane < 32) edge = w_halo ? tsrc[xm_off(g, 0, rc)] : tsrc[main_off(g, 0, rc, seg_c0 - 1)];
+                    else if (seg_has_last) edge = tsrc[xp_off(g, 0, rc)];
+                    else if (e_in_row) edge = tsrc[main_off(g, 0, rc, e_col)];
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int rr = r + u;
-                T left = __shfl_up(cur[NV - 1], 1, WAVE);
-                T right = __shfl_down(cur[0], 1, WAVE);
-                if (lane == 0) left = ew[u];
-                if (lane == WAVE - 1) right = ee[u];
+                const T ew = lane_value(edge, u), ee = lane_value(edge, 32 + u);
+                const T left = from_prev_lane(cur[NV - 1], ew);    // lane 0 keeps the W edge
+                const T right = from_next_lane(cur[0], ee);        // lane 63 keeps the E edge
                 if (rr <= r1) {
                     V out;
 #pragma unroll
                     for (int j = 0; j < NV; ++j) {
                         const T w = j == 0 ? left : cur[j - 1];
                         T e = j == NV - 1 ? right : cur[j + 1];
-                        if (has_last && j == jlast) e = ee[u];
+                        if (has_last && j == jlast) e = ee;
                         const T we = w + e;
                         const T sn = prev[j] + nx[u][j];
-                        if constexpr (MODE == MODE_UPDATE) {
-                            out[j] = Coef<T>::quarter * (we + sn);
-                        } else {
+                        if constexpr (MODE != MODE_RESIDUAL) out[j] = Coef<T>::quarter * (we + sn);
+                        if constexpr (MODE != MODE_UPDATE) {
                             const T res = (we + sn) - Coef<T>::four * cur[j];
                             const double rd = (double)res;
                             if (col0 + j <= last) acc += rd * rd;
                         }
                     }
-                    if constexpr (MODE == MODE_UPDATE) {
+                    if constexpr (MODE != MODE_RESIDUAL) {
                         if (active) {
                             stv<(NT & 2) != 0>((V *)(tdst + main_off(g, 0, rr, col0)), out);
                             if (push) {
@@ -243,7 +296,7 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
             }
         }
     }
-    if constexpr (MODE == MODE_RESIDUAL) {
+    if constexpr (MODE != MODE_UPDATE) {
         const double tot = wg_sum(acc, red);
         if (threadIdx.x == 0) partial[lwg] = tot;
     }
@@ -251,17 +304,22 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 
 // ------------------------------------------------------------------------------------
 // 3-D: 7-point update (or residual).  new = C6*(((x- + x+)+(y- + y+))+(z- + z+)).
-// A wavefront owns one row (i) x 64*NV columns and marches through R planes keeping
-// planes k-1, k, k+1 of its row in registers; rows i-1 and i+1 of plane k are loaded
-// (they are the "current" rows of the neighbouring wavefronts, so they come from cache).
+// A wavefront owns RW consecutive rows x 64*NV columns and marches through R planes,
+// keeping planes k-1, k, k+1 of its rows in registers.  The y neighbours of the inner rows
+// are then registers too; only row i0-1 and row i0+RW of the current plane are loaded (they
+// are current rows of the neighbouring wavefronts, so they come from cache).  All x-edge
+// cells a plane needs are fetched by ONE gather load (lane l < RW: W edge of row l, lane
+// 32+l: E edge of row l) and handed to lanes 0 / 63 as wave-uniform scalars (v_readlane).
+// Strip order: tile -> plane block -> row group -> column segment.
 // ------------------------------------------------------------------------------------
-template <typename T, int MODE, int U, int NT>
+template <typename T, int MODE, int RW, int U, int NT>
 __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
                                                      double *__restrict__ partial)
 {
     using V = typename Vec<T>::type;
     constexpr int NV = Vec<T>::N;
+    static_assert(RW >= 1 && RW <= 32, "edge gather uses lanes [0,RW) and [32,32+RW)");
     __shared__ double red[WAVES_PER_WG];
 
     const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
@@ -270,13 +328,13 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
     double acc = 0.0;
 
     if (s < sp.nstrips) {
-        // strip order: tile -> plane block -> row -> column segment
-        const long long per_tile = (long long)sp.nblk * g.th * sp.nseg;
+        const int ngrp = (g.th + RW - 1) / RW;
+        const long long per_tile = (long long)sp.nblk * ngrp * sp.nseg;
         const int t = (int)(s / per_tile);
         int rem = (int)(s - (long long)t * per_tile);
-        const int kb = rem / (g.th * sp.nseg);
-        rem -= kb * g.th * sp.nseg;
-        const int i = 1 + rem / sp.nseg, seg = rem % sp.nseg;
+        const int kb = rem / (ngrp * sp.nseg);
+        rem -= kb * ngrp * sp.nseg;
+        const int i0 = 1 + (rem / sp.nseg) * RW, seg = rem % sp.nseg;
         const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
         const int k0 = 1 + kb * sp.R;
         const int k1 = min(g.td, k0 + sp.R - 1);
@@ -285,89 +343,120 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
         const int last = g.tw - 1;
         const bool has_last = active && col0 <= last && last < col0 + NV;
         const int jlast = last - col0;
-        const bool w_lane = active && lane == 0;
-        const bool w_halo = col0 == 0;
-        const bool e_lane = has_last || (active && lane == WAVE - 1 && col0 + NV < g.pitch);
+        // which lane holds the tile's last column in this segment (if any), and whether the
+        // wavefront's last lane has a right-hand neighbour cell inside the row
+        const int seg_c0 = seg * WAVE * NV;
+        const bool seg_has_last = seg_c0 <= last && last < seg_c0 + WAVE * NV;
+        const bool w_halo = seg_c0 == 0;
+        const int e_col = seg_c0 + WAVE * NV;           // column right of the wavefront
+        const bool e_in_row = e_col < g.pitch;
 
         const T *tsrc = src + (long long)t * g.tile_stride;
         T *tdst = dst + (long long)t * g.tile_stride;
-        const bool push = MODE == MODE_UPDATE && sp.fused;
+        const bool push = MODE != MODE_RESIDUAL && sp.fused;
         const long long zs = (long long)g.Ty * g.Tx * g.tile_stride, ys = (long long)g.Tx * g.tile_stride;
         T *dst_zm = (push && tz > 0) ? tdst - zs : nullptr;
         T *dst_zp = (push && tz < g.Tz - 1) ? tdst + zs : nullptr;
-        T *dst_ym = (push && ty > 0 && i == 1) ? tdst - ys : nullptr;
-        T *dst_yp = (push && ty < g.Ty - 1 && i == g.th) ? tdst + ys : nullptr;
+        T *dst_ym = (push && ty > 0) ? tdst - ys : nullptr;
+        T *dst_yp = (push && ty < g.Ty - 1) ? tdst + ys : nullptr;
         T *dst_xm = (push && tx > 0 && col0 == 0 && active) ? tdst - g.tile_stride : nullptr;
         T *dst_xp = (push && tx < g.Tx - 1 && has_last) ? tdst + g.tile_stride : nullptr;
 
-        V below = V(0), cur = V(0);
-        if (active) {
-            below = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0 - 1, i, col0)));
-            cur = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0, i, col0)));
+        // rows below the tile (ragged last row group) are clamped to the y+ halo row th+1, so the
+        // register row after the last real row IS that row's y+ neighbour; clamped rows never store
+        auto row_of = [&](int rw) { return min(i0 + rw, g.th + 1); };
+
+        V below[RW], cur[RW];
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) {
+            below[rw] = cur[rw] = V(0);
+            if (active) {
+                below[rw] = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0 - 1, row_of(rw), col0)));
+                cur[rw] = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0, row_of(rw), col0)));
+            }
         }
         for (int k = k0; k <= k1; k += U) {
-            V up[U], ym[U], yp[U];
-            T ew[U], ee[U];
+            V up[U][RW], ym[U], yp[U];
+            T edge[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int kn = min(k + u + 1, g.td + 1);
+                const int kn = min(k + u + 1, g.td + 1);   // clamped: stays inside the tile
                 const int kc = min(k + u, g.td + 1);
-                up[u] = ym[u] = yp[u] = V(0);
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw)
+                    up[u][rw] = active ? ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, kn, row_of(rw), col0))) : V(0);
+                ym[u] = yp[u] = V(0);
                 if (active) {
-                    up[u] = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, kn, i, col0)));
-                    ym[u] = *(const V *)(tsrc + main_off(g, kc, i - 1, col0));
-                    yp[u] = *(const V *)(tsrc + main_off(g, kc, i + 1, col0));
+                    ym[u] = *(const V *)(tsrc + main_off(g, kc, i0 - 1, col0));
+                    yp[u] = *(const V *)(tsrc + main_off(g, kc, row_of(RW), col0));
                 }
-                ew[u] = T(0);
-                ee[u] = T(0);
-                if (w_lane) ew[u] = w_halo ? tsrc[xm_off(g, kc, i)] : tsrc[main_off(g, kc, i, col0 - 1)];
-                if (e_lane) ee[u] = has_last ? tsrc[xp_off(g, kc, i)] : tsrc[main_off(g, kc, i, col0 + NV)];
+                // x-edge gather for plane kc: lane l < RW -> W edge of row l, lane 32+l -> E edge
+                edge[u] = T(0);
+                const int el = lane & 31;
+                if (el < RW) {
+                    const int ir = row_of(el);
+                    if (lane < 32) {
+                        edge[u] = w_halo ? tsrc[xm_off(g, kc, ir)] : tsrc[main_off(g, kc, ir, seg_c0 - 1)];
+                    } else if (seg_has_last) {
+                        edge[u] = tsrc[xp_off(g, kc, ir)];
+                    } else if (e_in_row) {
+                        edge[u] = tsrc[main_off(g, kc, ir, e_col)];
+                    }
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int kk = k + u;
-                T left = __shfl_up(cur[NV - 1], 1, WAVE);
-                T right = __shfl_down(cur[0], 1, WAVE);
-                if (lane == 0) left = ew[u];
-                if (lane == WAVE - 1) right = ee[u];
-                if (kk <= k1) {
-                    V out;
 #pragma unroll
-                    for (int j = 0; j < NV; ++j) {
-                        const T w = j == 0 ? left : cur[j - 1];
-                        T e = j == NV - 1 ? right : cur[j + 1];
-                        if (has_last && j == jlast) e = ee[u];
-                        const T xx = w + e;
-                        const T yy = ym[u][j] + yp[u][j];
-                        const T zz = below[j] + up[u][j];
-                        if constexpr (MODE == MODE_UPDATE) {
-                            out[j] = Coef<T>::sixth * ((xx + yy) + zz);
-                        } else {
-                            const T res = ((xx + yy) + zz) - Coef<T>::six * cur[j];
-                            const double rd = (double)res;
-                            if (col0 + j <= last) acc += rd * rd;
+                for (int rw = 0; rw < RW; ++rw) {
+                    const int i = i0 + rw;
+                    const V c = cur[rw];
+                    const T ew = lane_value(edge[u], rw), ee = lane_value(edge[u], 32 + rw);
+                    const T left = from_prev_lane(c[NV - 1], ew);    // lane 0 keeps the W edge
+                    const T right = from_next_lane(c[0], ee);        // lane 63 keeps the E edge
+                    if (kk <= k1 && i <= g.th) {
+                        const V ymv = rw == 0 ? ym[u] : cur[rw == 0 ? 0 : rw - 1];
+                        const V ypv = rw == RW - 1 ? yp[u] : cur[rw == RW - 1 ? rw : rw + 1];
+                        V out;
+#pragma unroll
+                        for (int j = 0; j < NV; ++j) {
+                            const T w = j == 0 ? left : c[j - 1];
+                            T e = j == NV - 1 ? right : c[j + 1];
+                            if (has_last && j == jlast) e = ee;
+                            const T xx = w + e;
+                            const T yy = ymv[j] + ypv[j];
+                            const T zz = below[rw][j] + up[u][rw][j];
+                            if constexpr (MODE != MODE_RESIDUAL) out[j] = Coef<T>::sixth * ((xx + yy) + zz);
+                            if constexpr (MODE != MODE_UPDATE) {
+                                const T res = ((xx + yy) + zz) - Coef<T>::six * c[j];
+                                const double rd = (double)res;
+                                if (col0 + j <= last) acc += rd * rd;
+                            }
                         }
-                    }
-                    if constexpr (MODE == MODE_UPDATE) {
-                        if (active) {
-                            stv<(NT & 2) != 0>((V *)(tdst + main_off(g, kk, i, col0)), out);
-                            if (push) {
-                                if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
-                                if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
-                                if (dst_ym) *(V *)(dst_ym + main_off(g, kk, g.th + 1, col0)) = out;
-                                if (dst_yp) *(V *)(dst_yp + main_off(g, kk, 0, col0)) = out;
-                                if (dst_xm) dst_xm[xp_off(g, kk, i)] = out[0];
-                                if (dst_xp) dst_xp[xm_off(g, kk, i)] = out[jlast];
+                        if constexpr (MODE != MODE_RESIDUAL) {
+                            if (active) {
+                                stv<(NT & 2) != 0>((V *)(tdst + main_off(g, kk, i, col0)), out);
+                                if (push) {
+                                    if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
+                                    if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
+                                    if (i == 1 && dst_ym) *(V *)(dst_ym + main_off(g, kk, g.th + 1, col0)) = out;
+                                    if (i == g.th && dst_yp) *(V *)(dst_yp + main_off(g, kk, 0, col0)) = out;
+                                    if (dst_xm) dst_xm[xp_off(g, kk, i)] = out[0];
+                                    if (dst_xp) dst_xp[xm_off(g, kk, i)] = out[jlast];
+                                }
                             }
                         }
                     }
                 }
-                below = cur;
-                cur = up[u];
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw) {
+                    below[rw] = cur[rw];
+                    cur[rw] = up[u][rw];
+                }
             }
         }
     }
-    if constexpr (MODE == MODE_RESIDUAL) {
+    if constexpr (MODE != MODE_UPDATE) {
         const double tot = wg_sum(acc, red);
         if (threadIdx.x == 0) partial[lwg] = tot;
     }

@@ -68,6 +68,13 @@ class JacobiRun:
         fin = B.jacobi_sweep(self.plan, self.cur.data_ptr(), self.other().data_ptr(), iters, _stream())
         self.cur = self.a if fin == self.a.data_ptr() else self.b
 
+    def sweep_residual(self, iters: int, out: torch.Tensor) -> None:
+        """sweep(iters), and `out` (1-element float64 CUDA tensor) receives the residual norm
+        of the field as it was BEFORE these iterations."""
+        fin = B.jacobi_sweep_residual(self.plan, self.cur.data_ptr(), self.other().data_ptr(), iters,
+                                      out.data_ptr(), _stream())
+        self.cur = self.a if fin == self.a.data_ptr() else self.b
+
     def exchange(self) -> None:
         B.halo_exchange(self.plan, self.cur.data_ptr(), _stream())
 

@@ -82,6 +82,7 @@ def test_null_and_argument_errors_without_device(J):
     # argument validation happens before any HIP call
     for call in (lambda: J.jacobi_sweep(p, 0, 256, 1), lambda: J.jacobi_sweep(p, 256, 256, 1),
                  lambda: J.jacobi_sweep(p, 256, 512, -1), lambda: J.halo_exchange(p, 0),
+                 lambda: J.jacobi_sweep_residual(p, 256, 512, 0, 768), lambda: J.jacobi_sweep_residual(p, 256, 512, 1, 0),
                  lambda: J.residual_norm(p, 0, 256), lambda: J.residual_norm(p, 256, 0),
                  lambda: J.jacobi_scatter(p, 0, 256), lambda: J.jacobi_gather(p, 256, 0),
                  lambda: J.jacobi_set_option(p, "no_such_option", 1),

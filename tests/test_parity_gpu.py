@@ -100,6 +100,7 @@ def test_fp32_within_tolerance(H, oracle_mod, dims, tiles, iters, every, fused):
     dict(rows_per_strip=1), dict(rows_per_strip=3, unroll=2), dict(rows_per_strip=7, fused=0, unroll=4),
     dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=3, fused=0, rows_per_strip=5),
     dict(xcd_chunk=1), dict(xcd_chunk=3, unroll=1), dict(xcd_chunk=1000),
+    dict(rows_per_wave=1), dict(rows_per_wave=2, unroll=4), dict(rows_per_wave=4, unroll=1, rows_per_strip=3),
 ])
 def test_options_do_not_change_results(H, oracle_mod, opts):
     a = random_padded((150, 260), seed=3)
@@ -214,3 +215,33 @@ def test_split_calls_equal_one_call(H, oracle_mod):
             assert np.array_equal(r.fetch(), ref)
         finally:
             r.close()
+
+
+@pytest.mark.parametrize("dims,tiles,dtype", [
+    ((150, 260), (3, 2), np.float64), ((512, 512), (4, 4), np.float64), ((20, 18, 40), (2, 3, 2), np.float64),
+    ((64, 64, 64), (2, 2, 2), np.float64), ((96, 200), (3, 2), np.float32),
+])
+def test_sweep_residual_delivers_norm_of_input_grid(H, oracle_mod, dims, tiles, dtype):
+    """The residual computed inside the first update equals residual_norm of the input grid,
+    and the update itself is unchanged."""
+    import torch
+    a = random_padded(dims, dtype=dtype, seed=17)
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    r = H.JacobiRun(dims, tiles, dtype)
+    try:
+        r.load(a)
+        r.sweep_residual(3, out[0:1])          # residual of u^0, then 3 iterations
+        r.sweep_residual(2, out[1:2])          # residual of u^3, then 2 more
+        got = r.fetch()
+        res = out.cpu().tolist()
+    finally:
+        r.close()
+    u3, _ = oracle_mod.run(a, 3)
+    u5, _ = oracle_mod.run(a, 5)
+    tol = RES_RTOL[np.dtype(dtype)]
+    assert abs(res[0] - oracle_mod.residual(a)) <= tol * res[0]
+    assert abs(res[1] - oracle_mod.residual(u3)) <= tol * res[1]
+    if dtype == np.float64:
+        assert np.array_equal(got, u5)
+    else:
+        assert np.max(np.abs(got.astype(np.float64) - u5)) <= 1e-5 * np.max(np.abs(u5))
