@@ -198,6 +198,12 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *                    (0 = 4 where the tile allows; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
+ *   "tblock"         1 | 2   temporal blocking: 2 = jacobi_sweep advances two iterations per
+ *                    pass over memory where it can (2-D, tiles of at least 2 x 2 cells, at
+ *                    least 2 iterations left; an odd last iteration is a single step).  The
+ *                    two-step pass reads the cells it needs beyond a tile straight from the
+ *                    neighbouring tiles instead of from halo cells, so the depth-2 exchange is
+ *                    part of its loads and it leaves the halo cells alone (default 1)
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
  *                    made by jacobi_sweep (read with jacobi_profile_read)
  * None of the options changes any result bit.
@@ -207,7 +213,8 @@ int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);
 
 /*
  * With option "profile" = 1: waits for the recorded events, returns the summed
- * duration (milliseconds) and number of update-kernel launches since the last read,
+ * duration (milliseconds) and number of update-kernel launches since the last read
+ * (with "tblock" = 2 a launch may cover two iterations),
  * and resets the record.  At most 8192 launches are recorded between reads; later
  * ones are not timed (and not counted).  Errors: EINVAL, EHIP.
  */

@@ -48,7 +48,7 @@ struct jacobi_plan {
     Geo geo;
     size_t esize;
     // options
-    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0;
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0, tblock = 1;
     // residual scratch (device), sized for the residual launch
     double *partial = nullptr;
     int64_t partial_cap = 0;
@@ -180,6 +180,66 @@ int launch_update_with_residual(jacobi_plan *p, const void *src, void *dst, hipS
                : launch_sweep_t<float, jk::MODE_BOTH>(p, (const float *)src, (float *)dst, p->partial, st);
 }
 
+// Two time steps per pass (2-D only; needs tiles of at least 2 x 2 cells).
+bool t2_usable(const jacobi_plan *p)
+{
+    return p->tblock == 2 && p->geo.ndim == 2 && p->geo.th >= 2 && p->geo.tw >= 2;
+}
+
+int t2_rows(const jacobi_plan *p)
+{
+    int r = (int)p->rows_per_strip;
+    if (r <= 0) r = 8;
+    r = r >= 12 ? 12 : r >= 8 ? 8 : 4;         // compiled strip heights
+    while (r > 4 && r > p->geo.th) r -= 4;
+    return r;
+}
+
+StripParams t2_strips(const jacobi_plan *p)
+{
+    const Geo &g = p->geo;
+    StripParams sp;
+    sp.R = t2_rows(p);
+    sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * (16 / (int)p->esize));
+    sp.nblk = (int)ceil_div(g.th, sp.R);
+    sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
+    sp.fused = 0;
+    sp.xcd_chunk = (int)p->xcd_chunk;
+    return sp;
+}
+
+template <typename T, int MODE>
+int launch_t2_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStream_t st)
+{
+    const StripParams sp = t2_strips(p);
+    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+    const dim3 grid((unsigned)nwg), block(jk::WG);
+    const bool nts = (p->nontemporal & 2) != 0;
+#define JK_T2(RT_)                                                                                            \
+    do {                                                                                                      \
+        if (nts) hipLaunchKernelGGL((jk::sweep2d_t2_kernel<T, MODE, RT_, 2>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
+        else     hipLaunchKernelGGL((jk::sweep2d_t2_kernel<T, MODE, RT_, 0>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
+    } while (0)
+    switch (sp.R) {
+    case 4: JK_T2(4); break;
+    case 12: JK_T2(12); break;
+    default: JK_T2(8); break;
+    }
+#undef JK_T2
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+int launch_t2(jacobi_plan *p, const void *src, void *dst, bool with_residual, hipStream_t st)
+{
+    if (p->lay.dtype == JACOBI_F64)
+        return with_residual ? launch_t2_t<double, jk::MODE_BOTH>(p, (const double *)src, (double *)dst, p->partial, st)
+                             : launch_t2_t<double, jk::MODE_UPDATE>(p, (const double *)src, (double *)dst, nullptr, st);
+    return with_residual ? launch_t2_t<float, jk::MODE_BOTH>(p, (const float *)src, (float *)dst, p->partial, st)
+                         : launch_t2_t<float, jk::MODE_UPDATE>(p, (const float *)src, (float *)dst, nullptr, st);
+}
+
 template <typename T, int FMODE>
 int launch_faces_t(jacobi_plan *p, const T *src, T *dst, hipStream_t st)
 {
@@ -274,6 +334,7 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "unroll")) return &p->unroll;
     if (!strcmp(key, "xcd_chunk")) return &p->xcd_chunk;
     if (!strcmp(key, "rows_per_wave")) return &p->rows_per_wave;
+    if (!strcmp(key, "tblock")) return &p->tblock;
     return nullptr;
 }
 
@@ -401,9 +462,11 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
             plan->ev.push_back(e);
         }
     }
+    const bool t2 = t2_usable(plan) && iters >= 2;
     int64_t nwg_res = 0;
     if (residual_in_dev) {
-        nwg_res = ceil_div(make_config(plan, jk::MODE_BOTH).sp.nstrips, jk::WAVES_PER_WG);
+        const int64_t strips = t2 ? t2_strips(plan).nstrips : make_config(plan, jk::MODE_BOTH).sp.nstrips;
+        nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
         int rc = ensure_partials(plan, nwg_res + 1);
         if (rc) return rc;
     }
@@ -411,28 +474,35 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     int rc = launch_boundary_sync(plan, in, out, st);
     if (rc) return rc;
     void *src = in, *dst = out;
-    for (int k = 0; k < iters; ++k) {
-        // halos of src must be current before the update reads them; in fused mode the previous
-        // update already wrote them, so only the very first source buffer needs the copy kernel
-        if (!plan->fused || k == 0) {
-            rc = launch_exchange(plan, src, st);
-            if (rc) return rc;
+    int k = 0;
+    while (k < iters) {
+        const bool pair = t2 && iters - k >= 2;     // two iterations in one pass
+        const bool with_res = k == 0 && residual_in_dev;
+        if (!pair) {
+            // halos of src must be current before the single-step update reads them; in fused mode
+            // the previous single-step update already wrote them, so only the first one (or one
+            // that follows a two-step pass, which leaves halos alone) needs the copy kernel
+            if (!plan->fused || k == 0 || t2) {
+                rc = launch_exchange(plan, src, st);
+                if (rc) return rc;
+            }
         }
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
-        rc = (k == 0 && residual_in_dev) ? launch_update_with_residual(plan, src, dst, st)
-                                         : launch_update(plan, src, dst, st);
+        if (pair) rc = launch_t2(plan, src, dst, with_res, st);
+        else      rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));
             ++plan->ev_used;
         }
-        if (k == 0 && residual_in_dev) {
+        if (with_res) {
             hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, plan->partial,
                                (long long)nwg_res, residual_in_dev);
             HIP_TRY(hipGetLastError());
         }
         void *t = src; src = dst; dst = t;
+        k += pair ? 2 : 1;
     }
     if (final) *final = src;
     return JACOBI_OK;
@@ -482,10 +552,11 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 3 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 3 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? 2 : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
     if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
+    if (slot == &plan->tblock && value != 1 && value != 2) return fail(JACOBI_EINVAL, "tblock must be 1 or 2");
     if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)
         return fail(JACOBI_EINVAL, "rows_per_wave must be 0, 1, 2 or 4");
     *slot = value;

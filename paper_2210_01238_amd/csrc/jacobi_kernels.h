@@ -303,6 +303,180 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 }
 
 // ------------------------------------------------------------------------------------
+// 2-D, two time steps per pass over memory (temporal blocking, T = 2).
+//
+// A strip produces RT rows x 64*NV columns of u(t+2).  It needs u(t) on RT+4 rows and 2 more
+// columns on either side, and computes u(t+1) on RT+2 rows and 1 more column on either side
+// (the rim is recomputed by the neighbouring strips: redundant arithmetic instead of memory
+// traffic).  Cells outside the tile are read straight from the neighbouring tiles' interiors
+// (including the diagonal ones), so this kernel neither needs nor refreshes inter-tile halos:
+// the depth-2 "exchange" is folded into its loads.  Dirichlet ring cells are read from the
+// boundary tiles' halo cells and are constant in time, so u(t+1) on the ring is the ring.
+// Every u(t+1) and u(t+2) value is formed by the same expression as in the single-step
+// kernel, so the result is bit-identical to two single steps.
+//
+// The 2*(RT+4) + 2*(RT+2) cells beside the wavefront's columns come from ONE gather load:
+// lanes 0-15 column c0-1, lanes 16-31 column c0-2, lanes 32-47 the column right of the
+// wavefront (or of the tile's last column), lanes 48-63 the one after it; lane offset = row.
+// The u(t+1) value in the column just outside the wavefront ("ghost") is a wave-uniform
+// scalar computed from those cells.
+// ------------------------------------------------------------------------------------
+// Offset of the cell at row rho in [-1, th+2], column c in [-2, tw+1] relative to tile
+// (ty, tx), following it into the neighbouring tile or, on the domain boundary, onto the
+// Dirichlet halo cell (rows/columns beyond the ring are clamped onto it; they are never used).
+// Needs th >= 2 and tw >= 2.
+__device__ __forceinline__ long long t2_cell_off(const Geo &g, int ty, int tx, int rho, int c)
+{
+    int rr = rho, cc = c;
+    if (rho <= 0) {
+        if (ty > 0) { --ty; rr = g.th + rho; } else rr = 0;
+    } else if (rho > g.th) {
+        if (ty < g.Ty - 1) { ++ty; rr = rho - g.th; } else rr = g.th + 1;
+    }
+    if (c < 0) {
+        if (tx > 0) { --tx; cc = g.tw + c; } else cc = -1;
+    } else if (c >= g.tw) {
+        if (tx < g.Tx - 1) { ++tx; cc = c - g.tw; } else cc = g.tw;
+    }
+    const long long base = ((long long)ty * g.Tx + tx) * g.tile_stride;
+    return base + (cc < 0 ? xm_off(g, 0, rr) : cc >= g.tw ? xp_off(g, 0, rr) : main_off(g, 0, rr, cc));
+}
+
+template <typename T, int NV> __device__ __forceinline__ T vec_pick(const typename Vec<T>::type &v, int j)
+{
+    T r = v[0];
+#pragma unroll
+    for (int q = 1; q < NV; ++q) r = j == q ? v[q] : r;
+    return r;
+}
+
+template <typename T, int MODE, int RT, int NT>
+__global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
+                                                        const T *__restrict__ src, T *__restrict__ dst,
+                                                        double *__restrict__ partial)
+{
+    using V = typename Vec<T>::type;
+    constexpr int NV = Vec<T>::N;
+    static_assert(RT >= 1 && RT + 4 <= 16, "the edge gather gives each column 16 lanes");
+    static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
+    __shared__ double red[WAVES_PER_WG];
+
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    const long long lwg = xcd_logical_wg(sp.xcd_chunk);
+    const long long s = lwg * WAVES_PER_WG + wave;
+    double acc = 0.0;
+
+    if (s < sp.nstrips) {
+        const int per_tile = sp.nblk * sp.nseg;
+        const int t = (int)(s / per_tile);
+        const int rem = (int)(s - (long long)t * per_tile);
+        const int rb = rem / sp.nseg, seg = rem - rb * sp.nseg;
+        const int ty = t / g.Tx, tx = t - ty * g.Tx;
+        const int r0 = 1 + rb * RT;
+        const int r1 = min(g.th, r0 + RT - 1);
+        const int col0 = (seg * WAVE + lane) * NV;
+        const bool active = col0 < g.pitch;
+        const int last = g.tw - 1;
+        const bool has_last = active && col0 <= last && last < col0 + NV;
+        const int jlast = last - col0;
+        const int seg_c0 = seg * WAVE * NV;
+        const bool seg_has_last = seg_c0 <= last && last < seg_c0 + WAVE * NV;
+        const int ecol = seg_has_last ? g.tw : seg_c0 + WAVE * NV;   // first column right of our cells
+        const bool w_ring = tx == 0 && seg_c0 == 0;                  // column c0-1 is the Dirichlet ring
+        const bool e_ring = tx == g.Tx - 1 && seg_has_last;
+        // lane / component holding the cell left of column `ecol`
+        const int ll = seg_has_last ? (last - seg_c0) / NV : WAVE - 1;
+        const int jl = seg_has_last ? (last - seg_c0) % NV : NV - 1;
+
+        // rows r0-2 .. r0+RT+1 of u(t); index q, row rho = r0-2+q (clamped to th+2 for ragged strips)
+        auto rho_of = [&](int q) { return min(r0 - 2 + q, g.th + 2); };
+        auto ring_row = [&](int rho) { return (rho <= 0 && ty == 0) || (rho > g.th && ty == g.Ty - 1); };
+
+        V in[RT + 4];
+#pragma unroll
+        for (int q = 0; q < RT + 4; ++q) {
+            in[q] = V(0);
+            if (active) {
+                // same columns, row followed into the tile above / below (column 0 <= col0 < tw region)
+                const long long off = t2_cell_off(g, ty, tx, rho_of(q), 0) + col0;
+                in[q] = ldv<(NT & 1) != 0>((const V *)(src + off));
+            }
+        }
+        T edge = T(0);
+        {
+            const int q = lane & 15, grp = lane >> 4;
+            const int c = grp == 0 ? seg_c0 - 1 : grp == 1 ? seg_c0 - 2 : grp == 2 ? ecol : ecol + 1;
+            const bool unused = (grp == 1 && w_ring) || (grp == 3 && e_ring);
+            if (q < RT + 4 && !unused) edge = src[t2_cell_off(g, ty, tx, rho_of(q), c)];
+        }
+
+        // u(t+1): rows r0-1 .. r0+RT (index m, row r0-1+m, source index q = m+1), kept in a window of 3
+        V mid[RT + 2];
+        T gw[RT + 2], ge[RT + 2];
+#pragma unroll
+        for (int m = 0; m < RT + 2; ++m) {
+            const int q = m + 1;
+            const int rho = r0 - 1 + m;
+            const T w1 = lane_value(edge, q), e1 = lane_value(edge, 32 + q);
+            if (ring_row(min(rho, g.th + 2))) {
+                mid[m] = in[q];
+                gw[m] = w1;
+                ge[m] = e1;
+            } else {
+                const T left = from_prev_lane(in[q][NV - 1], w1);
+                const T right = from_next_lane(in[q][0], e1);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) {
+                    const T w = j == 0 ? left : in[q][j - 1];
+                    T e = j == NV - 1 ? right : in[q][j + 1];
+                    if (has_last && j == jlast) e = e1;
+                    const T we = w + e;
+                    const T sn = in[q - 1][j] + in[q + 1][j];
+                    mid[m][j] = Coef<T>::quarter * (we + sn);
+                    if constexpr (MODE == MODE_BOTH) {
+                        if (rho >= r0 && rho <= r1 && col0 + j <= last) {
+                            const T res = (we + sn) - Coef<T>::four * in[q][j];
+                            const double rd = (double)res;
+                            acc += rd * rd;
+                        }
+                    }
+                }
+                // ghosts: u(t+1) in the columns just left / right of our cells
+                const T first = lane_value(in[q][0], 0);
+                const T lastv = lane_value(vec_pick<T, NV>(in[q], jl), ll);
+                const T w1u = lane_value(edge, q - 1), w1d = lane_value(edge, q + 1);
+                const T e1u = lane_value(edge, 32 + q - 1), e1d = lane_value(edge, 32 + q + 1);
+                const T w2 = lane_value(edge, 16 + q), e2 = lane_value(edge, 48 + q);
+                gw[m] = w_ring ? w1 : Coef<T>::quarter * ((w2 + first) + (w1u + w1d));
+                ge[m] = e_ring ? e1 : Coef<T>::quarter * ((lastv + e2) + (e1u + e1d));
+            }
+            // u(t+2) for row r0+o, o = m-2, as soon as its three u(t+1) rows exist
+            if (m >= 2) {
+                const int o = m - 2, mm = m - 1;
+                const int rr = r0 + o;
+                const T left = from_prev_lane(mid[mm][NV - 1], gw[mm]);
+                const T right = from_next_lane(mid[mm][0], ge[mm]);
+                if (rr <= r1) {
+                    V out;
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) {
+                        const T w = j == 0 ? left : mid[mm][j - 1];
+                        T e = j == NV - 1 ? right : mid[mm][j + 1];
+                        if (has_last && j == jlast) e = ge[mm];
+                        out[j] = Coef<T>::quarter * ((w + e) + (mid[mm - 1][j] + mid[mm + 1][j]));
+                    }
+                    if (active) stv<(NT & 2) != 0>((V *)(dst + (long long)t * g.tile_stride + main_off(g, 0, rr, col0)), out);
+                }
+            }
+        }
+    }
+    if constexpr (MODE == MODE_BOTH) {
+        const double tot = wg_sum(acc, red);
+        if (threadIdx.x == 0) partial[lwg] = tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // 3-D: 7-point update (or residual).  new = C6*(((x- + x+)+(y- + y+))+(z- + z+)).
 // A wavefront owns RW consecutive rows x 64*NV columns and marches through R planes,
 // keeping planes k-1, k, k+1 of its rows in registers.  The y neighbours of the inner rows

@@ -245,3 +245,49 @@ def test_sweep_residual_delivers_norm_of_input_grid(H, oracle_mod, dims, tiles, 
         assert np.array_equal(got, u5)
     else:
         assert np.max(np.abs(got.astype(np.float64) - u5)) <= 1e-5 * np.max(np.abs(u5))
+
+
+T2_CASES = [
+    # dims, tiles, iters, residual_every
+    ((256, 256), (1, 1), 20, 5), ((96, 200), (3, 2), 13, 4), ((64, 1030), (2, 2), 9, 3),
+    ((48, 48), (24, 24), 7, 7),           # 2x2 tiles: every value crosses tiles, diagonals included
+    ((40, 36), (1, 18), 6, 2), ((36, 40), (18, 1), 6, 3), ((300, 70), (1, 1), 11, 11),
+    ((512, 512), (4, 4), 50, 10), ((1024, 1024), (8, 8), 25, 5), ((2, 2), (1, 1), 5, 1),
+    ((26, 300), (2, 1), 8, 8), ((130, 258), (5, 2), 10, 2),
+]
+
+
+@pytest.mark.parametrize("rows", [0, 4, 12])
+@pytest.mark.parametrize("dims,tiles,iters,every", T2_CASES)
+def test_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every, rows):
+    a = random_padded(dims, seed=sum(dims) + iters)
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, tblock=2, rows_per_strip=rows))
+
+
+def test_temporal_blocking_fp32_and_fused_residual(H, oracle_mod):
+    import torch
+    a = random_padded((96, 200), dtype=np.float32, seed=7)
+    check(*run_case(H, oracle_mod, a, (3, 2), 13, 4, tblock=2))
+    b = random_padded((192, 260), seed=9)
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    r = H.JacobiRun((192, 260), (3, 2), tblock=2)
+    try:
+        r.load(b)
+        r.sweep_residual(4, out[0:1])
+        r.sweep_residual(3, out[1:2])
+        got = r.fetch()
+        res = out.cpu().tolist()
+    finally:
+        r.close()
+    u4, _ = oracle_mod.run(b, 4)
+    u7, _ = oracle_mod.run(b, 7)
+    assert abs(res[0] - oracle_mod.residual(b)) <= 1e-12 * res[0]
+    assert abs(res[1] - oracle_mod.residual(u4)) <= 1e-12 * res[1]
+    assert np.array_equal(got, u7)
+
+
+def test_temporal_blocking_falls_back_on_thin_tiles_and_3d(H, oracle_mod):
+    a = random_padded((40, 36), seed=5)
+    check(*run_case(H, oracle_mod, a, (1, 36), 6, 2, tblock=2))      # tiles one column wide
+    b = random_padded((12, 10, 40), seed=6)
+    check(*run_case(H, oracle_mod, b, (2, 1, 2), 5, 5, tblock=2))    # 3-D: single steps
