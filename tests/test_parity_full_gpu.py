@@ -7,6 +7,8 @@ iterations in test time, so each workload is checked three ways:
       chosen points (tile junctions, tile edges, domain corners) exactly;
   (3) properties that hold at any size: discrete maximum principle, strictly decreasing
       residuals, and agreement of the first residual with the oracle's.
+The schedule is the benchmark's: blocks of `residual_every` iterations, each residual taken
+from the first update of the next block (jacobi_sweep_residual), the last one stand-alone.
 """
 import numpy as np
 import pytest
@@ -43,12 +45,12 @@ def windows_for(w, iters, extra=12):
     return boxes
 
 
-def full_size_check(H, oracle, name, few):
+def full_size_check(H, oracle, name, few, fuse_residual=True, **options):
     import torch
     w = gen.WORKLOADS[name]
     a = gen.generate(w)
     amin, amax = float(a.min()), float(a.max())
-    r = H.JacobiRun(w.dims, w.tiles)
+    r = H.JacobiRun(w.dims, w.tiles, **options)
     try:
         r.load(a)
         # (1) whole grid after `few` iterations
@@ -62,7 +64,7 @@ def full_size_check(H, oracle, name, few):
         del ref, out
         # (2)+(3) the full schedule, as the benchmark runs it
         r.load(a)
-        res = r.run(w.iters, w.residual_every)
+        res = r.run(w.iters, w.residual_every, fuse_residual=fuse_residual)
         assert len(res) == w.iters // w.residual_every
         assert all(res[i + 1] < res[i] for i in range(len(res) - 1)), f"{name}: residual not decreasing"
         g = r.fetch_device()
@@ -81,6 +83,18 @@ def full_size_check(H, oracle, name, few):
 
 def test_full_C3_16384sq_8x8(H, oracle_mod):
     full_size_check(H, oracle_mod, "C3", few=3)
+
+
+def test_full_C3_two_iterations_per_pass(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C3", few=3, tblock=2)
+
+
+def test_full_C5_two_iterations_per_pass(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C5", few=5, tblock=2)
+
+
+def test_full_C3_separate_exchange_and_residual_kernels(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C3", few=2, fuse_residual=False, fused=0)
 
 
 def test_full_C5_8192sq_64x64(H, oracle_mod):

@@ -291,3 +291,17 @@ def test_temporal_blocking_falls_back_on_thin_tiles_and_3d(H, oracle_mod):
     check(*run_case(H, oracle_mod, a, (1, 36), 6, 2, tblock=2))      # tiles one column wide
     b = random_padded((12, 10, 40), seed=6)
     check(*run_case(H, oracle_mod, b, (2, 1, 2), 5, 5, tblock=2))    # 3-D: single steps
+
+
+@pytest.mark.parametrize("tblock", [1, 2])
+def test_fused_residual_schedule_equals_separate(H, oracle_mod, tblock):
+    a = random_padded((260, 390), seed=31)
+    ref, ref_res = oracle_mod.run(a, 23, 5)
+    r = H.JacobiRun((260, 390), (2, 3), tblock=tblock)
+    try:
+        r.load(a)
+        res = r.run(23, 5, fuse_residual=True)
+        out = r.fetch()
+    finally:
+        r.close()
+    check(out, res, ref, ref_res)
