@@ -136,6 +136,7 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  *            `out` if iters is odd, `in` if even (the two buffers ping-pong).
  * First copies the Dirichlet boundary halos in -> out so both buffers carry them, then
  * for each iteration: halo exchange on the source buffer, update into the other buffer.
+ * (Option "tblock" > 1 replaces this per-iteration sequence by multi-iteration passes.)
  * With option "fused" = 1 the update kernel itself writes each tile's fresh edge
  * cells into the neighbours' halos of the destination buffer (pack, transfer and
  * unpack fused into the update's epilogue), and only the first iteration needs a
@@ -189,8 +190,9 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
  *                    through; 0 = choose from the shape (default 0)
- *   "nontemporal"    0..3    bit 0: streaming (non-temporal) loads of the marching rows,
- *                    bit 1: streaming stores of the results (default 2)
+ *   "nontemporal"    0 | 2   2 = results are written with streaming (non-temporal) stores
+ *                    (default 2).  Streaming loads were measured slower (border rows are
+ *                    re-read from cache) and are not offered.  Blocked passes always stream.
  *   "unroll"         0 | 1 | 2 | 4 | 8  rows (planes) whose loads a wavefront issues back to
  *                    back before computing; 0 = choose: 2-D the whole strip, up to 8; 3-D 2
  *                    (3-D accepts at most 4) (default 0)
@@ -198,12 +200,15 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *                    (0 = 4 where the tile allows; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
- *   "tblock"         1 | 2   temporal blocking: 2 = jacobi_sweep advances two iterations per
- *                    pass over memory where it can (2-D, tiles of at least 2 x 2 cells, at
- *                    least 2 iterations left; an odd last iteration is a single step).  The
- *                    two-step pass reads the cells it needs beyond a tile straight from the
- *                    neighbouring tiles instead of from halo cells, so the depth-2 exchange is
- *                    part of its loads and it leaves the halo cells alone (default 1)
+ *   "tblock"         1..8    temporal blocking depth: jacobi_sweep advances up to this many
+ *                    iterations per pass over memory (2-D only).  Compiled pass depths are 8
+ *                    and 4 (overlapped wavefronts; need tile width a multiple of 16 bytes and
+ *                    >= 64 bytes, tile height >= depth), 2 (needs tiles >= 2 x 2) and 1; the
+ *                    remaining iterations are covered greedily, deepest pass first.  Blocked
+ *                    passes read the cells they need beyond a tile straight from the
+ *                    neighbouring tiles, so the exchange is part of their loads and they leave
+ *                    the halo cells alone.  Results are bit-identical for every depth
+ *                    (default 1: one halo exchange and one update per iteration)
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
  *                    made by jacobi_sweep (read with jacobi_profile_read)
  * None of the options changes any result bit.

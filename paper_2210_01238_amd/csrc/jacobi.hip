@@ -123,12 +123,10 @@ int launch_sweep_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStr
 #define JK_ARGS grid, block, 0, st, p->geo, sp, src, dst, partial
     if (p->geo.ndim == 2) {
 #define JK_2D(U_)                                                                                  \
-    switch (nt) {                                                                                  \
-    case 1: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 1>), JK_ARGS); break;              \
-    case 2: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 2>), JK_ARGS); break;              \
-    case 3: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 3>), JK_ARGS); break;              \
-    default: hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 0>), JK_ARGS); break;             \
-    }
+    do {                                                                                           \
+        if (nt & 2) hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 2>), JK_ARGS);             \
+        else        hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 0>), JK_ARGS);             \
+    } while (0)
         switch (c.unroll) {
         case 1: JK_2D(1); break;
         case 2: JK_2D(2); break;
@@ -138,8 +136,6 @@ int launch_sweep_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStr
         }
 #undef JK_2D
     } else {
-        // 3-D: non-temporal loads are never useful (every row is re-read as a neighbour), so
-        // only the store bit of the option is honoured
 #define JK_3D(RW_, U_)                                                                             \
     do {                                                                                           \
         if (nt & 2) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, RW_, U_, 2>), JK_ARGS);        \
@@ -183,23 +179,16 @@ int launch_update_with_residual(jacobi_plan *p, const void *src, void *dst, hipS
 // Two time steps per pass (2-D only; needs tiles of at least 2 x 2 cells).
 bool t2_usable(const jacobi_plan *p)
 {
-    return p->tblock == 2 && p->geo.ndim == 2 && p->geo.th >= 2 && p->geo.tw >= 2;
+    return p->geo.ndim == 2 && p->geo.th >= 2 && p->geo.tw >= 2;
 }
 
-int t2_rows(const jacobi_plan *p)
-{
-    int r = (int)p->rows_per_strip;
-    if (r <= 0) r = 8;
-    r = r >= 12 ? 12 : r >= 8 ? 8 : 4;         // compiled strip heights
-    while (r > 4 && r > p->geo.th) r -= 4;
-    return r;
-}
+constexpr int T2_ROWS = 8;
 
 StripParams t2_strips(const jacobi_plan *p)
 {
     const Geo &g = p->geo;
     StripParams sp;
-    sp.R = t2_rows(p);
+    sp.R = T2_ROWS;
     sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * (16 / (int)p->esize));
     sp.nblk = (int)ceil_div(g.th, sp.R);
     sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
@@ -214,19 +203,8 @@ int launch_t2_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStream
     const StripParams sp = t2_strips(p);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-    const dim3 grid((unsigned)nwg), block(jk::WG);
-    const bool nts = (p->nontemporal & 2) != 0;
-#define JK_T2(RT_)                                                                                            \
-    do {                                                                                                      \
-        if (nts) hipLaunchKernelGGL((jk::sweep2d_t2_kernel<T, MODE, RT_, 2>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
-        else     hipLaunchKernelGGL((jk::sweep2d_t2_kernel<T, MODE, RT_, 0>), grid, block, 0, st, p->geo, sp, src, dst, partial); \
-    } while (0)
-    switch (sp.R) {
-    case 4: JK_T2(4); break;
-    case 12: JK_T2(12); break;
-    default: JK_T2(8); break;
-    }
-#undef JK_T2
+    hipLaunchKernelGGL((jk::sweep2d_t2_kernel<T, MODE, T2_ROWS, 2>), dim3((unsigned)nwg), dim3(jk::WG), 0, st, p->geo, sp,
+                       src, dst, partial);
     HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
@@ -238,6 +216,73 @@ int launch_t2(jacobi_plan *p, const void *src, void *dst, bool with_residual, hi
                              : launch_t2_t<double, jk::MODE_UPDATE>(p, (const double *)src, (double *)dst, nullptr, st);
     return with_residual ? launch_t2_t<float, jk::MODE_BOTH>(p, (const float *)src, (float *)dst, p->partial, st)
                          : launch_t2_t<float, jk::MODE_UPDATE>(p, (const float *)src, (float *)dst, nullptr, st);
+}
+
+// ---- general-depth temporal blocking (overlapped wavefronts) ------------------------------
+// Depths that are compiled (each with 16-row strips, the best measured shape).  A request for
+// depth d runs passes of the largest compiled depth that still fits the remaining iterations,
+// then the two-step kernel, then single steps.
+constexpr int TB_DEPTHS[] = {8, 4};
+constexpr int TB_ROWS = 16;
+
+bool tb_usable(const jacobi_plan *p, int depth)
+{
+    const Geo &g = p->geo;
+    const int nv = 16 / (int)p->esize;
+    return g.ndim == 2 && g.tw % nv == 0 && g.tw >= jk::TB_GHOST_LANES * nv && g.th >= depth;
+}
+
+StripParams tb_strips(const jacobi_plan *p)
+{
+    const Geo &g = p->geo;
+    StripParams sp;
+    sp.R = TB_ROWS;
+    sp.nseg = (int)ceil_div(g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
+    sp.nblk = (int)ceil_div(g.th, sp.R);
+    sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
+    sp.fused = 0;
+    sp.xcd_chunk = (int)p->xcd_chunk;
+    return sp;
+}
+
+template <typename T, int MODE>
+int launch_tb_t(jacobi_plan *p, int depth, const T *src, T *dst, double *partial, hipStream_t st)
+{
+    const StripParams sp = tb_strips(p);
+    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+    const dim3 grid((unsigned)nwg), block(jk::WG);
+    // last template argument: minimum wavefronts per SIMD the compiler must fit (3 is the largest
+    // occupancy these kernels reach without register spills); blocked passes always stream stores
+    switch (depth) {
+    case 8: hipLaunchKernelGGL((jk::sweep2d_tb_kernel<T, MODE, 8, TB_ROWS, 2, 3>), grid, block, 0, st, p->geo, sp, src, dst, partial); break;
+    case 4: hipLaunchKernelGGL((jk::sweep2d_tb_kernel<T, MODE, 4, TB_ROWS, 2, 3>), grid, block, 0, st, p->geo, sp, src, dst, partial); break;
+    default: return fail(JACOBI_EINVAL, "temporal-blocking depth not compiled");
+    }
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+int launch_tb(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
+{
+    if (p->lay.dtype == JACOBI_F64)
+        return with_residual ? launch_tb_t<double, jk::MODE_BOTH>(p, depth, (const double *)src, (double *)dst, p->partial, st)
+                             : launch_tb_t<double, jk::MODE_UPDATE>(p, depth, (const double *)src, (double *)dst, nullptr, st);
+    return with_residual ? launch_tb_t<float, jk::MODE_BOTH>(p, depth, (const float *)src, (float *)dst, p->partial, st)
+                         : launch_tb_t<float, jk::MODE_UPDATE>(p, depth, (const float *)src, (float *)dst, nullptr, st);
+}
+
+// What one pass does with `left` iterations to go: the deepest compiled overlapped-wavefront
+// pass that fits and applies, else the two-step kernel, else a single step (needs current halos).
+struct PassChoice { int depth; bool general; };
+
+PassChoice choose_pass(const jacobi_plan *p, int left)
+{
+    const int want = (int)(p->tblock < left ? p->tblock : left);
+    for (int d : TB_DEPTHS)
+        if (d <= want && tb_usable(p, d)) return {d, true};
+    if (want >= 2 && t2_usable(p)) return {2, false};
+    return {1, false};
 }
 
 template <typename T, int FMODE>
@@ -462,10 +507,12 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
             plan->ev.push_back(e);
         }
     }
-    const bool t2 = t2_usable(plan) && iters >= 2;
+    const PassChoice first = choose_pass(plan, iters);
     int64_t nwg_res = 0;
     if (residual_in_dev) {
-        const int64_t strips = t2 ? t2_strips(plan).nstrips : make_config(plan, jk::MODE_BOTH).sp.nstrips;
+        const int64_t strips = first.depth == 1 ? make_config(plan, jk::MODE_BOTH).sp.nstrips
+                               : first.general  ? tb_strips(plan).nstrips
+                                                : t2_strips(plan).nstrips;
         nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
         int rc = ensure_partials(plan, nwg_res + 1);
         if (rc) return rc;
@@ -475,22 +522,20 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     if (rc) return rc;
     void *src = in, *dst = out;
     int k = 0;
+    bool halos_current = false;     // inter-tile halos of src hold src's own edge cells
     while (k < iters) {
-        const bool pair = t2 && iters - k >= 2;     // two iterations in one pass
+        const PassChoice pc = choose_pass(plan, iters - k);
         const bool with_res = k == 0 && residual_in_dev;
-        if (!pair) {
-            // halos of src must be current before the single-step update reads them; in fused mode
-            // the previous single-step update already wrote them, so only the first one (or one
-            // that follows a two-step pass, which leaves halos alone) needs the copy kernel
-            if (!plan->fused || k == 0 || t2) {
-                rc = launch_exchange(plan, src, st);
-                if (rc) return rc;
-            }
+        if (pc.depth == 1 && !halos_current) {
+            // the single-step update reads halos; blocked passes neither need nor refresh them
+            rc = launch_exchange(plan, src, st);
+            if (rc) return rc;
         }
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
-        if (pair) rc = launch_t2(plan, src, dst, with_res, st);
-        else      rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
+        if (pc.depth == 1)   rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
+        else if (pc.general) rc = launch_tb(plan, pc.depth, src, dst, with_res, st);
+        else                 rc = launch_t2(plan, src, dst, with_res, st);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));
@@ -501,8 +546,10 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
                                (long long)nwg_res, residual_in_dev);
             HIP_TRY(hipGetLastError());
         }
+        // a single-step update with the fused push leaves dst's halos current
+        halos_current = pc.depth == 1 && plan->fused;
         void *t = src; src = dst; dst = t;
-        k += pair ? 2 : 1;
+        k += pc.depth;
     }
     if (final) *final = src;
     return JACOBI_OK;
@@ -552,11 +599,12 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 3 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? 2 : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? 8 : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
     if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
-    if (slot == &plan->tblock && value != 1 && value != 2) return fail(JACOBI_EINVAL, "tblock must be 1 or 2");
+    if (slot == &plan->nontemporal && value == 1) return fail(JACOBI_EINVAL, "nontemporal must be 0 or 2");
+    if (slot == &plan->tblock && value < 1) return fail(JACOBI_EINVAL, "tblock must be 1..8");
     if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)
         return fail(JACOBI_EINVAL, "rows_per_wave must be 0, 1, 2 or 4");
     *slot = value;

@@ -93,6 +93,14 @@ def test_full_C5_two_iterations_per_pass(H, oracle_mod):
     full_size_check(H, oracle_mod, "C5", few=5, tblock=2)
 
 
+def test_full_C3_eight_iterations_per_pass(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C3", few=3, tblock=8)
+
+
+def test_full_C2_eight_iterations_per_pass(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C2", few=10, tblock=8)
+
+
 def test_full_C3_separate_exchange_and_residual_kernels(H, oracle_mod):
     full_size_check(H, oracle_mod, "C3", few=2, fuse_residual=False, fused=0)
 

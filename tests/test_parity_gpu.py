@@ -98,7 +98,7 @@ def test_fp32_within_tolerance(H, oracle_mod, dims, tiles, iters, every, fused):
 
 @pytest.mark.parametrize("opts", [
     dict(rows_per_strip=1), dict(rows_per_strip=3, unroll=2), dict(rows_per_strip=7, fused=0, unroll=4),
-    dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=1), dict(nontemporal=3, fused=0, rows_per_strip=5),
+    dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=0, fused=0, rows_per_strip=5), dict(unroll=16, rows_per_strip=16),
     dict(xcd_chunk=1), dict(xcd_chunk=3, unroll=1), dict(xcd_chunk=1000),
     dict(rows_per_wave=1), dict(rows_per_wave=2, unroll=4), dict(rows_per_wave=4, unroll=1, rows_per_strip=3),
 ])
@@ -257,11 +257,10 @@ T2_CASES = [
 ]
 
 
-@pytest.mark.parametrize("rows", [0, 4, 12])
 @pytest.mark.parametrize("dims,tiles,iters,every", T2_CASES)
-def test_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every, rows):
+def test_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every):
     a = random_padded(dims, seed=sum(dims) + iters)
-    check(*run_case(H, oracle_mod, a, tiles, iters, every, tblock=2, rows_per_strip=rows))
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, tblock=2))
 
 
 def test_temporal_blocking_fp32_and_fused_residual(H, oracle_mod):
@@ -300,6 +299,36 @@ def test_fused_residual_schedule_equals_separate(H, oracle_mod, tblock):
     r = H.JacobiRun((260, 390), (2, 3), tblock=tblock)
     try:
         r.load(a)
+        res = r.run(23, 5, fuse_residual=True)
+        out = r.fetch()
+    finally:
+        r.close()
+    check(out, res, ref, ref_res)
+
+
+@pytest.mark.parametrize("opts", [dict(tblock=3), dict(tblock=4), dict(tblock=6), dict(tblock=8), dict(tblock=5), dict(tblock=7),
+                                  dict(tblock=8, xcd_chunk=1), dict(tblock=4, nontemporal=0)])
+@pytest.mark.parametrize("dims,tiles,iters,every", T2_CASES + [
+    ((64, 64), (8, 8), 19, 19),            # 8x8 tiles: ghost columns span exactly one neighbour tile
+    ((48, 224), (3, 2), 17, 4),            # tw = 112: exactly one wavefront of owned columns
+    ((40, 480), (2, 2), 16, 8),            # tw = 240: 3 column segments, last one ragged
+    ((100, 128), (2, 1), 33, 11),          # th = 50: ragged last 16-row strip
+    ((34, 64), (1, 4), 9, 9),              # tw = 16: every lane of a wavefront beyond the first tiles is a neighbour's
+])
+def test_deep_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every, opts):
+    a = random_padded(dims, seed=sum(dims) + iters)
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
+
+
+@pytest.mark.parametrize("tblock", [3, 4, 8])
+def test_deep_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock):
+    a = random_padded((96, 256), dtype=np.float32, seed=7)
+    check(*run_case(H, oracle_mod, a, (3, 2), 21, 5, tblock=tblock))
+    b = random_padded((192, 256), seed=9)
+    ref, ref_res = oracle_mod.run(b, 23, 5)
+    r = H.JacobiRun((192, 256), (3, 2), tblock=tblock)
+    try:
+        r.load(b)
         res = r.run(23, 5, fuse_residual=True)
         out = r.fetch()
     finally:
