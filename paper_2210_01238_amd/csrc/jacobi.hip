@@ -2,7 +2,8 @@
 // launches for the block-decomposed Jacobi iteration (paper Sec. VI-C).  Declarations and
 // the contract of every entry point are in include/jacobi.h.
 #include "jacobi.h"
-#include "jacobi_kernels.h"
+#include "aux_kernels.h"
+#include "launchers.h"
 
 #include <hip/hip_runtime.h>
 
@@ -111,69 +112,41 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     return c;
 }
 
-template <typename T, int MODE>
-int launch_sweep_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStream_t st)
+int launch_checked(hipError_t e, const char *what)
 {
-    const SweepConfig c = make_config(p, MODE);
-    const StripParams &sp = c.sp;
-    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
-    if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-    const dim3 grid((unsigned)nwg), block(jk::WG);
-    const int nt = (int)p->nontemporal;
-#define JK_ARGS grid, block, 0, st, p->geo, sp, src, dst, partial
-    if (p->geo.ndim == 2) {
-#define JK_2D(U_)                                                                                  \
-    do {                                                                                           \
-        if (nt & 2) hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 2>), JK_ARGS);             \
-        else        hipLaunchKernelGGL((jk::sweep2d_kernel<T, MODE, U_, 0>), JK_ARGS);             \
-    } while (0)
-        switch (c.unroll) {
-        case 1: JK_2D(1); break;
-        case 2: JK_2D(2); break;
-        case 8: JK_2D(8); break;
-        case 16: JK_2D(16); break;
-        default: JK_2D(4); break;
-        }
-#undef JK_2D
-    } else {
-#define JK_3D(RW_, U_)                                                                             \
-    do {                                                                                           \
-        if (nt & 2) hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, RW_, U_, 2>), JK_ARGS);        \
-        else        hipLaunchKernelGGL((jk::sweep3d_kernel<T, MODE, RW_, U_, 0>), JK_ARGS);        \
-    } while (0)
-#define JK_3D_U(RW_)                                                                               \
-    switch (c.unroll) {                                                                            \
-    case 1: JK_3D(RW_, 1); break;                                                                  \
-    case 4: JK_3D(RW_, 4); break;                                                                  \
-    default: JK_3D(RW_, 2); break;                                                                 \
-    }
-        switch (c.rows_per_wave) {
-        case 1: JK_3D_U(1); break;
-        case 2: JK_3D_U(2); break;
-        default: JK_3D_U(4); break;
-        }
-#undef JK_3D_U
-#undef JK_3D
-    }
-#undef JK_ARGS
-    HIP_TRY(hipGetLastError());
+    if (e == hipErrorInvalidValue) return fail(JACOBI_EINVAL, "kernel variant not compiled for these options");
+    if (e != hipSuccess) return fail_hip(e, what);
     return JACOBI_OK;
+}
+
+// Single-step pass over `src` in the given mode (jk::Mode).
+int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *partial, hipStream_t st)
+{
+    const SweepConfig c = make_config(p, mode);
+    const int64_t nwg = ceil_div(c.sp.nstrips, jk::WAVES_PER_WG);
+    if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+    const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, c.sp, src, dst, partial};
+    const bool f64 = p->lay.dtype == JACOBI_F64;
+    const int nt = (int)p->nontemporal;
+    hipError_t e;
+    if (p->geo.ndim == 2)
+        e = f64 ? jk::launch_sweep2d_f64(mode, c.unroll, nt, a) : jk::launch_sweep2d_f32(mode, c.unroll, nt, a);
+    else
+        e = f64 ? jk::launch_sweep3d_f64(mode, c.rows_per_wave, c.unroll, nt, a)
+                : jk::launch_sweep3d_f32(mode, c.rows_per_wave, c.unroll, nt, a);
+    return launch_checked(e, "update kernel launch");
 }
 
 int launch_update(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
 {
-    return p->lay.dtype == JACOBI_F64
-               ? launch_sweep_t<double, jk::MODE_UPDATE>(p, (const double *)src, (double *)dst, nullptr, st)
-               : launch_sweep_t<float, jk::MODE_UPDATE>(p, (const float *)src, (float *)dst, nullptr, st);
+    return launch_sweep(p, jk::MODE_UPDATE, src, dst, nullptr, st);
 }
 
 // Update src -> dst and, in the same pass, per-workgroup partial sums of the squared residual
 // terms of src.
 int launch_update_with_residual(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
 {
-    return p->lay.dtype == JACOBI_F64
-               ? launch_sweep_t<double, jk::MODE_BOTH>(p, (const double *)src, (double *)dst, p->partial, st)
-               : launch_sweep_t<float, jk::MODE_BOTH>(p, (const float *)src, (float *)dst, p->partial, st);
+    return launch_sweep(p, jk::MODE_BOTH, src, dst, p->partial, st);
 }
 
 // Two time steps per pass (2-D only; needs tiles of at least 2 x 2 cells).
@@ -182,13 +155,11 @@ bool t2_usable(const jacobi_plan *p)
     return p->geo.ndim == 2 && p->geo.th >= 2 && p->geo.tw >= 2;
 }
 
-constexpr int T2_ROWS = 8;
-
 StripParams t2_strips(const jacobi_plan *p)
 {
     const Geo &g = p->geo;
     StripParams sp;
-    sp.R = T2_ROWS;
+    sp.R = jk::T2_ROWS;
     sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * (16 / (int)p->esize));
     sp.nblk = (int)ceil_div(g.th, sp.R);
     sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
@@ -197,46 +168,30 @@ StripParams t2_strips(const jacobi_plan *p)
     return sp;
 }
 
-template <typename T, int MODE>
-int launch_t2_t(jacobi_plan *p, const T *src, T *dst, double *partial, hipStream_t st)
+int launch_t2(jacobi_plan *p, const void *src, void *dst, bool with_residual, hipStream_t st)
 {
     const StripParams sp = t2_strips(p);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-    hipLaunchKernelGGL((jk::sweep2d_t2_kernel<T, MODE, T2_ROWS, 2>), dim3((unsigned)nwg), dim3(jk::WG), 0, st, p->geo, sp,
-                       src, dst, partial);
-    HIP_TRY(hipGetLastError());
-    return JACOBI_OK;
-}
-
-int launch_t2(jacobi_plan *p, const void *src, void *dst, bool with_residual, hipStream_t st)
-{
-    if (p->lay.dtype == JACOBI_F64)
-        return with_residual ? launch_t2_t<double, jk::MODE_BOTH>(p, (const double *)src, (double *)dst, p->partial, st)
-                             : launch_t2_t<double, jk::MODE_UPDATE>(p, (const double *)src, (double *)dst, nullptr, st);
-    return with_residual ? launch_t2_t<float, jk::MODE_BOTH>(p, (const float *)src, (float *)dst, p->partial, st)
-                         : launch_t2_t<float, jk::MODE_UPDATE>(p, (const float *)src, (float *)dst, nullptr, st);
+    const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
+    return launch_checked(jk::launch_t2(p->lay.dtype == JACOBI_F64, with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE, a),
+                          "two-step kernel launch");
 }
 
 // ---- general-depth temporal blocking (overlapped wavefronts) ------------------------------
-// Depths that are compiled (each with 16-row strips, the best measured shape).  A request for
-// depth d runs passes of the largest compiled depth that still fits the remaining iterations,
-// then the two-step kernel, then single steps.
-constexpr int TB_DEPTHS[] = {8, 4};
-constexpr int TB_ROWS = 16;
-
 bool tb_usable(const jacobi_plan *p, int depth)
 {
     const Geo &g = p->geo;
     const int nv = 16 / (int)p->esize;
-    return g.ndim == 2 && g.tw % nv == 0 && g.tw >= jk::TB_GHOST_LANES * nv && g.th >= depth;
+    return depth >= jk::TB_MIN && depth <= jk::TB_MAX && g.ndim == 2 && g.tw % nv == 0 &&
+           g.tw >= jk::TB_GHOST_LANES * nv && g.th >= depth;
 }
 
 StripParams tb_strips(const jacobi_plan *p)
 {
     const Geo &g = p->geo;
     StripParams sp;
-    sp.R = TB_ROWS;
+    sp.R = jk::TB_ROWS;
     sp.nseg = (int)ceil_div(g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
     sp.nblk = (int)ceil_div(g.th, sp.R);
     sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
@@ -245,43 +200,43 @@ StripParams tb_strips(const jacobi_plan *p)
     return sp;
 }
 
-template <typename T, int MODE>
-int launch_tb_t(jacobi_plan *p, int depth, const T *src, T *dst, double *partial, hipStream_t st)
+int launch_tb(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
 {
     const StripParams sp = tb_strips(p);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-    const dim3 grid((unsigned)nwg), block(jk::WG);
-    // last template argument: minimum wavefronts per SIMD the compiler must fit (3 is the largest
-    // occupancy these kernels reach without register spills); blocked passes always stream stores
+    const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
+    const bool f64 = p->lay.dtype == JACOBI_F64;
+    const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
+    hipError_t e = hipErrorInvalidValue;
     switch (depth) {
-    case 8: hipLaunchKernelGGL((jk::sweep2d_tb_kernel<T, MODE, 8, TB_ROWS, 2, 3>), grid, block, 0, st, p->geo, sp, src, dst, partial); break;
-    case 4: hipLaunchKernelGGL((jk::sweep2d_tb_kernel<T, MODE, 4, TB_ROWS, 2, 3>), grid, block, 0, st, p->geo, sp, src, dst, partial); break;
-    default: return fail(JACOBI_EINVAL, "temporal-blocking depth not compiled");
+    case 4: e = jk::launch_tb_d4(f64, mode, a); break;
+    case 5: e = jk::launch_tb_d5(f64, mode, a); break;
+    case 6: e = jk::launch_tb_d6(f64, mode, a); break;
+    case 7: e = jk::launch_tb_d7(f64, mode, a); break;
+    case 8: e = jk::launch_tb_d8(f64, mode, a); break;
     }
-    HIP_TRY(hipGetLastError());
-    return JACOBI_OK;
+    return launch_checked(e, "blocked-pass kernel launch");
 }
 
-int launch_tb(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
-{
-    if (p->lay.dtype == JACOBI_F64)
-        return with_residual ? launch_tb_t<double, jk::MODE_BOTH>(p, depth, (const double *)src, (double *)dst, p->partial, st)
-                             : launch_tb_t<double, jk::MODE_UPDATE>(p, depth, (const double *)src, (double *)dst, nullptr, st);
-    return with_residual ? launch_tb_t<float, jk::MODE_BOTH>(p, depth, (const float *)src, (float *)dst, p->partial, st)
-                         : launch_tb_t<float, jk::MODE_UPDATE>(p, depth, (const float *)src, (float *)dst, nullptr, st);
-}
-
-// What one pass does with `left` iterations to go: the deepest compiled overlapped-wavefront
-// pass that fits and applies, else the two-step kernel, else a single step (needs current halos).
+// What the next pass does with `left` iterations to go.  The iterations are spread evenly over
+// the fewest passes the requested depth allows (10 iterations at depth 8 run as 5 + 5, not
+// 8 + 2: a pass costs little more for being deeper); below the shallowest overlapped-wavefront
+// depth the two-step kernel and single steps (which need current halos) take over.
 struct PassChoice { int depth; bool general; };
 
 PassChoice choose_pass(const jacobi_plan *p, int left)
 {
-    const int want = (int)(p->tblock < left ? p->tblock : left);
-    for (int d : TB_DEPTHS)
-        if (d <= want && tb_usable(p, d)) return {d, true};
-    if (want >= 2 && t2_usable(p)) return {2, false};
+    int maxd = (int)(p->tblock < left ? p->tblock : left);
+    if (maxd > jk::TB_MAX) maxd = jk::TB_MAX;
+    if (maxd > p->geo.th) maxd = p->geo.th;
+    if (maxd >= jk::TB_MIN) {
+        const int passes = (left + maxd - 1) / maxd;
+        int d = (left + passes - 1) / passes;
+        if (d < jk::TB_MIN) d = jk::TB_MIN;
+        if (tb_usable(p, d)) return {d, true};
+    }
+    if (maxd >= 2 && t2_usable(p)) return {2, false};
     return {1, false};
 }
 
@@ -360,9 +315,7 @@ int residual_common(jacobi_plan *p, void *grid, double *result_dev, hipStream_t 
     if (rc) return rc;
     rc = launch_exchange(p, grid, st);
     if (rc) return rc;
-    rc = p->lay.dtype == JACOBI_F64
-             ? launch_sweep_t<double, jk::MODE_RESIDUAL>(p, (const double *)grid, (double *)grid, p->partial, st)
-             : launch_sweep_t<float, jk::MODE_RESIDUAL>(p, (const float *)grid, (float *)grid, p->partial, st);
+    rc = launch_sweep(p, jk::MODE_RESIDUAL, grid, grid, p->partial, st);
     if (rc) return rc;
     double *out = result_dev ? result_dev : p->partial + nwg;
     hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, p->partial, (long long)nwg, out);

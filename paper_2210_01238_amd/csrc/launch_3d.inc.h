@@ -1,0 +1,48 @@
+// Dispatch over the compiled variants of sweep3d_kernel for one element type.
+// Included by launch_3d_f64.hip and launch_3d_f32.hip.  Streaming loads are never useful in
+// 3-D (every row is re-read as somebody's neighbour), so only the store bit of nt is honoured.
+#include "launchers.h"
+
+namespace jk {
+
+template <typename T>
+static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int nt, const LaunchArgs &a)
+{
+    const dim3 grid(a.nwg), block(WG);
+    const T *src = (const T *)a.src;
+    T *dst = (T *)a.dst;
+#define JK_L(MODE_, RW_, U_, NT_) \
+    hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+#define JK_NT(MODE_, RW_, U_)                 \
+    do {                                      \
+        if (nt & 2) JK_L(MODE_, RW_, U_, 2);  \
+        else        JK_L(MODE_, RW_, U_, 0);  \
+    } while (0)
+#define JK_U(MODE_, RW_)                      \
+    switch (unroll) {                         \
+    case 1: JK_NT(MODE_, RW_, 1); break;      \
+    case 2: JK_NT(MODE_, RW_, 2); break;      \
+    case 4: JK_NT(MODE_, RW_, 4); break;      \
+    default: return hipErrorInvalidValue;     \
+    }
+#define JK_RW(MODE_)                          \
+    switch (rows_per_wave) {                  \
+    case 1: JK_U(MODE_, 1); break;            \
+    case 2: JK_U(MODE_, 2); break;            \
+    case 4: JK_U(MODE_, 4); break;            \
+    default: return hipErrorInvalidValue;     \
+    }
+    switch (mode) {
+    case MODE_UPDATE: JK_RW(MODE_UPDATE); break;
+    case MODE_RESIDUAL: JK_RW(MODE_RESIDUAL); break;
+    case MODE_BOTH: JK_RW(MODE_BOTH); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef JK_RW
+#undef JK_U
+#undef JK_NT
+#undef JK_L
+    return hipGetLastError();
+}
+
+}  // namespace jk

@@ -1,0 +1,38 @@
+// Internal interface between the host API (jacobi.hip) and the translation units that hold
+// the compiled variants of the update kernels.  The variants are spread over several files
+// only so that they compile in parallel; each launcher picks the instantiation for its
+// arguments, launches it and returns hipGetLastError() (hipErrorInvalidValue if the requested
+// variant is not compiled).
+#pragma once
+#include "jacobi_kernels.h"
+
+namespace jk {
+
+struct LaunchArgs {
+    unsigned nwg;        // workgroups (grid size); block size is always WG
+    hipStream_t st;
+    Geo g;
+    StripParams sp;
+    const void *src;     // element type is given by the f64 flag of the call
+    void *dst;
+    double *partial;     // per-workgroup partial sums (residual modes), else unused
+};
+
+// single-step update / residual (mode: Mode; unroll 1,2,4,8,16; nt: 0 or 2)
+hipError_t launch_sweep2d_f64(int mode, int unroll, int nt, const LaunchArgs &a);
+hipError_t launch_sweep2d_f32(int mode, int unroll, int nt, const LaunchArgs &a);
+// rows_per_wave 1,2,4; unroll 1,2,4
+hipError_t launch_sweep3d_f64(int mode, int rows_per_wave, int unroll, int nt, const LaunchArgs &a);
+hipError_t launch_sweep3d_f32(int mode, int rows_per_wave, int unroll, int nt, const LaunchArgs &a);
+// two iterations per pass (8-row strips); mode MODE_UPDATE or MODE_BOTH
+constexpr int T2_ROWS = 8;
+hipError_t launch_t2(bool f64, int mode, const LaunchArgs &a);
+// TB_MIN..TB_MAX iterations per pass (overlapped wavefronts, 16-row strips)
+constexpr int TB_MIN = 4, TB_MAX = 8, TB_ROWS = 16;
+hipError_t launch_tb_d4(bool f64, int mode, const LaunchArgs &a);
+hipError_t launch_tb_d5(bool f64, int mode, const LaunchArgs &a);
+hipError_t launch_tb_d6(bool f64, int mode, const LaunchArgs &a);
+hipError_t launch_tb_d7(bool f64, int mode, const LaunchArgs &a);
+hipError_t launch_tb_d8(bool f64, int mode, const LaunchArgs &a);
+
+}  // namespace jk
