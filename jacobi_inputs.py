@@ -83,13 +83,16 @@ class Workload:
                         self.boundary, self.interior, self.seed)
 
 
-# The five workload shapes.  C3 is the one the throughput figure is quoted on.
+# The workload shapes.  C3 is the one the throughput figure is quoted on.
 WORKLOADS: Dict[str, Workload] = {
     "C1": Workload("C1", (256, 256), (1, 1), 100, 100, "top1", "zero", 0),
     "C2": Workload("C2", (4096, 4096), (4, 4), 1000, 100, "random01", "random01", 2),
     "C3": Workload("C3", (16384, 16384), (8, 8), 200, 10, "x2-y2", "random11", 3),
     "C4": Workload("C4", (512, 512, 512), (4, 4, 4), 100, 10, "random01", "zero", 4),
     "C5": Workload("C5", (8192, 8192), (64, 64), 500, 50, "x+y", "random01", 5),
+    # the one domain size the paper states for its 3-D proxy runs (Sec. VI-C: 1024 x 1024 x 768),
+    # cut into 128^3 blocks; data recipe as C4
+    "P1": Workload("P1", (768, 1024, 1024), (6, 8, 8), 100, 10, "random01", "zero", 6),
 }
 
 

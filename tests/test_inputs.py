@@ -53,5 +53,6 @@ def test_workload_table_matches_shapes():
     assert W["C3"].dims == (16384, 16384) and W["C3"].tiles == (8, 8) and W["C3"].iters == 200
     assert W["C4"].dims == (512,) * 3 and W["C4"].tiles == (4,) * 3
     assert W["C5"].tiles == (64, 64) and W["C5"].dims[0] // 64 == 128
+    assert W["P1"].dims == (768, 1024, 1024) and W["P1"].points == 1024 * 1024 * 768
     for w in W.values():
         assert all(d % t == 0 for d, t in zip(w.dims, w.tiles))

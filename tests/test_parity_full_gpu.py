@@ -115,3 +115,7 @@ def test_full_C4_512cube_4x4x4(H, oracle_mod):
 
 def test_full_C2_4096sq_4x4(H, oracle_mod):
     full_size_check(H, oracle_mod, "C2", few=10)
+
+
+def test_full_P1_paper_domain_1024x1024x768(H, oracle_mod):
+    full_size_check(H, oracle_mod, "P1", few=2)

@@ -334,3 +334,41 @@ def test_deep_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock):
     finally:
         r.close()
     check(out, res, ref, ref_res)
+
+
+def test_sweep_can_be_captured_in_a_hip_graph(H, oracle_mod):
+    """jacobi_sweep only enqueues kernels (no allocation, no memset, no synchronisation), so a
+    caller may record it into a HIP graph and replay it; every replay must equal the eager result."""
+    import torch
+    w = gen.WORKLOADS["C1"]
+    a = gen.generate(w)
+    ref10, _ = oracle_mod.run(a, 10)
+    ref30, _ = oracle_mod.run(a, 30)
+    for opts in (dict(), dict(tblock=8)):
+        r = H.JacobiRun(w.dims, w.tiles, **opts)
+        try:
+            r.load(a)
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                r.sweep(10)                       # eager, on the side stream (also warms up)
+            torch.cuda.current_stream().wait_stream(s)
+            torch.cuda.synchronize()
+            assert np.array_equal(r.fetch(), ref10)
+            # record 10 more iterations starting from the current buffer
+            src, dst = r.cur, r.other()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                fin = H.B.jacobi_sweep(r.plan, src.data_ptr(), dst.data_ptr(), 10,
+                                       int(torch.cuda.current_stream().cuda_stream))
+            assert fin == src.data_ptr()          # even count: result back in the source buffer
+            for k in range(2):                    # two replays with eager work in between
+                g.replay()
+                torch.cuda.synchronize()
+                got = r.fetch()
+                torch.cuda.synchronize()
+                exp, _ = oracle_mod.run(a, 20 + 10 * k)
+                assert np.array_equal(got, exp), (opts, k)
+            assert np.array_equal(r.fetch(), ref30)
+        finally:
+            r.close()
