@@ -189,7 +189,8 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  * Options (all int64).  Unknown key or out-of-range value -> EINVAL.
  *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
- *                    through; 0 = choose from the shape (default 0)
+ *                    through; 0 = choose from the shape: 8 rows / 16 planes for single steps,
+ *                    128 rows for blocked passes of depth >= 3 (default 0)
  *   "nontemporal"    0 | 2   2 = results are written with streaming (non-temporal) stores
  *                    (default 2).  Streaming loads were measured slower (border rows are
  *                    re-read from cache) and are not offered.  Blocked passes always stream.
@@ -201,10 +202,11 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
  *   "tblock"         1..8    temporal blocking depth: jacobi_sweep advances up to this many
- *                    iterations per pass over memory (2-D only).  Compiled pass depths are 8
- *                    and 4 (overlapped wavefronts; need tile width a multiple of 16 bytes and
- *                    >= 64 bytes, tile height >= depth), 2 (needs tiles >= 2 x 2) and 1; the
- *                    remaining iterations are covered greedily, deepest pass first.  Blocked
+ *                    iterations per pass over memory (2-D only).  The iterations of a call are
+ *                    spread evenly over the fewest passes the depth allows (10 iterations at
+ *                    depth 8 run as 5 + 5).  Passes of depth 3..8 need a tile width that is a
+ *                    multiple of 16 bytes and at least 64 bytes, and a tile height >= depth;
+ *                    depth 2 needs tiles >= 2 x 2; otherwise single steps are used.  Blocked
  *                    passes read the cells they need beyond a tile straight from the
  *                    neighbouring tiles, so the exchange is part of their loads and they leave
  *                    the halo cells alone.  Results are bit-identical for every depth

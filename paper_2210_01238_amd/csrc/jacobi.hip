@@ -178,20 +178,23 @@ int launch_t2(jacobi_plan *p, const void *src, void *dst, bool with_residual, hi
                           "two-step kernel launch");
 }
 
-// ---- general-depth temporal blocking (overlapped wavefronts) ------------------------------
-bool tb_usable(const jacobi_plan *p, int depth)
+// ---- pipelined temporal blocking (tall strips) ----------------------------------------------
+bool tp_usable(const jacobi_plan *p, int depth)
 {
     const Geo &g = p->geo;
     const int nv = 16 / (int)p->esize;
-    return depth >= jk::TB_MIN && depth <= jk::TB_MAX && g.ndim == 2 && g.tw % nv == 0 &&
+    return depth >= jk::TP_MIN && depth <= jk::TP_MAX && g.ndim == 2 && g.tw % nv == 0 &&
            g.tw >= jk::TB_GHOST_LANES * nv && g.th >= depth;
 }
 
-StripParams tb_strips(const jacobi_plan *p)
+StripParams tp_strips(const jacobi_plan *p)
 {
     const Geo &g = p->geo;
     StripParams sp;
-    sp.R = jk::TB_ROWS;
+    int R = (int)p->rows_per_strip;
+    if (R <= 0) R = 128;                       // run-in of 2*depth rows per strip: keep strips tall
+    if (R > g.th) R = g.th;
+    sp.R = R;
     sp.nseg = (int)ceil_div(g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
     sp.nblk = (int)ceil_div(g.th, sp.R);
     sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
@@ -200,44 +203,34 @@ StripParams tb_strips(const jacobi_plan *p)
     return sp;
 }
 
-int launch_tb(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
+int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
 {
-    const StripParams sp = tb_strips(p);
+    const StripParams sp = tp_strips(p);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
-    const bool f64 = p->lay.dtype == JACOBI_F64;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
-    hipError_t e = hipErrorInvalidValue;
-    switch (depth) {
-    case 4: e = jk::launch_tb_d4(f64, mode, a); break;
-    case 5: e = jk::launch_tb_d5(f64, mode, a); break;
-    case 6: e = jk::launch_tb_d6(f64, mode, a); break;
-    case 7: e = jk::launch_tb_d7(f64, mode, a); break;
-    case 8: e = jk::launch_tb_d8(f64, mode, a); break;
-    }
-    return launch_checked(e, "blocked-pass kernel launch");
+    return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp_f64(depth, mode, a) : jk::launch_tp_f32(depth, mode, a),
+                          "pipelined blocked-pass kernel launch");
 }
 
 // What the next pass does with `left` iterations to go.  The iterations are spread evenly over
 // the fewest passes the requested depth allows (10 iterations at depth 8 run as 5 + 5, not
-// 8 + 2: a pass costs little more for being deeper); below the shallowest overlapped-wavefront
-// depth the two-step kernel and single steps (which need current halos) take over.
-struct PassChoice { int depth; bool general; };
+// 8 + 2: a pass costs little more for being deeper).  kernel: 0 single step (needs current
+// halos), 1 two-step kernel, 2 pipelined kernel (depths 3..8).
+struct PassChoice { int depth; int kernel; };
 
 PassChoice choose_pass(const jacobi_plan *p, int left)
 {
     int maxd = (int)(p->tblock < left ? p->tblock : left);
-    if (maxd > jk::TB_MAX) maxd = jk::TB_MAX;
-    if (maxd > p->geo.th) maxd = p->geo.th;
-    if (maxd >= jk::TB_MIN) {
+    if (maxd > jk::TP_MAX) maxd = jk::TP_MAX;
+    if (maxd >= 2) {
         const int passes = (left + maxd - 1) / maxd;
-        int d = (left + passes - 1) / passes;
-        if (d < jk::TB_MIN) d = jk::TB_MIN;
-        if (tb_usable(p, d)) return {d, true};
+        const int d = (left + passes - 1) / passes;
+        if (tp_usable(p, d)) return {d, 2};
+        if (t2_usable(p)) return {2, 1};
     }
-    if (maxd >= 2 && t2_usable(p)) return {2, false};
-    return {1, false};
+    return {1, 0};
 }
 
 template <typename T, int FMODE>
@@ -463,9 +456,9 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     const PassChoice first = choose_pass(plan, iters);
     int64_t nwg_res = 0;
     if (residual_in_dev) {
-        const int64_t strips = first.depth == 1 ? make_config(plan, jk::MODE_BOTH).sp.nstrips
-                               : first.general  ? tb_strips(plan).nstrips
-                                                : t2_strips(plan).nstrips;
+        const int64_t strips = first.kernel == 0   ? make_config(plan, jk::MODE_BOTH).sp.nstrips
+                               : first.kernel == 1 ? t2_strips(plan).nstrips
+                                                   : tp_strips(plan).nstrips;
         nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
         int rc = ensure_partials(plan, nwg_res + 1);
         if (rc) return rc;
@@ -486,9 +479,9 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         }
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
-        if (pc.depth == 1)   rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
-        else if (pc.general) rc = launch_tb(plan, pc.depth, src, dst, with_res, st);
-        else                 rc = launch_t2(plan, src, dst, with_res, st);
+        if (pc.kernel == 0)      rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
+        else if (pc.kernel == 1) rc = launch_t2(plan, src, dst, with_res, st);
+        else                     rc = launch_tp(plan, pc.depth, src, dst, with_res, st);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));

@@ -477,41 +477,46 @@ __global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
 }
 
 // ------------------------------------------------------------------------------------
-// 2-D, TB time steps per pass over memory (temporal blocking, general depth).
+// 2-D, TB time steps per pass over memory (temporal blocking, depths 3..8), pipelined down
+// the rows.
 //
 // Overlapped wavefronts: a wavefront still loads 64 lanes x 16 bytes per row, but only its
 // middle 56 lanes (896 bytes = 7 whole cache lines) own output columns; the 4 lanes (64 bytes)
 // on either side are ghost lanes that carry the neighbouring columns through the time steps
-// and are recomputed by the neighbouring wavefront.  A strip loads RT + 2*TB rows of u(t),
-// advances them in registers level by level (each level is valid on one row and one column
-// less on every side), and stores RT rows of u(t+TB).  No halo cells are needed or written:
+// and are recomputed by the neighbouring wavefront (a level is valid on one column less per
+// side than the level before, so TB <= ghost width).  No halo cells are needed or written:
 // columns and rows beyond the tile are read from the neighbouring tiles (diagonal ones
-// included).  Dirichlet ring cells come from the boundary tiles' halo cells and are frozen:
-// every level keeps their value, which also stops garbage from beyond the ring.
-// Each value is formed by the single-step expression, so TB steps here are bit-identical to
-// TB single steps.  Needs tw a multiple of the vector width, tw >= ghost width, th >= TB.
+// included); Dirichlet ring cells come from the boundary tiles' halo cells.
+//
+// A strip is tall (sp.R rows) and is processed as a software pipeline: every step loads ONE
+// new row of u(t) and advances each of the TB levels by one row - level l produces its row
+// (rho - l) from the three rows (rho-l-1, rho-l, rho-l+1) of level l-1, the last of which the
+// level before has just produced.  Only two rows per level stay in registers (2*TB vectors),
+// whatever the strip height, and the only redundant work is the 2*TB-row run-in of a strip.
+// Ring cells keep their value by copying the centre value (the same cell one level down),
+// under wave-uniform branches that ordinary wavefronts skip.  Every value is formed by the
+// single-step expression, so a pass is bit-identical to TB single steps.
+// Needs tw a multiple of the vector width, tw >= ghost width, th >= TB.
 // ------------------------------------------------------------------------------------
 constexpr int TB_GHOST_LANES = 4;                       // 64 bytes on either side
 constexpr int TB_OWN_LANES = WAVE - 2 * TB_GHOST_LANES; // 56 lanes = 896 bytes
 
-template <typename T, int MODE, int TB, int RT, int NT, int MINW>
-__global__ __launch_bounds__(WG, MINW) void sweep2d_tb_kernel(Geo g, StripParams sp,
-                                                        const T *__restrict__ src, T *__restrict__ dst,
-                                                        double *__restrict__ partial)
+template <typename T, int MODE, int TB, int PF, int MINW>
+__global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams sp,
+                                                              const T *__restrict__ src, T *__restrict__ dst,
+                                                              double *__restrict__ partial)
 {
     using V = typename Vec<T>::type;
     constexpr int NV = Vec<T>::N;
-    constexpr int GH = TB_GHOST_LANES * NV;     // ghost columns per side
-    constexpr int SEGW = TB_OWN_LANES * NV;     // columns a wavefront owns
-    constexpr int NR = RT + 2 * TB;             // rows held in registers
+    constexpr int GH = TB_GHOST_LANES * NV;
+    constexpr int SEGW = TB_OWN_LANES * NV;
     static_assert(TB >= 1 && TB <= GH, "a level loses one ghost column per side");
+    static_assert(PF >= 2 && PF % 2 == 0, "the two-row windows swap roles every step");
     static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
     __shared__ double red[WAVES_PER_WG];
 
     const int lane = threadIdx.x % WAVE;
-    // the wavefront index is uniform: saying so keeps the strip decode and all row offsets in
-    // scalar registers, which this register-hungry kernel needs
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);   // uniform: keeps row math scalar
     const long long lwg = xcd_logical_wg(sp.xcd_chunk);
     const long long s = lwg * WAVES_PER_WG + wave;
     double acc = 0.0;
@@ -522,15 +527,12 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tb_kernel(Geo g, StripParams
         const int rem = (int)(s - (long long)t * per_tile);
         const int rb = rem / sp.nseg, seg = rem - rb * sp.nseg;
         const int ty = t / g.Tx, tx = t - ty * g.Tx;
-        const int r0 = 1 + rb * RT;
-        const int r1 = min(g.th, r0 + RT - 1);
+        const int r0 = 1 + rb * sp.R;
+        const int r1 = min(g.th, r0 + sp.R - 1);
 
         // ---- columns of this lane (tile-relative; may lie in a neighbouring tile or on the ring)
         const int c0 = seg * SEGW - GH + lane * NV;
-        int txx = tx, cc = c0;
-        // kind: 0 cells of some tile (vector load), 1 last component is the W ring column,
-        //       2 first component is the E ring column, 3 nothing there
-        int kind = 0;
+        int txx = tx, cc = c0, kind = 0;   // 0 tile cells, 1 W ring in last component, 2 E ring in first, 3 nothing
         if (c0 < 0) {
             if (tx > 0) { txx = tx - 1; cc = g.tw + c0; }
             else kind = c0 == -NV ? 1 : 3;
@@ -539,40 +541,29 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tb_kernel(Geo g, StripParams
             else if (tx < g.Tx - 1) { txx = tx + 1; cc = c0 - g.tw; }
             else kind = c0 == g.tw ? 2 : 3;
         }
-        // per-lane address parts, the same for every row (relative to tile (row's ty, tx), column 0)
         const long long lane_off = kind == 0 ? (long long)(txx - tx) * g.tile_stride + cc : 0;
         const long long halo_base = kind == 2 ? g.xoff + g.hpitch : g.xoff;
-        // Only the two wavefronts of a domain row that hold a ring column have ring lanes.
         const bool ring_lane = kind == 1 || kind == 2;
         const bool wave_has_ring = __any(ring_lane) != 0;
         const bool owner = lane >= TB_GHOST_LANES && lane < WAVE - TB_GHOST_LANES && c0 >= 0 && c0 < g.tw;
+        const bool top_ring = ty == 0, bottom_ring = ty == g.Ty - 1;
+        T *tdst = dst + (long long)t * g.tile_stride;
 
-        // ---- rows r0-TB .. r0+RT+TB-1 (index q), followed into the tiles above / below
-        // row_ref: grid offset of tile (row's ty, tx), row inside that tile, and whether it is a ring row
-        auto row_ref = [&](int q, long long &row_off, int &rr) -> bool {
-            int rho = r0 - TB + q, tyy = ty;
-            bool ring = false;
+        // u(t) row rho (relative to this tile; clamped to [-(TB), th+1+TB] and onto the ring)
+        auto load_row = [&](int rho) -> V {
+            int tyy = ty, rr;
+            rho = min(rho, g.th + TB);
             if (rho <= 0) {
-                if (ty > 0) { tyy = ty - 1; rr = g.th + rho; }
-                else { rr = 0; ring = true; }
+                if (!top_ring) { tyy = ty - 1; rr = g.th + rho; }
+                else rr = 0;
             } else if (rho > g.th) {
-                rho = min(rho, g.th + TB);       // ragged last strip: rows past the rim are not needed
-                if (ty < g.Ty - 1) { tyy = ty + 1; rr = rho - g.th; }
-                else { rr = g.th + 1; ring = true; }
+                if (!bottom_ring) { tyy = ty + 1; rr = rho - g.th; }
+                else rr = g.th + 1;
             } else rr = rho;
-            row_off = ((long long)tyy * g.Tx + tx) * g.tile_stride;
-            return ring;
-        };
-        // One 16-byte load per lane and row, whatever the lane holds.  Address = uniform row part +
-        // per-lane part.  Ring lanes load the aligned vector of the dense x-halo array that holds
-        // their cell and move it into place; "nothing there" lanes load some valid cell, unused.
-        auto load_row = [&](int q) -> V {
-            long long row_off;
-            int rr;
-            (void)row_ref(q, row_off, rr);
-            const long long cell_off = (long long)rr * g.pitch + lane_off;                  // kinds 0, 3
-            const long long halo_off = halo_base + (rr & ~(NV - 1));                        // kinds 1, 2
-            V v = ldv<(NT & 1) != 0>((const V *)(src + row_off + (ring_lane ? halo_off : cell_off)));
+            const long long row_off = ((long long)tyy * g.Tx + tx) * g.tile_stride;
+            const long long cell_off = (long long)rr * g.pitch + lane_off;
+            const long long halo_off = halo_base + (rr & ~(NV - 1));
+            V v = *(const V *)(src + row_off + (ring_lane ? halo_off : cell_off));
             if (wave_has_ring && ring_lane) {
                 const T rv = vec_pick<T, NV>(v, rr & (NV - 1));
                 v = V(0);
@@ -581,80 +572,61 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tb_kernel(Geo g, StripParams
             return v;
         };
 
-        V a[NR];
-        bool strip_has_ring_row = false;
+        V w[TB][2];                      // per level l (0..TB-1): the two newest rows, roles swap each step
 #pragma unroll
-        for (int q = 0; q < NR; ++q) {
-            long long ro;
-            int rr;
-            strip_has_ring_row |= row_ref(q, ro, rr);
-            a[q] = load_row(q);
-        }
-        const bool needs_fixup = wave_has_ring || strip_has_ring_row;   // wave-uniform, rare
+        for (int l = 0; l < TB; ++l) w[l][0] = w[l][1] = V(0);
 
-        // ---- residual of u(t) on the owned cells (its own small loop: folding it into the first
-        // level below costs that loop ~90 registers and the kernel its occupancy)
-        if constexpr (MODE == MODE_BOTH) {
+        const int nsteps = (r1 - r0 + 1) + 2 * TB;          // rows rho = r0-TB .. r1+TB
+        const int nblocks = (nsteps + PF - 1) / PF;
+        V cur[PF], nxt[PF];
 #pragma unroll
-            for (int o = 0; o < RT; ++o) {
-                const int q = TB + o;
-                const V c = a[q];
-                const T left = from_prev_lane(c[NV - 1], T(0));
-                const T right = from_next_lane(c[0], T(0));
-                if (r0 + o <= r1 && owner) {
+        for (int u = 0; u < PF; ++u) cur[u] = load_row(r0 - TB + u);
+
+        for (int b = 0; b < nblocks; ++b) {
 #pragma unroll
-                    for (int j = 0; j < NV; ++j) {
-                        const T w = j == 0 ? left : c[j - 1];
-                        const T e = j == NV - 1 ? right : c[j + 1];
-                        const T res = ((w + e) + (a[q - 1][j] + a[q + 1][j])) - Coef<T>::four * c[j];
-                        const double rd = (double)res;
-                        acc += rd * rd;
+            for (int u = 0; u < PF; ++u) nxt[u] = load_row(r0 - TB + (b + 1) * PF + u);
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int q = b * PF + u;
+                const int rho = r0 - TB + q;             // row of u(t) entering the pipeline
+                const int p = u & 1;                     // slot holding the OLDER row of every level
+                V down = cur[u];
+#pragma unroll
+                for (int l = 1; l <= TB; ++l) {
+                    const V up = w[l - 1][p], c = w[l - 1][1 - p];
+                    const int row = rho - l;             // the row this level produces
+                    V nw;
+                    if ((top_ring && row == 0) || (bottom_ring && row == g.th + 1)) {
+                        nw = c;                          // Dirichlet row: keeps its values
+                    } else {
+                        const T left = from_prev_lane(c[NV - 1], T(0));
+                        const T right = from_next_lane(c[0], T(0));
+#pragma unroll
+                        for (int j = 0; j < NV; ++j) {
+                            const T we = (j == 0 ? left : c[j - 1]) + (j == NV - 1 ? right : c[j + 1]);
+                            const T sn = up[j] + down[j];
+                            nw[j] = Coef<T>::quarter * (we + sn);
+                            if constexpr (MODE == MODE_BOTH) {
+                                if (l == 1 && row >= r0 && row <= r1 && owner) {
+                                    const T res = (we + sn) - Coef<T>::four * c[j];
+                                    const double rd = (double)res;
+                                    acc += rd * rd;
+                                }
+                            }
+                        }
+                        if (wave_has_ring && ring_lane) {   // Dirichlet column cell keeps its value
+                            if (kind == 1) nw[NV - 1] = c[NV - 1]; else nw[0] = c[0];
+                        }
                     }
+                    w[l - 1][p] = down;                  // the older row is dead: its slot takes the newest
+                    down = nw;
                 }
+                const int orow = rho - TB;               // `down` is now u(t+TB) of this row
+                if (q >= 2 * TB && orow <= r1 && owner)
+                    __builtin_nontemporal_store(down, (V *)(tdst + main_off(g, 0, orow, c0)));
             }
-        }
-
-        // ---- TB levels in place; level l is valid on rows [l, NR-l) and loses a column per side.
-        // Ring cells must keep their value; the update overwrites them like any other cell, and the
-        // few wavefronts that hold ring cells load them again after every level.
 #pragma unroll
-        for (int l = 1; l <= TB; ++l) {
-            V up = a[l - 1];                     // old value of the row above the one being updated
-#pragma unroll
-            for (int q = l; q < NR - l; ++q) {
-                const V c = a[q];
-                const T left = from_prev_lane(c[NV - 1], T(0));
-                const T right = from_next_lane(c[0], T(0));
-                V nw;
-#pragma unroll
-                for (int j = 0; j < NV; ++j) {
-                    const T w = j == 0 ? left : c[j - 1];
-                    const T e = j == NV - 1 ? right : c[j + 1];
-                    const T we = w + e;
-                    const T sn = up[j] + a[q + 1][j];
-                    nw[j] = Coef<T>::quarter * (we + sn);
-                }
-                a[q] = nw;
-                up = c;
-            }
-            if (needs_fixup && l < TB) {
-#pragma unroll
-                for (int q = l; q < NR - l; ++q) {
-                    long long ro;
-                    int rr;
-                    const bool ring = row_ref(q, ro, rr);
-                    if (ring) a[q] = load_row(q);                       // whole ring row
-                    else if (wave_has_ring && ring_lane) a[q] = load_row(q);   // ring column cells
-                }
-            }
-        }
-
-        // ---- store u(t+TB): rows r0..r1, owned lanes
-        if (owner) {
-            T *tdst = dst + (long long)t * g.tile_stride;
-#pragma unroll
-            for (int o = 0; o < RT; ++o)
-                if (r0 + o <= r1) stv<(NT & 2) != 0>((V *)(tdst + main_off(g, 0, r0 + o, c0)), a[TB + o]);
+            for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
         }
     }
     if constexpr (MODE == MODE_BOTH) {

@@ -1,0 +1,39 @@
+// Dispatch over the depths of the pipelined temporal-blocking kernel (sweep2d_tp_kernel) for
+// one element type.  Included by launch_tp_f64.hip and launch_tp_f32.hip.
+#include "launchers.h"
+
+namespace jk {
+
+template <typename T>
+static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
+{
+    const dim3 grid(a.nwg), block(WG);
+    const T *src = (const T *)a.src;
+    T *dst = (T *)a.dst;
+    // Template arguments after the depth: rows loaded ahead (4), and the occupancy the compiler
+    // must fit in wavefronts per SIMD - the largest that compiles without register spills
+    // (fp64: depth 8 needs 158 VGPRs, depth 6 126; the fp32 variants need one step more).
+    constexpr bool F32 = sizeof(T) == 4;
+#define JK_MINW(TB_) (F32 ? ((TB_) >= 7 ? 2 : (TB_) >= 5 ? 3 : 4) : ((TB_) >= 7 ? 3 : 4))
+#define JK_L(MODE_, TB_) \
+    hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+#define JK_D(MODE_)                         \
+    switch (depth) {                        \
+    case 3: JK_L(MODE_, 3); break;          \
+    case 4: JK_L(MODE_, 4); break;          \
+    case 5: JK_L(MODE_, 5); break;          \
+    case 6: JK_L(MODE_, 6); break;          \
+    case 7: JK_L(MODE_, 7); break;          \
+    case 8: JK_L(MODE_, 8); break;          \
+    default: return hipErrorInvalidValue;   \
+    }
+    if (mode == MODE_UPDATE) { JK_D(MODE_UPDATE) }
+    else if (mode == MODE_BOTH) { JK_D(MODE_BOTH) }
+    else return hipErrorInvalidValue;
+#undef JK_D
+#undef JK_L
+#undef JK_MINW
+    return hipGetLastError();
+}
+
+}  // namespace jk

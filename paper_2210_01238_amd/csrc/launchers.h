@@ -27,12 +27,9 @@ hipError_t launch_sweep3d_f32(int mode, int rows_per_wave, int unroll, int nt, c
 // two iterations per pass (8-row strips); mode MODE_UPDATE or MODE_BOTH
 constexpr int T2_ROWS = 8;
 hipError_t launch_t2(bool f64, int mode, const LaunchArgs &a);
-// TB_MIN..TB_MAX iterations per pass (overlapped wavefronts, 16-row strips)
-constexpr int TB_MIN = 4, TB_MAX = 8, TB_ROWS = 16;
-hipError_t launch_tb_d4(bool f64, int mode, const LaunchArgs &a);
-hipError_t launch_tb_d5(bool f64, int mode, const LaunchArgs &a);
-hipError_t launch_tb_d6(bool f64, int mode, const LaunchArgs &a);
-hipError_t launch_tb_d7(bool f64, int mode, const LaunchArgs &a);
-hipError_t launch_tb_d8(bool f64, int mode, const LaunchArgs &a);
+// TP_MIN..TP_MAX iterations per pass, pipelined down tall strips (overlapped wavefronts)
+constexpr int TP_MIN = 3, TP_MAX = 8;
+hipError_t launch_tp_f64(int depth, int mode, const LaunchArgs &a);
+hipError_t launch_tp_f32(int depth, int mode, const LaunchArgs &a);
 
 }  // namespace jk

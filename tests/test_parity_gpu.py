@@ -306,8 +306,9 @@ def test_fused_residual_schedule_equals_separate(H, oracle_mod, tblock):
     check(out, res, ref, ref_res)
 
 
-@pytest.mark.parametrize("opts", [dict(tblock=3), dict(tblock=4), dict(tblock=6), dict(tblock=8), dict(tblock=5), dict(tblock=7),
-                                  dict(tblock=8, xcd_chunk=1), dict(tblock=4, nontemporal=0)])
+@pytest.mark.parametrize("opts", [dict(tblock=d) for d in (3, 4, 5, 6, 7, 8)] +
+                         [dict(tblock=8, xcd_chunk=1), dict(tblock=4, nontemporal=0), dict(tblock=8, rows_per_strip=16),
+                          dict(tblock=5, rows_per_strip=7), dict(tblock=8, rows_per_strip=4096)])
 @pytest.mark.parametrize("dims,tiles,iters,every", T2_CASES + [
     ((64, 64), (8, 8), 19, 19),            # 8x8 tiles: ghost columns span exactly one neighbour tile
     ((48, 224), (3, 2), 17, 4),            # tw = 112: exactly one wavefront of owned columns
@@ -320,7 +321,7 @@ def test_deep_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, ite
     check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
 
 
-@pytest.mark.parametrize("tblock", [3, 4, 8])
+@pytest.mark.parametrize("tblock", [3, 4, 5, 6, 7, 8])
 def test_deep_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock):
     a = random_padded((96, 256), dtype=np.float32, seed=7)
     check(*run_case(H, oracle_mod, a, (3, 2), 21, 5, tblock=tblock))
