@@ -93,6 +93,9 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
         // The read-only residual pass has no writes to keep apart from its reads and prefers
         // taller strips (fewer border re-reads): 16 rows, all in flight.
         R = d3 ? 16 : mode == jk::MODE_RESIDUAL ? 16 : 8;
+        // mid-sized 2-D grids: at 8 rows a 4096^2 grid gives each CU only ~3 rounds of workgroups
+        // and the last round runs half empty; 4-row strips measure 8 % faster there
+        if (!d3 && mode != jk::MODE_RESIDUAL && (int64_t)ceil_div(extent, R) * lanes_of_work < 24576) R = 4;
         while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < 4096) R /= 2;
     }
     if (R > extent) R = extent;
