@@ -205,7 +205,7 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *                    iterations per pass over memory (2-D only).  The iterations of a call are
  *                    spread evenly over the fewest passes the depth allows (10 iterations at
  *                    depth 8 run as 5 + 5).  Passes of depth 3..8 need a tile width that is a
- *                    multiple of 16 bytes and at least 64 bytes, and a tile height >= depth;
+ *                    multiple of 16 bytes and a tile height >= depth;
  *                    depth 2 needs tiles >= 2 x 2; otherwise single steps are used.  Blocked
  *                    passes read the cells they need beyond a tile straight from the
  *                    neighbouring tiles, so the exchange is part of their loads and they leave

@@ -186,21 +186,27 @@ bool tp_usable(const jacobi_plan *p, int depth)
 {
     const Geo &g = p->geo;
     const int nv = 16 / (int)p->esize;
-    return depth >= jk::TP_MIN && depth <= jk::TP_MAX && g.ndim == 2 && g.tw % nv == 0 &&
-           g.tw >= jk::TB_GHOST_LANES * nv && g.th >= depth;
+    return depth >= jk::TP_MIN && depth <= jk::TP_MAX && g.ndim == 2 && g.tw % nv == 0 && g.th >= depth &&
+           (int64_t)g.Tx * g.tw < 0x7fffffffLL;
 }
 
 StripParams tp_strips(const jacobi_plan *p)
 {
     const Geo &g = p->geo;
     StripParams sp;
+    // column segments run along a whole row of tiles; strips = rows of tiles x row blocks x segments
+    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
     int R = (int)p->rows_per_strip;
-    if (R <= 0) R = 128;                       // run-in of 2*depth rows per strip: keep strips tall
+    if (R <= 0) {
+        // every strip pays a run-in of 2*depth rows, so strips should be tall - but not so tall
+        // that there are fewer than ~4 workgroups per CU to run
+        R = 128;
+        while (R > 8 && (int64_t)g.Ty * sp.nseg * ceil_div(g.th, R) < 4096) R /= 2;
+    }
     if (R > g.th) R = g.th;
     sp.R = R;
-    sp.nseg = (int)ceil_div(g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
     sp.nblk = (int)ceil_div(g.th, sp.R);
-    sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
+    sp.nstrips = (int64_t)g.Ty * sp.nseg * sp.nblk;
     sp.fused = 0;
     sp.xcd_chunk = (int)p->xcd_chunk;
     return sp;

@@ -484,9 +484,11 @@ __global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
 // middle 56 lanes (896 bytes = 7 whole cache lines) own output columns; the 4 lanes (64 bytes)
 // on either side are ghost lanes that carry the neighbouring columns through the time steps
 // and are recomputed by the neighbouring wavefront (a level is valid on one column less per
-// side than the level before, so TB <= ghost width).  No halo cells are needed or written:
-// columns and rows beyond the tile are read from the neighbouring tiles (diagonal ones
-// included); Dirichlet ring cells come from the boundary tiles' halo cells.
+// side than the level before, so TB <= ghost width).  The 896-byte segments are laid out along
+// a whole ROW OF TILES, not per tile, so narrow tiles cost nothing: a wavefront's lanes simply
+// address whichever tile their column falls in.  No halo cells are needed or written: rows
+// beyond the tile are read from the tiles above / below; Dirichlet ring cells come from the
+// boundary tiles' halo cells.
 //
 // A strip is tall (sp.R rows) and is processed as a software pipeline: every step loads ONE
 // new row of u(t) and advances each of the TB levels by one row - level l produces its row
@@ -496,7 +498,7 @@ __global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
 // Ring cells keep their value by copying the centre value (the same cell one level down),
 // under wave-uniform branches that ordinary wavefronts skip.  Every value is formed by the
 // single-step expression, so a pass is bit-identical to TB single steps.
-// Needs tw a multiple of the vector width, tw >= ghost width, th >= TB.
+// Needs tw a multiple of the vector width and th >= TB.
 // ------------------------------------------------------------------------------------
 constexpr int TB_GHOST_LANES = 4;                       // 64 bytes on either side
 constexpr int TB_OWN_LANES = WAVE - 2 * TB_GHOST_LANES; // 56 lanes = 896 bytes
@@ -522,32 +524,32 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
     double acc = 0.0;
 
     if (s < sp.nstrips) {
-        const int per_tile = sp.nblk * sp.nseg;
-        const int t = (int)(s / per_tile);
-        const int rem = (int)(s - (long long)t * per_tile);
+        // strip = (row of tiles ty, row block rb, column segment seg); the segments run across the
+        // whole row of tiles, so a wavefront's lanes may lie in two (or more) neighbouring tiles
+        const int per_tyrow = sp.nblk * sp.nseg;
+        const int ty = (int)(s / per_tyrow);
+        const int rem = (int)(s - (long long)ty * per_tyrow);
         const int rb = rem / sp.nseg, seg = rem - rb * sp.nseg;
-        const int ty = t / g.Tx, tx = t - ty * g.Tx;
         const int r0 = 1 + rb * sp.R;
         const int r1 = min(g.th, r0 + sp.R - 1);
 
-        // ---- columns of this lane (tile-relative; may lie in a neighbouring tile or on the ring)
-        const int c0 = seg * SEGW - GH + lane * NV;
-        int txx = tx, cc = c0, kind = 0;   // 0 tile cells, 1 W ring in last component, 2 E ring in first, 3 nothing
-        if (c0 < 0) {
-            if (tx > 0) { txx = tx - 1; cc = g.tw + c0; }
-            else kind = c0 == -NV ? 1 : 3;
-        } else if (c0 >= g.tw) {
-            if (c0 >= g.tw + GH) kind = 3;
-            else if (tx < g.Tx - 1) { txx = tx + 1; cc = c0 - g.tw; }
-            else kind = c0 == g.tw ? 2 : 3;
-        }
-        const long long lane_off = kind == 0 ? (long long)(txx - tx) * g.tile_stride + cc : 0;
-        const long long halo_base = kind == 2 ? g.xoff + g.hpitch : g.xoff;
+        // ---- columns of this lane, counted along the row of tiles (0 .. Tx*tw-1; -1 and Tx*tw are
+        // the Dirichlet ring).  kind: 0 cells of some tile, 1 W ring in the last component,
+        // 2 E ring in the first component, 3 nothing there
+        const int wrow = g.Tx * g.tw;
+        const int gc = seg * SEGW - GH + lane * NV;
+        int kind = 0, txx = 0, cc = 0;
+        if (gc < 0) kind = gc == -NV ? 1 : 3;
+        else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
+        else { txx = gc / g.tw; cc = gc - txx * g.tw; }
+        // per-lane address parts, the same for every row (relative to tile (row's ty, 0), row 0)
+        const long long lane_off = kind == 0 ? (long long)txx * g.tile_stride + cc : 0;
+        const long long halo_base = kind == 2 ? (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch : g.xoff;
         const bool ring_lane = kind == 1 || kind == 2;
         const bool wave_has_ring = __any(ring_lane) != 0;
-        const bool owner = lane >= TB_GHOST_LANES && lane < WAVE - TB_GHOST_LANES && c0 >= 0 && c0 < g.tw;
+        const bool owner = lane >= TB_GHOST_LANES && lane < WAVE - TB_GHOST_LANES && kind == 0;
         const bool top_ring = ty == 0, bottom_ring = ty == g.Ty - 1;
-        T *tdst = dst + (long long)t * g.tile_stride;
+        T *tdst = dst + (long long)ty * g.Tx * g.tile_stride + lane_off;   // this lane's cells, row 0
 
         // u(t) row rho (relative to this tile; clamped to [-(TB), th+1+TB] and onto the ring)
         auto load_row = [&](int rho) -> V {
@@ -560,7 +562,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                 if (!bottom_ring) { tyy = ty + 1; rr = rho - g.th; }
                 else rr = g.th + 1;
             } else rr = rho;
-            const long long row_off = ((long long)tyy * g.Tx + tx) * g.tile_stride;
+            const long long row_off = (long long)tyy * g.Tx * g.tile_stride;
             const long long cell_off = (long long)rr * g.pitch + lane_off;
             const long long halo_off = halo_base + (rr & ~(NV - 1));
             V v = *(const V *)(src + row_off + (ring_lane ? halo_off : cell_off));
@@ -623,7 +625,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                 }
                 const int orow = rho - TB;               // `down` is now u(t+TB) of this row
                 if (q >= 2 * TB && orow <= r1 && owner)
-                    __builtin_nontemporal_store(down, (V *)(tdst + main_off(g, 0, orow, c0)));
+                    __builtin_nontemporal_store(down, (V *)(tdst + main_off(g, 0, orow, 0)));
             }
 #pragma unroll
             for (int u = 0; u < PF; ++u) cur[u] = nxt[u];

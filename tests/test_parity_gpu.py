@@ -314,7 +314,9 @@ def test_fused_residual_schedule_equals_separate(H, oracle_mod, tblock):
     ((48, 224), (3, 2), 17, 4),            # tw = 112: exactly one wavefront of owned columns
     ((40, 480), (2, 2), 16, 8),            # tw = 240: 3 column segments, last one ragged
     ((100, 128), (2, 1), 33, 11),          # th = 50: ragged last 16-row strip
-    ((34, 64), (1, 4), 9, 9),              # tw = 16: every lane of a wavefront beyond the first tiles is a neighbour's
+    ((34, 64), (1, 4), 9, 9),              # tw = 16: a wavefront's lanes span all four tiles of a row
+    ((24, 48), (3, 24), 10, 5),            # tw = 2 (one vector wide): 24 tiles under one wavefront
+    ((64, 640), (2, 5), 12, 6),            # 5 tiles of 128: segments of 112 columns straddle tile boundaries
 ])
 def test_deep_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every, opts):
     a = random_padded(dims, seed=sum(dims) + iters)
