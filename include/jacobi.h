@@ -26,7 +26,8 @@
  *   - "padded global array": (N+2) per dim; padded index 0 and N+1 hold the
  *     Dirichlet boundary ring, 1..N the interior.
  *   - "grid": the library's tile-major device buffer of jacobi_grid_bytes()
- *     bytes, 256-byte aligned, allocated and owned by the CALLER (device memory).
+ *     bytes, at least 16-byte (better 256-byte) aligned, allocated and owned by the
+ *     CALLER (device memory); a misaligned grid pointer is rejected with EINVAL.
  *     Its layout is described by jacobi_get_layout(); move data in and out with
  *     jacobi_scatter()/jacobi_gather().
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -52,8 +53,9 @@ enum jacobi_dtype { JACOBI_F64 = 0, JACOBI_F32 = 1 };
 
 enum jacobi_status {
     JACOBI_OK = 0,
-    JACOBI_EINVAL = 1,  /* null pointer, ndim not 2/3, dim <= 0, tiles <= 0, bad dtype,
-                           in == out, iters < 0, unknown option, tile too large */
+    JACOBI_EINVAL = 1,  /* null or misaligned pointer, ndim not 2/3, dim <= 0, tiles <= 0, bad
+                           dtype, in == out or overlapping, iters < 0, unknown option or value,
+                           tile too large */
     JACOBI_ENOTDIV = 2, /* dims[d] % tiles[d] != 0 */
     JACOBI_ENOMEM = 3,  /* host or device allocation failed */
     JACOBI_EHIP = 4     /* a HIP call failed; text in jacobi_last_error() */
@@ -144,7 +146,7 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  * After return, the inter-tile halos of the result are unspecified (stale or fresh
  * depending on the option); call halo_exchange if they are needed.
  * Asynchronous on `stream`; allocates nothing; does not synchronise.
- * Errors: EINVAL (null, in == out, iters < 0), EHIP.
+ * Errors: EINVAL (null, in == out or overlapping, misaligned, iters < 0), EHIP.
  */
 int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final);
 

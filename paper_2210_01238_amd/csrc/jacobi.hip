@@ -325,6 +325,17 @@ int residual_common(jacobi_plan *p, void *grid, double *result_dev, hipStream_t 
     return JACOBI_OK;
 }
 
+// Grid buffers must be 16-byte aligned (every lane moves 16 bytes at a time).
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+// Two grids of this plan overlap if their start addresses are closer than one grid.
+bool grids_overlap(const jacobi_plan *p, const void *a, const void *b)
+{
+    const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+    const uintptr_t d = x > y ? x - y : y - x;
+    return d < (uintptr_t)p->lay.grid_bytes;
+}
+
 int64_t *option_slot(jacobi_plan *p, const char *key)
 {
     if (!strcmp(key, "fused")) return &p->fused;
@@ -430,6 +441,7 @@ int jacobi_get_layout(const jacobi_plan *plan, jacobi_layout *layout)
 int jacobi_scatter(jacobi_plan *plan, const void *global_padded_dev, void *grid, void *stream)
 {
     if (!plan || !global_padded_dev || !grid) return fail(JACOBI_EINVAL, "NULL argument");
+    if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     return plan->lay.dtype == JACOBI_F64
                ? launch_sg_t<double, false>(plan, (const double *)global_padded_dev, (double *)grid, st)
@@ -439,6 +451,7 @@ int jacobi_scatter(jacobi_plan *plan, const void *global_padded_dev, void *grid,
 int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, void *stream)
 {
     if (!plan || !global_padded_dev || !grid) return fail(JACOBI_EINVAL, "NULL argument");
+    if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     return plan->lay.dtype == JACOBI_F64
                ? launch_sg_t<double, true>(plan, (const double *)grid, (double *)global_padded_dev, st)
@@ -448,6 +461,7 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
 int halo_exchange(jacobi_plan *plan, void *grid, void *stream)
 {
     if (!plan || !grid) return fail(JACOBI_EINVAL, "NULL argument");
+    if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     return launch_exchange(plan, grid, (hipStream_t)stream);
 }
 
@@ -514,6 +528,8 @@ int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream
 {
     if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
     if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (misaligned(in) || misaligned(out)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
+    if (grids_overlap(plan, in, out)) return fail(JACOBI_EINVAL, "in and out overlap");
     if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
     if (final) *final = in;
     if (iters == 0) return JACOBI_OK;
@@ -525,6 +541,8 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
 {
     if (!plan || !in || !out || !residual_in_dev) return fail(JACOBI_EINVAL, "NULL argument");
     if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (misaligned(in) || misaligned(out)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
+    if (grids_overlap(plan, in, out)) return fail(JACOBI_EINVAL, "in and out overlap");
     if (iters < 1) return fail(JACOBI_EINVAL, "iters must be >= 1");
     if (final) *final = in;
     return sweep_common(plan, in, out, iters, (hipStream_t)stream, final, residual_in_dev);
@@ -533,12 +551,14 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
 int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *stream)
 {
     if (!plan || !grid || !result_dev) return fail(JACOBI_EINVAL, "NULL argument");
+    if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     return residual_common(plan, grid, result_dev, (hipStream_t)stream);
 }
 
 int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void *stream)
 {
     if (!plan || !grid || !result_host) return fail(JACOBI_EINVAL, "NULL argument");
+    if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     int rc = residual_common(plan, grid, nullptr, st);
     if (rc) return rc;

@@ -80,9 +80,13 @@ def test_null_and_argument_errors_without_device(J):
     assert raw.jacobi_create(ctypes.byref(h), 2, d, None, 0) == 1 and not h.value
     p = J.jacobi_create((8, 8), (2, 2))
     # argument validation happens before any HIP call
+    nb = J.jacobi_grid_bytes(p)
     for call in (lambda: J.jacobi_sweep(p, 0, 256, 1), lambda: J.jacobi_sweep(p, 256, 256, 1),
-                 lambda: J.jacobi_sweep(p, 256, 512, -1), lambda: J.halo_exchange(p, 0),
-                 lambda: J.jacobi_sweep_residual(p, 256, 512, 0, 768), lambda: J.jacobi_sweep_residual(p, 256, 512, 1, 0),
+                 lambda: J.jacobi_sweep(p, 256, 256 + 8, 1),               # misaligned
+                 lambda: J.jacobi_sweep(p, 4096, 4096 + nb - 16, 1),       # overlapping
+                 lambda: J.halo_exchange(p, 264), lambda: J.residual_norm(p, 264, 256),
+                 lambda: J.jacobi_sweep(p, 256, 256 + nb, -1), lambda: J.halo_exchange(p, 0),
+                 lambda: J.jacobi_sweep_residual(p, 256, 256 + nb, 0, 768), lambda: J.jacobi_sweep_residual(p, 256, 256 + nb, 1, 0),
                  lambda: J.residual_norm(p, 0, 256), lambda: J.residual_norm(p, 256, 0),
                  lambda: J.jacobi_scatter(p, 0, 256), lambda: J.jacobi_gather(p, 256, 0),
                  lambda: J.jacobi_set_option(p, "no_such_option", 1),
@@ -94,7 +98,7 @@ def test_null_and_argument_errors_without_device(J):
         with pytest.raises(J.JacobiError) as e:
             call()
         assert e.value.code == 1
-    assert J.jacobi_sweep(p, 256, 512, 0) == 256          # zero iterations: no-op, result in `in`
+    assert J.jacobi_sweep(p, 256, 256 + nb, 0) == 256     # zero iterations: no-op, result in `in`
     J.jacobi_set_option(p, "fused", 0)
     assert J.jacobi_get_option(p, "fused") == 0
     assert J.jacobi_grid_bytes(None) == 0

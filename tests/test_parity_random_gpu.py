@@ -1,0 +1,73 @@
+"""Randomised GPU parity: seeded random shapes, tilings, iteration counts, residual cadences
+and option combinations, each compared bit for bit (fp64) with the CPU oracle.  The case list
+is fixed by the seed, so a failure names a reproducible case."""
+import numpy as np
+import pytest
+
+from parity_util import random_padded
+from test_parity_gpu import check, run_case
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2210_01238_amd import harness
+    return harness
+
+
+def divisors(n):
+    return [d for d in range(1, n + 1) if n % d == 0]
+
+
+def make_cases(ndim, count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        if ndim == 2:
+            dims = (int(rng.integers(1, 200)), int(rng.integers(1, 700)))
+        else:
+            dims = (int(rng.integers(1, 24)), int(rng.integers(1, 40)), int(rng.integers(1, 300)))
+        tiles = tuple(int(rng.choice(divisors(d))) for d in dims)
+        iters = int(rng.integers(1, 20))
+        every = int(rng.integers(1, iters + 1))
+        opts = dict(fused=int(rng.integers(0, 2)),
+                    rows_per_strip=int(rng.choice([0, 0, 1, 2, 3, 5, 8, 16, 33, 128])),
+                    unroll=int(rng.choice([0, 0, 1, 2, 4, 8] + ([16] if ndim == 2 else []))),
+                    xcd_chunk=int(rng.choice([0, 1, 2, 8, 8, 64])),
+                    nontemporal=int(rng.choice([0, 2, 2])))
+        if ndim == 2:
+            opts["tblock"] = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8]))
+        else:
+            opts["rows_per_wave"] = int(rng.choice([0, 1, 2, 4]))
+        fuse_res = bool(rng.integers(0, 2))
+        cases.append((dims, tiles, iters, every, opts, fuse_res))
+    return cases
+
+
+def run_random(H, oracle, case, seed):
+    dims, tiles, iters, every, opts, fuse_res = case
+    a = random_padded(dims, seed=seed)
+    if not fuse_res:
+        return check(*run_case(H, oracle, a, tiles, iters, every, **opts))
+    r = H.JacobiRun(dims, tiles, **opts)
+    try:
+        r.load(a)
+        res = r.run(iters, every, fuse_residual=True)
+        out = r.fetch()
+    finally:
+        r.close()
+    ref, ref_res = oracle.run(a, iters, every)
+    check(out, res, ref, ref_res)
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_cases(2, 120, 20221001))))
+def test_random_2d(H, oracle_mod, n, case):
+    run_random(H, oracle_mod, case, 1000 + n)
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_cases(3, 80, 20221002))))
+def test_random_3d(H, oracle_mod, n, case):
+    run_random(H, oracle_mod, case, 2000 + n)
