@@ -68,9 +68,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tblock", type=int, default=8, help="depth of the extra temporal-blocking measurement")
+    ap.add_argument("--tblock", type=int, default=8,
+                    help="depth limit of the extra temporal-blocking measurement (3-D passes advance 2 iterations)")
     ap.add_argument("--no-temporal-blocking", action="store_true",
-                    help="skip the extra measurement with two iterations per pass")
+                    help="skip the extra measurement with several iterations per pass")
     ap.add_argument("--separate-residual", action="store_true",
                     help="compute every residual with the stand-alone reduction pass")
     ap.add_argument("--option", action="append", default=[], help="key=value passed to jacobi_set_option")
@@ -152,7 +153,7 @@ def main() -> int:
 
     # optional temporal blocking (several iterations per pass over memory), reported separately
     tb = None
-    if len(w.dims) == 2 and not args.no_temporal_blocking:
+    if not args.no_temporal_blocking:
         run.set_option("tblock", args.tblock)
         tb_elapsed, tb_res = timed_steps()
         tb_ms, tb_n = profiled_steps()

@@ -96,6 +96,15 @@ __device__ __forceinline__ int dpp_from_next(int v, int fill)
 {
     return __builtin_amdgcn_update_dpp(fill, v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
 }
+// Same moves with the hardware's own zero fill for the lane that has no source (no fill register).
+__device__ __forceinline__ int dpp_from_prev_z(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x138 /* wave_shr:1 */, 0xf, 0xf, true);
+}
+__device__ __forceinline__ int dpp_from_next_z(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x130 /* wave_shl:1 */, 0xf, 0xf, true);
+}
 struct Int2 { int lo, hi; };
 __device__ __forceinline__ float from_prev_lane(float v, float fill)
 {
@@ -115,6 +124,26 @@ __device__ __forceinline__ double from_next_lane(double v, double fill)
 {
     const Int2 a = __builtin_bit_cast(Int2, v), f = __builtin_bit_cast(Int2, fill);
     const Int2 r = {dpp_from_next(a.lo, f.lo), dpp_from_next(a.hi, f.hi)};
+    return __builtin_bit_cast(double, r);
+}
+__device__ __forceinline__ float from_prev_lane_or_zero(float v)
+{
+    return __builtin_bit_cast(float, dpp_from_prev_z(__builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ float from_next_lane_or_zero(float v)
+{
+    return __builtin_bit_cast(float, dpp_from_next_z(__builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ double from_prev_lane_or_zero(double v)
+{
+    const Int2 a = __builtin_bit_cast(Int2, v);
+    const Int2 r = {dpp_from_prev_z(a.lo), dpp_from_prev_z(a.hi)};
+    return __builtin_bit_cast(double, r);
+}
+__device__ __forceinline__ double from_next_lane_or_zero(double v)
+{
+    const Int2 a = __builtin_bit_cast(Int2, v);
+    const Int2 r = {dpp_from_next_z(a.lo), dpp_from_next_z(a.hi)};
     return __builtin_bit_cast(double, r);
 }
 // Value held by lane `l` (a compile-time constant after unrolling), as a wave-uniform scalar.
@@ -792,6 +821,211 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
         }
     }
     if constexpr (MODE != MODE_UPDATE) {
+        const double tot = wg_sum(acc, red);
+        if (threadIdx.x == 0) partial[lwg] = tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// 3-D, TB time steps per pass over memory, pipelined along z (temporal blocking for the
+// 7-point update).  In x a wavefront owns the columns of its inner lanes and carries
+// ceil(TB / vector width) ghost lanes per side; segments are laid along a whole row of tiles
+// as in sweep2d_tp_kernel.  In y a wavefront owns RW rows and carries TB ghost rows on either
+// side (NRW = RW + 2*TB rows per plane; the neighbouring wavefronts recompute them).  In z a
+// strip of sp.R planes is a software pipeline: every step loads ONE new plane of u(t) (its NRW
+// rows) and advances each level by one plane.  Level l makes its plane (kappa - l) from planes
+// (kappa-l-1, kappa-l, kappa-l+1) of level l-1; per level two planes stay in registers.  Rows
+// are processed one after the other through all levels, so no third plane buffer is needed.
+// Ring cells (planes, rows, columns) keep their value by copying the centre value under
+// wave-uniform branches.  All addresses are a wave-uniform base plus one per-lane byte offset
+// that never changes.  Bit-identical to TB single steps.  Needs tw a multiple of the vector
+// width, th >= TB, td >= TB, and a row of tiles smaller than 2 GiB.
+// ------------------------------------------------------------------------------------
+template <typename T, int TB> struct Tp3dGeometry {
+    static constexpr int NV = Vec<T>::N;
+    static constexpr int GHOST_LANES = (TB + NV - 1) / NV;
+    static constexpr int OWN_LANES = WAVE - 2 * GHOST_LANES;
+    static constexpr int SEGW = OWN_LANES * NV;            // columns a wavefront owns
+};
+
+template <typename T, int MODE, int TB, int RW, int MINW>
+__global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams sp, int nrg,
+                                                              const T *__restrict__ src, T *__restrict__ dst,
+                                                              double *__restrict__ partial)
+{
+    using V = typename Vec<T>::type;
+    using G3 = Tp3dGeometry<T, TB>;
+    constexpr int NV = Vec<T>::N;
+    typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
+    constexpr int GL = G3::GHOST_LANES;
+    constexpr int GH = GL * NV;
+    constexpr int SEGW = G3::SEGW;
+    constexpr int NRW = RW + 2 * TB;
+    static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
+    __shared__ double red[WAVES_PER_WG];
+
+    const int lane = threadIdx.x % WAVE;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const long long lwg = xcd_logical_wg(sp.xcd_chunk);
+    const long long s = lwg * WAVES_PER_WG + wave;
+    double acc = 0.0;
+
+    if (s < sp.nstrips) {
+        // strip = (tz, ty) row of tiles -> plane block -> row group -> column segment
+        const long long per_tilerow = (long long)sp.nblk * nrg * sp.nseg;
+        const int tr = (int)(s / per_tilerow);
+        int rem = (int)(s - (long long)tr * per_tilerow);
+        const int kb = rem / (nrg * sp.nseg);
+        rem -= kb * nrg * sp.nseg;
+        const int rg = rem / sp.nseg, seg = rem - rg * sp.nseg;
+        const int tz = tr / g.Ty, ty = tr - tz * g.Ty;
+        const int k0 = 1 + kb * sp.R, k1 = min(g.td, k0 + sp.R - 1);
+        const int i0 = 1 + rg * RW;
+        const long long tilerow = (long long)g.Tx * g.tile_stride;     // elements in one row of tiles
+
+        // ---- columns of this lane along the row of tiles
+        const int wrow = g.Tx * g.tw;
+        const int gc = seg * SEGW - GH + lane * NV;
+        int kind = 0, txx = 0, cc = 0;   // 0 tile cells, 1 W ring in last component, 2 E ring in first, 3 nothing
+        if (gc < 0) kind = gc == -NV ? 1 : 3;
+        else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
+        else { txx = gc / g.tw; cc = gc - txx * g.tw; }
+        // Per-lane byte offset that never changes: the lane's cells, or (ring lanes) the place in the
+        // first / last tile's x-halo array from which a vector read puts the ring value into the
+        // component next to the tile cells (the other components of a ring lane are never used).
+        long long lane_elems = 0;
+        if (kind == 0) lane_elems = (long long)txx * g.tile_stride + cc;
+        else if (kind == 1) lane_elems = g.xoff - (NV - 1);
+        else if (kind == 2) lane_elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
+        const unsigned lane_bytes = (unsigned)(lane_elems * (long long)sizeof(T));
+        const bool ring_lane = kind == 1 || kind == 2;
+        const bool wave_has_ring = __any(ring_lane) != 0;
+        const bool owner = lane >= GL && lane < WAVE - GL && kind == 0;
+        const bool z_lo_ring = tz == 0, z_hi_ring = tz == g.Tz - 1;
+
+        // ---- rows j = 0..NRW-1 <-> tile row iota = i0 - TB + j, followed into the tiles above / below
+        long long row_base[NRW];     // element offset of the row inside a z-layer of tiles
+        int row_to_halo[NRW];        // (halo entry of the row) - (first cell of the row), elements, plane part aside
+        bool ring_row[NRW];
+#pragma unroll
+        for (int j = 0; j < NRW; ++j) {
+            const int iota = min(i0 - TB + j, g.th + TB);
+            int tyy = ty, rr = iota;
+            ring_row[j] = false;
+            if (iota <= 0) {
+                if (ty > 0) { tyy = ty - 1; rr = g.th + iota; }
+                else { rr = 0; ring_row[j] = true; }
+            } else if (iota > g.th) {
+                if (ty < g.Ty - 1) { tyy = ty + 1; rr = iota - g.th; }
+                else { rr = g.th + 1; ring_row[j] = true; }
+            }
+            row_base[j] = (long long)tyy * tilerow + (long long)rr * g.pitch;
+            row_to_halo[j] = rr - rr * g.pitch;
+        }
+        // plane kappa of u(t) (relative to this tile, clamped): offset of its cells, and the distance from
+        // a row's first cell to the row's x-halo entry
+        long long pl_cells;
+        int pl_to_halo;
+        auto locate_plane = [&](int kappa) {
+            int tzz = tz, kk;
+            kappa = min(kappa, g.td + TB);
+            if (kappa <= 0) {
+                if (!z_lo_ring) { tzz = tz - 1; kk = g.td + kappa; }
+                else kk = 0;
+            } else if (kappa > g.td) {
+                if (!z_hi_ring) { tzz = tz + 1; kk = kappa - g.td; }
+                else kk = g.td + 1;
+            } else kk = kappa;
+            pl_cells = (long long)tzz * g.Ty * tilerow + (long long)kk * g.plane;
+            pl_to_halo = kk * g.rows - (int)((long long)kk * g.plane);
+        };
+        auto load_row = [&](int j) -> V {
+            const T *rowp = src + (pl_cells + row_base[j]);
+            unsigned off = lane_bytes;
+            if (wave_has_ring) off += ring_lane ? (unsigned)((pl_to_halo + row_to_halo[j]) * (int)sizeof(T)) : 0u;
+            return *(const VU *)((const char *)rowp + off);      // ring lanes read element-aligned
+        };
+
+        V st[TB][2][NRW];                // per level l-1: the two newest planes; roles swap each step
+#pragma unroll
+        for (int l = 0; l < TB; ++l)
+#pragma unroll
+            for (int j = 0; j < NRW; ++j) st[l][0][j] = st[l][1][j] = V(0);
+
+        const int nsteps = (k1 - k0 + 1) + 2 * TB;          // planes kappa = k0-TB .. k1+TB
+        const int npairs = (nsteps + 1) / 2;
+        V ld[2][NRW];                                        // plane entering the pipeline / the one after it
+        locate_plane(k0 - TB);
+#pragma unroll
+        for (int j = 0; j < NRW; ++j) ld[0][j] = load_row(j);
+
+        const long long out_tile = ((long long)tz * g.Ty + ty) * tilerow;
+
+        for (int pr = 0; pr < npairs; ++pr) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {                    // p: slot holding the OLDER plane of every level
+                const int q = 2 * pr + p;
+                const int kappa = k0 - TB + q;               // plane of u(t) entering the pipeline
+                locate_plane(kappa + 1);
+#pragma unroll
+                for (int j = 0; j < NRW; ++j) ld[1 - p][j] = load_row(j);
+                bool ring_plane[TB + 1];
+#pragma unroll
+                for (int l = 1; l <= TB; ++l)
+                    ring_plane[l] = (z_lo_ring && kappa - l == 0) || (z_hi_ring && kappa - l == g.td + 1);
+                const int oplane = kappa - TB;
+                const bool store_plane = q >= 2 * TB && oplane <= k1;
+                T *outp = dst + (out_tile + (long long)oplane * g.plane + (long long)i0 * g.pitch);
+#pragma unroll
+                for (int j = 0; j < NRW; ++j) {
+                    V d = ld[p][j];                          // newest plane of the level below, row j
+#pragma unroll
+                    for (int l = 1; l <= TB; ++l) {
+                        if (j < l - 1 || j >= NRW - (l - 1)) break;     // row not carried at level l-1
+                        const V zm = st[l - 1][p][j];
+                        st[l - 1][p][j] = d;                 // the older plane is dead: its slot takes the newest
+                        if (j < l || j >= NRW - l) break;    // row not produced at level l
+                        const V c = st[l - 1][1 - p][j];
+                        V nw;
+                        if (ring_plane[l] || ring_row[j]) {
+                            nw = c;                          // Dirichlet plane / row keeps its values
+                        } else {
+                            const V ym = st[l - 1][1 - p][j - 1], yp = st[l - 1][1 - p][j + 1];
+                            const T left = from_prev_lane_or_zero(c[NV - 1]);
+                            const T right = from_next_lane_or_zero(c[0]);
+#pragma unroll
+                            for (int e = 0; e < NV; ++e) {
+                                const T xx = (e == 0 ? left : c[e - 1]) + (e == NV - 1 ? right : c[e + 1]);
+                                const T yy = ym[e] + yp[e];
+                                const T zz = zm[e] + d[e];
+                                nw[e] = Coef<T>::sixth * ((xx + yy) + zz);
+                                if constexpr (MODE == MODE_BOTH) {
+                                    const int plane = kappa - 1, row = i0 - TB + j;
+                                    if (l == 1 && plane >= k0 && plane <= k1 && j >= TB && j < TB + RW && row <= g.th && owner) {
+                                        const T res = ((xx + yy) + zz) - Coef<T>::six * c[e];
+                                        const double rd = (double)res;
+                                        acc += rd * rd;
+                                    }
+                                }
+                            }
+                            if (wave_has_ring) {
+                                if (ring_lane) {
+                                    if (kind == 1) nw[NV - 1] = c[NV - 1]; else nw[0] = c[0];
+                                }
+                            }
+                        }
+                        d = nw;
+                    }
+                    // after TB levels `d` is u(t+TB) of plane kappa-TB for the owned rows
+                    if (j >= TB && j < TB + RW) {
+                        if (store_plane && i0 + (j - TB) <= g.th && owner)
+                            __builtin_nontemporal_store(d, (V *)((char *)(outp + (long long)(j - TB) * g.pitch) + lane_bytes));
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (MODE == MODE_BOTH) {
         const double tot = wg_sum(acc, red);
         if (threadIdx.x == 0) partial[lwg] = tot;
     }

@@ -16,6 +16,7 @@ struct LaunchArgs {
     const void *src;     // element type is given by the f64 flag of the call
     void *dst;
     double *partial;     // per-workgroup partial sums (residual modes), else unused
+    int aux = 0;         // kernel-specific extra (3-D blocked pass: row groups per tile)
 };
 
 // single-step update / residual (mode: Mode; unroll 1,2,4,8,16; nt: 0 or 2)
@@ -31,5 +32,10 @@ hipError_t launch_t2(bool f64, int mode, const LaunchArgs &a);
 constexpr int TP_MIN = 3, TP_MAX = 8;
 hipError_t launch_tp_f64(int depth, int mode, const LaunchArgs &a);
 hipError_t launch_tp_f32(int depth, int mode, const LaunchArgs &a);
+
+// 3-D: depth-2 passes pipelined along z; rows_per_wave 2 or 4
+constexpr int TP3D_DEPTH = 2;
+hipError_t launch_tp3d_f64(int depth, int rows_per_wave, int mode, const LaunchArgs &a);
+hipError_t launch_tp3d_f32(int depth, int rows_per_wave, int mode, const LaunchArgs &a);
 
 }  // namespace jk

@@ -288,8 +288,48 @@ def test_temporal_blocking_fp32_and_fused_residual(H, oracle_mod):
 def test_temporal_blocking_falls_back_on_thin_tiles_and_3d(H, oracle_mod):
     a = random_padded((40, 36), seed=5)
     check(*run_case(H, oracle_mod, a, (1, 36), 6, 2, tblock=2))      # tiles one column wide
-    b = random_padded((12, 10, 40), seed=6)
-    check(*run_case(H, oracle_mod, b, (2, 1, 2), 5, 5, tblock=2))    # 3-D: single steps
+    b = random_padded((12, 10, 41), seed=6)
+    check(*run_case(H, oracle_mod, b, (2, 1, 1), 5, 5, tblock=2))    # 3-D, odd tile width: single steps
+    c = random_padded((12, 5, 40), seed=8)
+    check(*run_case(H, oracle_mod, c, (2, 5, 2), 5, 5, tblock=2))    # 3-D, tiles one row high: single steps
+
+
+CASES_3D_TB = [
+    ((24, 20, 36), (2, 2, 3), 9, 3),        # tw = 12: a wavefront's columns span the whole tile row
+    ((16, 16, 16), (1, 1, 1), 8, 4),
+    ((6, 10, 130), (3, 5, 1), 6, 6),        # td = th = 2: every plane and row borders another tile
+    ((8, 8, 8), (4, 4, 1), 7, 2),
+    ((128, 128, 128), (4, 4, 4), 12, 4),    # 64 tiles of 32^3
+    ((70, 33, 20), (1, 1, 1), 6, 3),        # th = 33: ragged last row group
+    ((40, 18, 256), (2, 3, 1), 10, 5),      # tw = 256: three column segments, last one ragged
+    ((20, 14, 448), (1, 1, 4), 8, 8),       # 4 tiles of 112 columns = one wavefront of owned columns each
+    ((33, 9, 64), (1, 1, 32), 5, 5),        # tw = 2 (one fp64 vector)
+]
+
+
+@pytest.mark.parametrize("opts", [dict(tblock=2), dict(tblock=8, rows_per_wave=2), dict(tblock=2, rows_per_wave=4),
+                                  dict(tblock=2, rows_per_strip=1), dict(tblock=3, rows_per_strip=5, xcd_chunk=1),
+                                  dict(tblock=2, rows_per_strip=4096, rows_per_wave=2)])
+@pytest.mark.parametrize("dims,tiles,iters,every", CASES_3D_TB)
+def test_3d_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every, opts):
+    a = random_padded(dims, seed=sum(dims) + iters)
+    check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
+
+
+@pytest.mark.parametrize("rows_per_wave", [2, 4])
+def test_3d_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, rows_per_wave):
+    a = random_padded((24, 20, 72), dtype=np.float32, seed=17)
+    check(*run_case(H, oracle_mod, a, (2, 2, 3), 11, 4, tblock=2, rows_per_wave=rows_per_wave))
+    b = random_padded((36, 22, 140), seed=19)
+    ref, ref_res = oracle_mod.run(b, 13, 3)
+    r = H.JacobiRun((36, 22, 140), (3, 2, 5), tblock=2, rows_per_wave=rows_per_wave)
+    try:
+        r.load(b)
+        res = r.run(13, 3, fuse_residual=True)
+        out = r.fetch()
+    finally:
+        r.close()
+    check(out, res, ref, ref_res)
 
 
 @pytest.mark.parametrize("tblock", [1, 2])

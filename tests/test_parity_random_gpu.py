@@ -22,7 +22,7 @@ def divisors(n):
     return [d for d in range(1, n + 1) if n % d == 0]
 
 
-def make_cases(ndim, count, seed):
+def make_cases(ndim, count, seed, blocked_3d=False):
     rng = np.random.default_rng(seed)
     cases = []
     for _ in range(count):
@@ -42,6 +42,8 @@ def make_cases(ndim, count, seed):
             opts["tblock"] = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8]))
         else:
             opts["rows_per_wave"] = int(rng.choice([0, 1, 2, 4]))
+            if blocked_3d:
+                opts["tblock"] = int(rng.choice([2, 3, 8]))
         fuse_res = bool(rng.integers(0, 2))
         cases.append((dims, tiles, iters, every, opts, fuse_res))
     return cases
@@ -71,3 +73,8 @@ def test_random_2d(H, oracle_mod, n, case):
 @pytest.mark.parametrize("n,case", list(enumerate(make_cases(3, 80, 20221002))))
 def test_random_3d(H, oracle_mod, n, case):
     run_random(H, oracle_mod, case, 2000 + n)
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_cases(3, 80, 20221003, blocked_3d=True))))
+def test_random_3d_blocked(H, oracle_mod, n, case):
+    run_random(H, oracle_mod, case, 3000 + n)
