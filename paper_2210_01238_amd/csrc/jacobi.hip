@@ -195,9 +195,7 @@ StripParams tp_strips(const jacobi_plan *p)
     const Geo &g = p->geo;
     StripParams sp;
     // column segments run along a whole row of tiles; strips = rows of tiles x row blocks x segments
-    const int segw = p->lay.dtype == JACOBI_F64 ? jk::Tp3dGeometry<double, jk::TP3D_DEPTH>::SEGW
-                                                : jk::Tp3dGeometry<float, jk::TP3D_DEPTH>::SEGW;
-    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, segw);
+    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
         // every strip pays a run-in of 2*depth rows, so strips should be tall - but not so tall
@@ -226,28 +224,30 @@ int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_r
 }
 
 // ---- 3-D pipelined temporal blocking ------------------------------------------------------------
-bool tp3d_usable(const jacobi_plan *p)
+bool tp3d_usable(const jacobi_plan *p, int depth)
 {
     const Geo &g = p->geo;
     const int nv = 16 / (int)p->esize;
-    return g.ndim == 3 && g.tw % nv == 0 && g.th >= jk::TP3D_DEPTH && g.td >= jk::TP3D_DEPTH &&
+    return g.ndim == 3 && depth >= jk::TP3D_MIN && depth <= jk::TP3D_MAX && g.tw % nv == 0 && g.th >= depth &&
+           g.td >= depth &&
            (int64_t)g.Tx * g.tile_stride * (int64_t)p->esize < 0x7fffffffLL;   // per-lane byte offsets are 32-bit
 }
 
-int tp3d_rows_per_wave(const jacobi_plan *p)
+int tp3d_rows_per_wave(const jacobi_plan *p, int depth)
 {
+    if (depth == 3) return 2;
     const int rw = (int)p->rows_per_wave;
     return rw == 2 ? 2 : rw == 4 ? 4 : (p->geo.th >= 4 ? 4 : 2);
 }
 
-StripParams tp3d_strips(const jacobi_plan *p, int *nrg_out)
+StripParams tp3d_strips(const jacobi_plan *p, int depth, int *nrg_out)
 {
     const Geo &g = p->geo;
     StripParams sp;
-    const int rw = tp3d_rows_per_wave(p);
+    const int rw = tp3d_rows_per_wave(p, depth);
     const int nrg = (int)ceil_div(g.th, rw);
-    const int segw = p->lay.dtype == JACOBI_F64 ? jk::Tp3dGeometry<double, jk::TP3D_DEPTH>::SEGW
-                                                : jk::Tp3dGeometry<float, jk::TP3D_DEPTH>::SEGW;
+    const int nv = 16 / (int)p->esize;
+    const int segw = (jk::WAVE - 2 * (int)ceil_div(depth, nv)) * nv;     // Tp3dGeometry<T, depth>::SEGW
     sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, segw);
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
@@ -265,18 +265,18 @@ StripParams tp3d_strips(const jacobi_plan *p, int *nrg_out)
     return sp;
 }
 
-int launch_tp3d(jacobi_plan *p, const void *src, void *dst, bool with_residual, hipStream_t st)
+int launch_tp3d(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
 {
     int nrg = 0;
-    const StripParams sp = tp3d_strips(p, &nrg);
+    const StripParams sp = tp3d_strips(p, depth, &nrg);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
     a.aux = nrg;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
-    const int rw = tp3d_rows_per_wave(p);
-    return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp3d_f64(jk::TP3D_DEPTH, rw, mode, a)
-                                                     : jk::launch_tp3d_f32(jk::TP3D_DEPTH, rw, mode, a),
+    const int rw = tp3d_rows_per_wave(p, depth);
+    return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp3d_f64(depth, rw, mode, a)
+                                                     : jk::launch_tp3d_f32(depth, rw, mode, a),
                           "3-D blocked-pass kernel launch");
 }
 
@@ -284,7 +284,7 @@ int launch_tp3d(jacobi_plan *p, const void *src, void *dst, bool with_residual, 
 // the fewest passes the requested depth allows (10 iterations at depth 8 run as 5 + 5, not
 // 8 + 2: a pass costs little more for being deeper).  kernel: 0 single step (needs current
 // halos), 1 two-step kernel (2-D), 2 pipelined kernel (2-D, depths 3..8), 3 pipelined 3-D
-// kernel (depth 2).
+// kernel (depths 2..3).
 struct PassChoice { int depth; int kernel; };
 
 PassChoice choose_pass(const jacobi_plan *p, int left)
@@ -292,7 +292,10 @@ PassChoice choose_pass(const jacobi_plan *p, int left)
     int maxd = (int)(p->tblock < left ? p->tblock : left);
     if (maxd > jk::TP_MAX) maxd = jk::TP_MAX;
     if (maxd >= 2 && p->geo.ndim == 3) {
-        if (tp3d_usable(p)) return {jk::TP3D_DEPTH, 3};
+        if (maxd > jk::TP3D_MAX) maxd = jk::TP3D_MAX;
+        const int passes = (left + maxd - 1) / maxd;
+        for (int d = (left + passes - 1) / passes; d >= jk::TP3D_MIN; --d)
+            if (tp3d_usable(p, d)) return {d, 3};
     } else if (maxd >= 2) {
         const int passes = (left + maxd - 1) / maxd;
         const int d = (left + passes - 1) / passes;
@@ -543,7 +546,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         const int64_t strips = first.kernel == 0   ? make_config(plan, jk::MODE_BOTH).sp.nstrips
                                : first.kernel == 1 ? t2_strips(plan).nstrips
                                : first.kernel == 2 ? tp_strips(plan).nstrips
-                                                   : tp3d_strips(plan, nullptr).nstrips;
+                                                   : tp3d_strips(plan, first.depth, nullptr).nstrips;
         nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
         int rc = ensure_partials(plan, nwg_res + 1);
         if (rc) return rc;
@@ -567,7 +570,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         if (pc.kernel == 0)      rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
         else if (pc.kernel == 1) rc = launch_t2(plan, src, dst, with_res, st);
         else if (pc.kernel == 2) rc = launch_tp(plan, pc.depth, src, dst, with_res, st);
-        else                     rc = launch_tp3d(plan, src, dst, with_res, st);
+        else                     rc = launch_tp3d(plan, pc.depth, src, dst, with_res, st);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));

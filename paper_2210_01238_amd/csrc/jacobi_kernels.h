@@ -848,7 +848,7 @@ template <typename T, int TB> struct Tp3dGeometry {
     static constexpr int SEGW = OWN_LANES * NV;            // columns a wavefront owns
 };
 
-template <typename T, int MODE, int TB, int RW, int MINW>
+template <typename T, int MODE, int TB, int RW, int PF, int MINW>
 __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams sp, int nrg,
                                                               const T *__restrict__ src, T *__restrict__ dst,
                                                               double *__restrict__ partial)
@@ -953,22 +953,30 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
             for (int j = 0; j < NRW; ++j) st[l][0][j] = st[l][1][j] = V(0);
 
         const int nsteps = (k1 - k0 + 1) + 2 * TB;          // planes kappa = k0-TB .. k1+TB
-        const int npairs = (nsteps + 1) / 2;
-        V ld[2][NRW];                                        // plane entering the pipeline / the one after it
-        locate_plane(k0 - TB);
+        // the plane in use plus PF planes in flight; the step loop is unrolled so that both the
+        // buffer in use and the older state slot are compile-time indices
+        constexpr int LDN = PF + 1;
+        constexpr int UN = LDN % 2 == 0 ? LDN : 2 * LDN;
+        V ld[LDN][NRW];
 #pragma unroll
-        for (int j = 0; j < NRW; ++j) ld[0][j] = load_row(j);
+        for (int f = 0; f < PF; ++f) {
+            locate_plane(k0 - TB + f);
+#pragma unroll
+            for (int j = 0; j < NRW; ++j) ld[f][j] = load_row(j);
+        }
 
         const long long out_tile = ((long long)tz * g.Ty + ty) * tilerow;
 
-        for (int pr = 0; pr < npairs; ++pr) {
+        for (int q0 = 0; q0 < nsteps; q0 += UN) {
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {                    // p: slot holding the OLDER plane of every level
-                const int q = 2 * pr + p;
+            for (int u = 0; u < UN; ++u) {
+                const int q = q0 + u;
+                if (q >= nsteps) break;
+                const int p = u & 1;                         // slot holding the OLDER plane of every level
                 const int kappa = k0 - TB + q;               // plane of u(t) entering the pipeline
-                locate_plane(kappa + 1);
+                locate_plane(kappa + PF);
 #pragma unroll
-                for (int j = 0; j < NRW; ++j) ld[1 - p][j] = load_row(j);
+                for (int j = 0; j < NRW; ++j) ld[(u + PF) % LDN][j] = load_row(j);
                 bool ring_plane[TB + 1];
 #pragma unroll
                 for (int l = 1; l <= TB; ++l)
@@ -978,7 +986,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
                 T *outp = dst + (out_tile + (long long)oplane * g.plane + (long long)i0 * g.pitch);
 #pragma unroll
                 for (int j = 0; j < NRW; ++j) {
-                    V d = ld[p][j];                          // newest plane of the level below, row j
+                    V d = ld[u % LDN][j];                    // newest plane of the level below, row j
 #pragma unroll
                     for (int l = 1; l <= TB; ++l) {
                         if (j < l - 1 || j >= NRW - (l - 1)) break;     // row not carried at level l-1

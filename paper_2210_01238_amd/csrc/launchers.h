@@ -33,8 +33,8 @@ constexpr int TP_MIN = 3, TP_MAX = 8;
 hipError_t launch_tp_f64(int depth, int mode, const LaunchArgs &a);
 hipError_t launch_tp_f32(int depth, int mode, const LaunchArgs &a);
 
-// 3-D: depth-2 passes pipelined along z; rows_per_wave 2 or 4
-constexpr int TP3D_DEPTH = 2;
+// 3-D: passes of depth 2 (2 or 4 rows per wavefront) or 3 (2 rows), pipelined along z
+constexpr int TP3D_MIN = 2, TP3D_MAX = 3;
 hipError_t launch_tp3d_f64(int depth, int rows_per_wave, int mode, const LaunchArgs &a);
 hipError_t launch_tp3d_f32(int depth, int rows_per_wave, int mode, const LaunchArgs &a);
 

@@ -113,9 +113,21 @@ def test_full_C4_512cube_4x4x4(H, oracle_mod):
     full_size_check(H, oracle_mod, "C4", few=4)
 
 
+def test_full_C4_blocked_passes_of_three_and_two_iterations(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C4", few=5, tblock=3)      # 5 = 3 + 2; 10 per period = 3 + 3 + 2 + 2
+
+
+def test_full_C4_two_iterations_per_pass(H, oracle_mod):
+    full_size_check(H, oracle_mod, "C4", few=4, tblock=2)
+
+
 def test_full_C2_4096sq_4x4(H, oracle_mod):
     full_size_check(H, oracle_mod, "C2", few=10)
 
 
 def test_full_P1_paper_domain_1024x1024x768(H, oracle_mod):
     full_size_check(H, oracle_mod, "P1", few=2)
+
+
+def test_full_P1_paper_domain_blocked_passes(H, oracle_mod):
+    full_size_check(H, oracle_mod, "P1", few=3, tblock=8)

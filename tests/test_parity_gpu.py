@@ -316,13 +316,13 @@ def test_3d_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters
     check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
 
 
-@pytest.mark.parametrize("rows_per_wave", [2, 4])
-def test_3d_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, rows_per_wave):
+@pytest.mark.parametrize("tblock,rows_per_wave", [(2, 2), (2, 4), (3, 0)])
+def test_3d_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock, rows_per_wave):
     a = random_padded((24, 20, 72), dtype=np.float32, seed=17)
-    check(*run_case(H, oracle_mod, a, (2, 2, 3), 11, 4, tblock=2, rows_per_wave=rows_per_wave))
+    check(*run_case(H, oracle_mod, a, (2, 2, 3), 11, 4, tblock=tblock, rows_per_wave=rows_per_wave))
     b = random_padded((36, 22, 140), seed=19)
     ref, ref_res = oracle_mod.run(b, 13, 3)
-    r = H.JacobiRun((36, 22, 140), (3, 2, 5), tblock=2, rows_per_wave=rows_per_wave)
+    r = H.JacobiRun((36, 22, 140), (3, 2, 5), tblock=tblock, rows_per_wave=rows_per_wave)
     try:
         r.load(b)
         res = r.run(13, 3, fuse_residual=True)
