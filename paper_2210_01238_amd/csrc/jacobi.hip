@@ -187,15 +187,22 @@ bool tp_usable(const jacobi_plan *p, int depth)
     const Geo &g = p->geo;
     const int nv = 16 / (int)p->esize;
     return depth >= jk::TP_MIN && depth <= jk::TP_MAX && g.ndim == 2 && g.tw % nv == 0 && g.th >= depth &&
-           (int64_t)g.Tx * g.tw < 0x7fffffffLL;
+           (int64_t)g.Tx * g.tile_stride * (int64_t)p->esize < 0x7fffffffLL;   // per-lane byte offsets are 32-bit
 }
 
-StripParams tp_strips(const jacobi_plan *p)
+// columns a wavefront owns in a blocked pass of this depth (jk::TpGeometry<T, depth, ndim>::SEGW)
+int tp_segment_width(const jacobi_plan *p, int depth)
+{
+    const int nv = 16 / (int)p->esize;
+    return (jk::WAVE - 2 * jk::tp_ghost_lanes((int)p->esize, p->geo.ndim, depth)) * nv;
+}
+
+StripParams tp_strips(const jacobi_plan *p, int depth)
 {
     const Geo &g = p->geo;
     StripParams sp;
     // column segments run along a whole row of tiles; strips = rows of tiles x row blocks x segments
-    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, (int64_t)jk::TB_OWN_LANES * (16 / (int)p->esize));
+    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, tp_segment_width(p, depth));
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
         // every strip pays a run-in of 2*depth rows, so strips should be tall - but not so tall
@@ -214,7 +221,7 @@ StripParams tp_strips(const jacobi_plan *p)
 
 int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
 {
-    const StripParams sp = tp_strips(p);
+    const StripParams sp = tp_strips(p, depth);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
@@ -246,9 +253,7 @@ StripParams tp3d_strips(const jacobi_plan *p, int depth, int *nrg_out)
     StripParams sp;
     const int rw = tp3d_rows_per_wave(p, depth);
     const int nrg = (int)ceil_div(g.th, rw);
-    const int nv = 16 / (int)p->esize;
-    const int segw = (jk::WAVE - 2 * (int)ceil_div(depth, nv)) * nv;     // Tp3dGeometry<T, depth>::SEGW
-    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, segw);
+    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, tp_segment_width(p, depth));
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
         // a strip pays a run-in of 2*depth planes: keep it deep, but leave enough strips to fill the chip
@@ -292,7 +297,9 @@ PassChoice choose_pass(const jacobi_plan *p, int left)
     int maxd = (int)(p->tblock < left ? p->tblock : left);
     if (maxd > jk::TP_MAX) maxd = jk::TP_MAX;
     if (maxd >= 2 && p->geo.ndim == 3) {
-        if (maxd > jk::TP3D_MAX) maxd = jk::TP3D_MAX;
+        // fp32 passes of depth 3 are bound by arithmetic and measured slower per iteration than depth 2
+        const int deepest = p->lay.dtype == JACOBI_F64 ? jk::TP3D_MAX : jk::TP3D_MIN;
+        if (maxd > deepest) maxd = deepest;
         const int passes = (left + maxd - 1) / maxd;
         for (int d = (left + passes - 1) / passes; d >= jk::TP3D_MIN; --d)
             if (tp3d_usable(p, d)) return {d, 3};
@@ -545,7 +552,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     if (residual_in_dev) {
         const int64_t strips = first.kernel == 0   ? make_config(plan, jk::MODE_BOTH).sp.nstrips
                                : first.kernel == 1 ? t2_strips(plan).nstrips
-                               : first.kernel == 2 ? tp_strips(plan).nstrips
+                               : first.kernel == 2 ? tp_strips(plan, first.depth).nstrips
                                                    : tp3d_strips(plan, first.depth, nullptr).nstrips;
         nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
         int rc = ensure_partials(plan, nwg_res + 1);

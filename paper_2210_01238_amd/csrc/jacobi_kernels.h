@@ -529,8 +529,24 @@ __global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
 // single-step expression, so a pass is bit-identical to TB single steps.
 // Needs tw a multiple of the vector width and th >= TB.
 // ------------------------------------------------------------------------------------
-constexpr int TB_GHOST_LANES = 4;                       // 64 bytes on either side
-constexpr int TB_OWN_LANES = WAVE - 2 * TB_GHOST_LANES; // 56 lanes = 896 bytes
+// Column geometry of a blocked pass of depth TB: every level loses one ghost column per side,
+// so at least ceil(TB / vector width) lanes per side are ghosts and the rest own their columns.
+// In 2-D, fp64 passes keep 4 ghost lanes at every depth: the owned part of a wavefront's row is
+// then 896 bytes = 7 whole cache lines, which measured faster than fewer ghosts and ragged lines;
+// 3-D passes measured best with 2.
+constexpr int tp_ghost_lanes(int elem_size, int ndim, int depth)
+{
+    const int nv = 16 / elem_size;
+    const int need = (depth + nv - 1) / nv;
+    const int least = ndim == 2 ? (elem_size == 8 ? 4 : 2) : 2;
+    return need > least ? need : least;
+}
+template <typename T, int TB, int NDIM> struct TpGeometry {
+    static constexpr int NV = Vec<T>::N;
+    static constexpr int GHOST_LANES = tp_ghost_lanes((int)sizeof(T), NDIM, TB);
+    static constexpr int OWN_LANES = WAVE - 2 * GHOST_LANES;
+    static constexpr int SEGW = OWN_LANES * NV;            // columns a wavefront owns
+};
 
 template <typename T, int MODE, int TB, int PF, int MINW>
 __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams sp,
@@ -539,9 +555,10 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
 {
     using V = typename Vec<T>::type;
     constexpr int NV = Vec<T>::N;
-    constexpr int GH = TB_GHOST_LANES * NV;
-    constexpr int SEGW = TB_OWN_LANES * NV;
-    static_assert(TB >= 1 && TB <= GH, "a level loses one ghost column per side");
+    typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
+    constexpr int GL = TpGeometry<T, TB, 2>::GHOST_LANES;
+    constexpr int GH = GL * NV;
+    constexpr int SEGW = TpGeometry<T, TB, 2>::SEGW;
     static_assert(PF >= 2 && PF % 2 == 0, "the two-row windows swap roles every step");
     static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
     __shared__ double red[WAVES_PER_WG];
@@ -571,14 +588,21 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
         if (gc < 0) kind = gc == -NV ? 1 : 3;
         else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
         else { txx = gc / g.tw; cc = gc - txx * g.tw; }
-        // per-lane address parts, the same for every row (relative to tile (row's ty, 0), row 0)
-        const long long lane_off = kind == 0 ? (long long)txx * g.tile_stride + cc : 0;
-        const long long halo_base = kind == 2 ? (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch : g.xoff;
+        // Per-lane byte offset, the same for every row (relative to the row's first cell in the first
+        // tile of the row of tiles): the lane's cells, or (ring lanes) the place in the first / last
+        // tile's x-halo array from which a vector read puts the ring value into the component next to
+        // the tile cells (a ring lane's other components are never used).
+        long long lane_elems = 0;
+        if (kind == 0) lane_elems = (long long)txx * g.tile_stride + cc;
+        else if (kind == 1) lane_elems = g.xoff - (NV - 1);
+        else if (kind == 2) lane_elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
+        const unsigned lane_bytes = (unsigned)(lane_elems * (long long)sizeof(T));
         const bool ring_lane = kind == 1 || kind == 2;
         const bool wave_has_ring = __any(ring_lane) != 0;
-        const bool owner = lane >= TB_GHOST_LANES && lane < WAVE - TB_GHOST_LANES && kind == 0;
+        const bool owner = lane >= GL && lane < WAVE - GL && kind == 0;
         const bool top_ring = ty == 0, bottom_ring = ty == g.Ty - 1;
-        T *tdst = dst + (long long)ty * g.Tx * g.tile_stride + lane_off;   // this lane's cells, row 0
+        const long long tilerow = (long long)g.Tx * g.tile_stride;
+        T *trow = dst + (long long)ty * tilerow;                 // first tile of this row of tiles
 
         // u(t) row rho (relative to this tile; clamped to [-(TB), th+1+TB] and onto the ring)
         auto load_row = [&](int rho) -> V {
@@ -591,16 +615,10 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                 if (!bottom_ring) { tyy = ty + 1; rr = rho - g.th; }
                 else rr = g.th + 1;
             } else rr = rho;
-            const long long row_off = (long long)tyy * g.Tx * g.tile_stride;
-            const long long cell_off = (long long)rr * g.pitch + lane_off;
-            const long long halo_off = halo_base + (rr & ~(NV - 1));
-            V v = *(const V *)(src + row_off + (ring_lane ? halo_off : cell_off));
-            if (wave_has_ring && ring_lane) {
-                const T rv = vec_pick<T, NV>(v, rr & (NV - 1));
-                v = V(0);
-                if (kind == 1) v[NV - 1] = rv; else v[0] = rv;
-            }
-            return v;
+            const T *rowp = src + ((long long)tyy * tilerow + (long long)rr * g.pitch);
+            unsigned off = lane_bytes;
+            if (wave_has_ring) off += ring_lane ? (unsigned)((rr - rr * g.pitch) * (int)sizeof(T)) : 0u;
+            return *(const VU *)((const char *)rowp + off);      // ring lanes read element-aligned
         };
 
         V w[TB][2];                      // per level l (0..TB-1): the two newest rows, roles swap each step
@@ -630,8 +648,8 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                     if ((top_ring && row == 0) || (bottom_ring && row == g.th + 1)) {
                         nw = c;                          // Dirichlet row: keeps its values
                     } else {
-                        const T left = from_prev_lane(c[NV - 1], T(0));
-                        const T right = from_next_lane(c[0], T(0));
+                        const T left = from_prev_lane_or_zero(c[NV - 1]);
+                        const T right = from_next_lane_or_zero(c[0]);
 #pragma unroll
                         for (int j = 0; j < NV; ++j) {
                             const T we = (j == 0 ? left : c[j - 1]) + (j == NV - 1 ? right : c[j + 1]);
@@ -645,8 +663,10 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                                 }
                             }
                         }
-                        if (wave_has_ring && ring_lane) {   // Dirichlet column cell keeps its value
-                            if (kind == 1) nw[NV - 1] = c[NV - 1]; else nw[0] = c[0];
+                        if (wave_has_ring) {
+                            if (ring_lane) {             // Dirichlet column cell keeps its value
+                                if (kind == 1) nw[NV - 1] = c[NV - 1]; else nw[0] = c[0];
+                            }
                         }
                     }
                     w[l - 1][p] = down;                  // the older row is dead: its slot takes the newest
@@ -654,7 +674,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                 }
                 const int orow = rho - TB;               // `down` is now u(t+TB) of this row
                 if (q >= 2 * TB && orow <= r1 && owner)
-                    __builtin_nontemporal_store(down, (V *)(tdst + main_off(g, 0, orow, 0)));
+                    __builtin_nontemporal_store(down, (V *)((char *)(trow + (long long)orow * g.pitch) + lane_bytes));
             }
 #pragma unroll
             for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
@@ -841,20 +861,13 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
 // that never changes.  Bit-identical to TB single steps.  Needs tw a multiple of the vector
 // width, th >= TB, td >= TB, and a row of tiles smaller than 2 GiB.
 // ------------------------------------------------------------------------------------
-template <typename T, int TB> struct Tp3dGeometry {
-    static constexpr int NV = Vec<T>::N;
-    static constexpr int GHOST_LANES = (TB + NV - 1) / NV;
-    static constexpr int OWN_LANES = WAVE - 2 * GHOST_LANES;
-    static constexpr int SEGW = OWN_LANES * NV;            // columns a wavefront owns
-};
-
 template <typename T, int MODE, int TB, int RW, int PF, int MINW>
 __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams sp, int nrg,
                                                               const T *__restrict__ src, T *__restrict__ dst,
                                                               double *__restrict__ partial)
 {
     using V = typename Vec<T>::type;
-    using G3 = Tp3dGeometry<T, TB>;
+    using G3 = TpGeometry<T, TB, 3>;
     constexpr int NV = Vec<T>::N;
     typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
     constexpr int GL = G3::GHOST_LANES;
