@@ -167,8 +167,9 @@ def main() -> int:
             "passes_timed": tb_n,
             "iterations_per_pass": round(every * K / max(tb_n, 1), 3),
             "residuals_match_single_step_1e-12": all(abs(x - y) <= 1e-12 * abs(y) for x, y in zip(tb_res, residuals)),
-            "note": "same iterations, bit-identical grids; a pass advances up to `tblock` iterations and reads "
-                    "the rim it needs from the neighbouring tiles itself instead of a halo exchange per iteration",
+            "note": "same iterations, bit-identical grids; a pass advances up to `tblock` iterations (3-D: up to 3) "
+                    "and reads the rim it needs from the neighbouring tiles itself instead of a halo exchange "
+                    "per iteration",
         }
 
     # practical ceiling: a plain streaming copy of one grid into the other (same bytes in and out)

@@ -266,6 +266,9 @@ StripParams tp3d_strips(const jacobi_plan *p, int depth, int *nrg_out)
     sp.nstrips = (int64_t)g.Tz * g.Ty * sp.nblk * nrg * sp.nseg;
     sp.fused = 0;
     sp.xcd_chunk = (int)p->xcd_chunk;
+    // depth 3 (2 owned rows of 8 loaded) runs faster when a workgroup's wavefronts are neighbours in y;
+    // depth 2 (4 of 8) when they are neighbours in x
+    sp.rows_fastest = depth >= 3;
     if (nrg_out) *nrg_out = nrg;
     return sp;
 }

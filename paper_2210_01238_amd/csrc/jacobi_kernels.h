@@ -211,6 +211,7 @@ struct StripParams {
     long long nstrips;   // total
     int fused;           // update mode: push edge cells into neighbour halos of dst
     int xcd_chunk;       // G of xcd_logical_wg(): consecutive workgroups one XCD takes
+    int rows_fastest = 0; // 3-D blocked passes: consecutive strips are neighbours in y (else in x)
 };
 
 // ------------------------------------------------------------------------------------
@@ -884,13 +885,16 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
     double acc = 0.0;
 
     if (s < sp.nstrips) {
-        // strip = (tz, ty) row of tiles -> plane block -> row group -> column segment
+        // strip = (tz, ty) row of tiles -> plane block -> (column segment, row group), either one fastest:
+        // with rows fastest the wavefronts of a workgroup are neighbours in y and share their ghost rows
         const long long per_tilerow = (long long)sp.nblk * nrg * sp.nseg;
         const int tr = (int)(s / per_tilerow);
         int rem = (int)(s - (long long)tr * per_tilerow);
         const int kb = rem / (nrg * sp.nseg);
         rem -= kb * nrg * sp.nseg;
-        const int rg = rem / sp.nseg, seg = rem - rg * sp.nseg;
+        int seg, rg;
+        if (sp.rows_fastest) { seg = rem / nrg; rg = rem - seg * nrg; }
+        else { rg = rem / sp.nseg; seg = rem - rg * sp.nseg; }
         const int tz = tr / g.Ty, ty = tr - tz * g.Ty;
         const int k0 = 1 + kb * sp.R, k1 = min(g.td, k0 + sp.R - 1);
         const int i0 = 1 + rg * RW;
