@@ -49,7 +49,7 @@ struct jacobi_plan {
     Geo geo;
     size_t esize;
     // options
-    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0, tblock = 1;
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0, tblock = 1, cooperative = 1;
     // residual scratch (device), sized for the residual launch
     double *partial = nullptr;
     int64_t partial_cap = 0;
@@ -288,24 +288,86 @@ int launch_tp3d(jacobi_plan *p, int depth, const void *src, void *dst, bool with
                           "3-D blocked-pass kernel launch");
 }
 
+// ---- 3-D workgroup-cooperative temporal blocking --------------------------------------------------
+bool tc3d_usable(const jacobi_plan *p, int depth)
+{
+    const Geo &g = p->geo;
+    const int nv = 16 / (int)p->esize;
+    return p->cooperative && g.ndim == 3 && depth >= jk::TC3D_MIN && depth <= jk::TC3D_MAX && g.tw % nv == 0 &&
+           g.td >= depth && (int64_t)g.Ty * g.th < 0x7fffffffLL - 64 &&
+           (int64_t)g.Tx * g.tile_stride * (int64_t)p->esize < 0x7fffffffLL;   // per-lane byte offsets are 32-bit
+}
+
+// sp.nstrips counts wavefronts (4 per work unit); *nyg_out = row groups along the whole column of tiles
+StripParams tc3d_strips(const jacobi_plan *p, int depth, int *nyg_out)
+{
+    const Geo &g = p->geo;
+    StripParams sp;
+    const int own = jk::WAVES_PER_WG * jk::tc3d_rows_per_wave(depth) - 2 * depth;
+    const int nyg = (int)ceil_div((int64_t)g.Ty * g.th, own);
+    sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, tp_segment_width(p, depth));
+    int R = (int)p->rows_per_strip;
+    if (R <= 0) {
+        // a unit pays a run-in of 2*depth planes: keep it deep, but leave ~4 workgroups per CU
+        R = g.td;
+        while (R > 8 * depth && (int64_t)g.Tz * nyg * sp.nseg * ceil_div(g.td, R) < 1024) R = (R + 1) / 2;
+    }
+    if (R > g.td) R = g.td;
+    sp.R = R;
+    sp.nblk = (int)ceil_div(g.td, R);
+    sp.nstrips = (int64_t)g.Tz * sp.nblk * sp.nseg * nyg * jk::WAVES_PER_WG;
+    sp.fused = 0;
+    sp.xcd_chunk = (int)p->xcd_chunk;
+    if (nyg_out) *nyg_out = nyg;
+    return sp;
+}
+
+int launch_tc3d(jacobi_plan *p, int depth, const void *src, void *dst, bool with_residual, hipStream_t st)
+{
+    int nyg = 0;
+    const StripParams sp = tc3d_strips(p, depth, &nyg);
+    const int64_t nwg = sp.nstrips / jk::WAVES_PER_WG;      // exactly one workgroup per unit: all of them have work
+    if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+    jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
+    a.aux = nyg;
+    const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
+    return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tc3d_f64(depth, mode, a)
+                                                     : jk::launch_tc3d_f32(depth, mode, a),
+                          "3-D cooperative blocked-pass kernel launch");
+}
+
 // What the next pass does with `left` iterations to go.  The iterations are spread evenly over
 // the fewest passes the requested depth allows (10 iterations at depth 8 run as 5 + 5, not
 // 8 + 2: a pass costs little more for being deeper).  kernel: 0 single step (needs current
-// halos), 1 two-step kernel (2-D), 2 pipelined kernel (2-D, depths 3..8), 3 pipelined 3-D
-// kernel (depths 2..3).
+// halos), 1 two-step kernel (2-D), 2 pipelined kernel (2-D, depths 3..8), 3 / 4 pipelined 3-D
+// kernels (depths 2..4).
 struct PassChoice { int depth; int kernel; };
+
+// 3-D blocked pass of this depth: 4 = workgroup-cooperative kernel, 3 = one wavefront per row group
+// (the faster one at depth 2, and the only one with option cooperative = 0), 0 = neither can run it.
+int pick_3d_kernel(const jacobi_plan *p, int depth)
+{
+    const bool per_wave = tp3d_usable(p, depth) && (p->lay.dtype == JACOBI_F64 || depth == jk::TP3D_MIN);
+    if (depth == 2 && per_wave) return 3;
+    if (tc3d_usable(p, depth)) return 4;
+    return per_wave ? 3 : 0;
+}
 
 PassChoice choose_pass(const jacobi_plan *p, int left)
 {
     int maxd = (int)(p->tblock < left ? p->tblock : left);
     if (maxd > jk::TP_MAX) maxd = jk::TP_MAX;
     if (maxd >= 2 && p->geo.ndim == 3) {
-        // fp32 passes of depth 3 are bound by arithmetic and measured slower per iteration than depth 2
-        const int deepest = p->lay.dtype == JACOBI_F64 ? jk::TP3D_MAX : jk::TP3D_MIN;
-        if (maxd > deepest) maxd = deepest;
-        const int passes = (left + maxd - 1) / maxd;
-        for (int d = (left + passes - 1) / passes; d >= jk::TP3D_MIN; --d)
-            if (tp3d_usable(p, d)) return {d, 3};
+        // fp32 passes deeper than 3 are bound by arithmetic and measured slower per iteration
+        int deepest = 0;
+        for (int d = p->lay.dtype == JACOBI_F64 ? jk::TC3D_MAX : 3; d >= 2 && !deepest; --d)
+            if (pick_3d_kernel(p, d)) deepest = d;
+        if (deepest) {
+            if (maxd > deepest) maxd = deepest;
+            const int passes = (left + maxd - 1) / maxd;
+            for (int d = (left + passes - 1) / passes; d >= 2; --d)
+                if (const int k = pick_3d_kernel(p, d)) return {d, k};
+        }
     } else if (maxd >= 2) {
         const int passes = (left + maxd - 1) / maxd;
         const int d = (left + passes - 1) / passes;
@@ -419,6 +481,7 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "xcd_chunk")) return &p->xcd_chunk;
     if (!strcmp(key, "rows_per_wave")) return &p->rows_per_wave;
     if (!strcmp(key, "tblock")) return &p->tblock;
+    if (!strcmp(key, "cooperative")) return &p->cooperative;
     return nullptr;
 }
 
@@ -556,6 +619,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         const int64_t strips = first.kernel == 0   ? make_config(plan, jk::MODE_BOTH).sp.nstrips
                                : first.kernel == 1 ? t2_strips(plan).nstrips
                                : first.kernel == 2 ? tp_strips(plan, first.depth).nstrips
+                               : first.kernel == 4 ? tc3d_strips(plan, first.depth, nullptr).nstrips
                                                    : tp3d_strips(plan, first.depth, nullptr).nstrips;
         nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
         int rc = ensure_partials(plan, nwg_res + 1);
@@ -580,7 +644,8 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         if (pc.kernel == 0)      rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
         else if (pc.kernel == 1) rc = launch_t2(plan, src, dst, with_res, st);
         else if (pc.kernel == 2) rc = launch_tp(plan, pc.depth, src, dst, with_res, st);
-        else                     rc = launch_tp3d(plan, pc.depth, src, dst, with_res, st);
+        else if (pc.kernel == 3) rc = launch_tp3d(plan, pc.depth, src, dst, with_res, st);
+        else                     rc = launch_tc3d(plan, pc.depth, src, dst, with_res, st);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));

@@ -645,28 +645,24 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
                 for (int l = 1; l <= TB; ++l) {
                     const V up = w[l - 1][p], c = w[l - 1][1 - p];
                     const int row = rho - l;             // the row this level produces
+                    // Dirichlet cells keep their value: whole rows (wave-uniform) and the one component of
+                    // a ring lane that is the ring column.  Selects, not branches: with branches the
+                    // compiler copied the whole vector around at every level (9 moves per level and row).
+                    const bool frozen_all = (top_ring && row == 0) || (bottom_ring && row == g.th + 1);
+                    const T left = from_prev_lane_or_zero(c[NV - 1]);
+                    const T right = from_next_lane_or_zero(c[0]);
                     V nw;
-                    if ((top_ring && row == 0) || (bottom_ring && row == g.th + 1)) {
-                        nw = c;                          // Dirichlet row: keeps its values
-                    } else {
-                        const T left = from_prev_lane_or_zero(c[NV - 1]);
-                        const T right = from_next_lane_or_zero(c[0]);
 #pragma unroll
-                        for (int j = 0; j < NV; ++j) {
-                            const T we = (j == 0 ? left : c[j - 1]) + (j == NV - 1 ? right : c[j + 1]);
-                            const T sn = up[j] + down[j];
-                            nw[j] = Coef<T>::quarter * (we + sn);
-                            if constexpr (MODE == MODE_BOTH) {
-                                if (l == 1 && row >= r0 && row <= r1 && owner) {
-                                    const T res = (we + sn) - Coef<T>::four * c[j];
-                                    const double rd = (double)res;
-                                    acc += rd * rd;
-                                }
-                            }
-                        }
-                        if (wave_has_ring) {
-                            if (ring_lane) {             // Dirichlet column cell keeps its value
-                                if (kind == 1) nw[NV - 1] = c[NV - 1]; else nw[0] = c[0];
+                    for (int j = 0; j < NV; ++j) {
+                        const T we = (j == 0 ? left : c[j - 1]) + (j == NV - 1 ? right : c[j + 1]);
+                        const T sn = up[j] + down[j];
+                        const bool frozen = frozen_all || (j == NV - 1 && kind == 1) || (j == 0 && kind == 2);
+                        nw[j] = frozen ? c[j] : Coef<T>::quarter * (we + sn);
+                        if constexpr (MODE == MODE_BOTH) {
+                            if (l == 1 && row >= r0 && row <= r1 && owner) {
+                                const T res = (we + sn) - Coef<T>::four * c[j];
+                                const double rd = (double)res;
+                                acc += rd * rd;
                             }
                         }
                     }
@@ -1011,31 +1007,26 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
                         st[l - 1][p][j] = d;                 // the older plane is dead: its slot takes the newest
                         if (j < l || j >= NRW - l) break;    // row not produced at level l
                         const V c = st[l - 1][1 - p][j];
+                        // Dirichlet cells keep their value (selects, not branches: see sweep2d_tp_kernel)
+                        const bool frozen_all = ring_plane[l] || ring_row[j];
+                        const V ym = st[l - 1][1 - p][j - 1], yp = st[l - 1][1 - p][j + 1];
+                        const T left = from_prev_lane_or_zero(c[NV - 1]);
+                        const T right = from_next_lane_or_zero(c[0]);
                         V nw;
-                        if (ring_plane[l] || ring_row[j]) {
-                            nw = c;                          // Dirichlet plane / row keeps its values
-                        } else {
-                            const V ym = st[l - 1][1 - p][j - 1], yp = st[l - 1][1 - p][j + 1];
-                            const T left = from_prev_lane_or_zero(c[NV - 1]);
-                            const T right = from_next_lane_or_zero(c[0]);
 #pragma unroll
-                            for (int e = 0; e < NV; ++e) {
-                                const T xx = (e == 0 ? left : c[e - 1]) + (e == NV - 1 ? right : c[e + 1]);
-                                const T yy = ym[e] + yp[e];
-                                const T zz = zm[e] + d[e];
-                                nw[e] = Coef<T>::sixth * ((xx + yy) + zz);
-                                if constexpr (MODE == MODE_BOTH) {
-                                    const int plane = kappa - 1, row = i0 - TB + j;
-                                    if (l == 1 && plane >= k0 && plane <= k1 && j >= TB && j < TB + RW && row <= g.th && owner) {
-                                        const T res = ((xx + yy) + zz) - Coef<T>::six * c[e];
-                                        const double rd = (double)res;
-                                        acc += rd * rd;
-                                    }
-                                }
-                            }
-                            if (wave_has_ring) {
-                                if (ring_lane) {
-                                    if (kind == 1) nw[NV - 1] = c[NV - 1]; else nw[0] = c[0];
+                        for (int e = 0; e < NV; ++e) {
+                            const T xx = (e == 0 ? left : c[e - 1]) + (e == NV - 1 ? right : c[e + 1]);
+                            const T yy = ym[e] + yp[e];
+                            const T zz = zm[e] + d[e];
+                            const T sum = (xx + yy) + zz;
+                            const bool frozen = frozen_all || (e == NV - 1 && kind == 1) || (e == 0 && kind == 2);
+                            nw[e] = frozen ? c[e] : Coef<T>::sixth * sum;
+                            if constexpr (MODE == MODE_BOTH) {
+                                const int plane = kappa - 1, row = i0 - TB + j;
+                                if (l == 1 && plane >= k0 && plane <= k1 && j >= TB && j < TB + RW && row <= g.th && owner) {
+                                    const T res = sum - Coef<T>::six * c[e];
+                                    const double rd = (double)res;
+                                    acc += rd * rd;
                                 }
                             }
                         }
@@ -1048,6 +1039,199 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
                     }
                 }
             }
+        }
+    }
+    if constexpr (MODE == MODE_BOTH) {
+        const double tot = wg_sum(acc, red);
+        if (threadIdx.x == 0) partial[lwg] = tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// 3-D, TB time steps per pass, pipelined along z, with the four wavefronts of a workgroup
+// sharing one range of rows.  Wavefront w holds rows [w*NR, (w+1)*NR) of the workgroup's
+// 4*NR rows (per level two planes of them, in registers); the rows just above and below a
+// wavefront's range belong to its neighbours in the workgroup, which publish their first and last
+// row of every level's newest plane in LDS each step (double-buffered: one barrier per step).
+// Only the workgroup as a whole carries TB ghost rows per side, so 4*NR rows are loaded per
+// 4*NR - 2*TB rows stored.  Rows are counted along the whole column of tiles (a workgroup's rows
+// may lie in two tiles).  Columns, planes, ring handling and addressing as in sweep3d_tp_kernel.
+// Rows outside the shrinking range of a level are computed anyway (nothing valid reads them).
+// Every workgroup of the grid has work and all its wavefronts take the same number of steps.
+// Bit-identical to TB single steps.  Needs tw a multiple of the vector width and td >= TB.
+// ------------------------------------------------------------------------------------
+template <typename T, int MODE, int TB, int NR, int MINW>
+__global__ __launch_bounds__(WG, MINW) void sweep3d_tc_kernel(Geo g, StripParams sp, int nyg,
+                                                              const T *__restrict__ src, T *__restrict__ dst,
+                                                              double *__restrict__ partial)
+{
+    using V = typename Vec<T>::type;
+    using G3 = TpGeometry<T, TB, 3>;
+    constexpr int NV = Vec<T>::N;
+    typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
+    constexpr int GL = G3::GHOST_LANES;
+    constexpr int GH = GL * NV;
+    constexpr int SEGW = G3::SEGW;
+    constexpr int WROWS = WAVES_PER_WG * NR;     // rows a workgroup holds
+    constexpr int OWN = WROWS - 2 * TB;          // rows it stores
+    static_assert(OWN >= 1, "ghost rows must leave something to own");
+    static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
+    __shared__ V xch[2][TB][WAVES_PER_WG][2][WAVE];   // [step parity][level][wavefront][first / last row][lane]
+    __shared__ double red[WAVES_PER_WG];
+
+    const int lane = threadIdx.x % WAVE;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const long long lwg = xcd_logical_wg(sp.xcd_chunk);     // a work unit: the grid has exactly one workgroup each
+    double acc = 0.0;
+
+    // unit = z-layer of tiles -> plane block -> column segment -> row group
+    const int per_layer = sp.nblk * sp.nseg * nyg;
+    const int tz = (int)(lwg / per_layer);
+    int rem = (int)(lwg - (long long)tz * per_layer);
+    const int kb = rem / (sp.nseg * nyg);
+    rem -= kb * sp.nseg * nyg;
+    const int seg = rem / nyg, yg = rem - seg * nyg;
+    const int k0 = 1 + kb * sp.R, k1 = min(g.td, k0 + sp.R - 1);
+    const int nrows = g.Ty * g.th;               // rows 1..nrows along the column of tiles; 0 and nrows+1: ring
+    const int y0 = 1 + yg * OWN;                 // first row this workgroup stores
+    const long long tilerow = (long long)g.Tx * g.tile_stride;
+
+    // ---- columns of this lane along the row of tiles (see sweep3d_tp_kernel)
+    const int wrow = g.Tx * g.tw;
+    const int gc = seg * SEGW - GH + lane * NV;
+    int kind = 0, txx = 0, cc = 0;   // 0 tile cells, 1 W ring in last component, 2 E ring in first, 3 nothing
+    if (gc < 0) kind = gc == -NV ? 1 : 3;
+    else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
+    else { txx = gc / g.tw; cc = gc - txx * g.tw; }
+    long long lane_elems = 0;
+    if (kind == 0) lane_elems = (long long)txx * g.tile_stride + cc;
+    else if (kind == 1) lane_elems = g.xoff - (NV - 1);
+    else if (kind == 2) lane_elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
+    const unsigned lane_bytes = (unsigned)(lane_elems * (long long)sizeof(T));
+    const bool ring_lane = kind == 1 || kind == 2;
+    const bool wave_has_ring = __any(ring_lane) != 0;
+    const bool owner = lane >= GL && lane < WAVE - GL && kind == 0;
+    const bool z_lo_ring = tz == 0, z_hi_ring = tz == g.Tz - 1;
+
+    // ---- this wavefront's rows j = 0..NR-1: row y0 - TB + wave*NR + j of the column of tiles
+    long long row_base[NR];      // element offset of the row inside a z-layer of tiles
+    int row_to_halo[NR];         // (x-halo entry of the row) - (first cell of the row), elements, plane part aside
+    bool ring_row[NR], own_row[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const int gi = wave * NR + j;
+        const int gy = y0 - TB + gi;
+        int tyy, rr;
+        ring_row[j] = false;
+        if (gy <= 0) { tyy = 0; rr = 0; ring_row[j] = true; }
+        else if (gy > nrows) { tyy = g.Ty - 1; rr = g.th + 1; ring_row[j] = true; }
+        else { tyy = (gy - 1) / g.th; rr = gy - tyy * g.th; }
+        own_row[j] = gi >= TB && gi < WROWS - TB && gy <= nrows;
+        row_base[j] = (long long)tyy * tilerow + (long long)rr * g.pitch;
+        row_to_halo[j] = rr - rr * g.pitch;
+    }
+    long long pl_cells;
+    int pl_to_halo;
+    auto locate_plane = [&](int kappa) {
+        int tzz = tz, kk;
+        kappa = min(kappa, g.td + TB);
+        if (kappa <= 0) {
+            if (!z_lo_ring) { tzz = tz - 1; kk = g.td + kappa; }
+            else kk = 0;
+        } else if (kappa > g.td) {
+            if (!z_hi_ring) { tzz = tz + 1; kk = kappa - g.td; }
+            else kk = g.td + 1;
+        } else kk = kappa;
+        pl_cells = (long long)tzz * g.Ty * tilerow + (long long)kk * g.plane;
+        pl_to_halo = kk * g.rows - (int)((long long)kk * g.plane);
+    };
+    auto load_row = [&](int j) -> V {
+        const T *rowp = src + (pl_cells + row_base[j]);
+        unsigned off = lane_bytes;
+        if (wave_has_ring) off += ring_lane ? (unsigned)((pl_to_halo + row_to_halo[j]) * (int)sizeof(T)) : 0u;
+        return *(const VU *)((const char *)rowp + off);
+    };
+
+    V st[TB][2][NR];                 // per level l-1: the two newest planes; roles swap each step
+#pragma unroll
+    for (int l = 0; l < TB; ++l)
+#pragma unroll
+        for (int j = 0; j < NR; ++j) st[l][0][j] = st[l][1][j] = V(0);
+
+    const int nsteps = (k1 - k0 + 1) + 2 * TB;              // planes kappa = k0-TB .. k1+TB
+    // The plane entering the pipeline, loaded one step ahead: as soon as a row has been taken, the load
+    // of the same row of the next plane is issued in its place, so only ONE plane of loads is live.
+    V ld[NR];
+    locate_plane(k0 - TB);
+#pragma unroll
+    for (int j = 0; j < NR; ++j) ld[j] = load_row(j);
+
+    const long long out_layer = (long long)tz * g.Ty * tilerow;
+    const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, WAVES_PER_WG - 1);
+
+    for (int q0 = 0; q0 < nsteps; q0 += 2) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {                        // p: slot holding the OLDER plane of every level
+            const int q = q0 + p;
+            if (q >= nsteps) break;
+            const int kappa = k0 - TB + q;                   // plane of u(t) entering the pipeline
+            locate_plane(kappa + 1);
+            bool ring_plane[TB + 1];
+#pragma unroll
+            for (int l = 1; l <= TB; ++l)
+                ring_plane[l] = (z_lo_ring && kappa - l == 0) || (z_hi_ring && kappa - l == g.td + 1);
+            const int oplane = kappa - TB;
+            const bool store_plane = q >= 2 * TB && oplane <= k1;
+            const long long out_plane = out_layer + (long long)oplane * g.plane;
+#pragma unroll
+            for (int j = 0; j < NR; ++j) {
+                V d = ld[j];                                 // newest plane of the level below, row j
+                ld[j] = load_row(j);                         // same row of the next plane, for the next step
+#pragma unroll
+                for (int l = 1; l <= TB; ++l) {
+                    const V zm = st[l - 1][p][j];
+                    st[l - 1][p][j] = d;                     // the older plane is dead: its slot takes the newest
+                    // the neighbouring wavefronts need this plane of our first and last row in the next step
+                    if (j == 0) xch[1 - p][l - 1][wave][0][lane] = d;
+                    if (j == NR - 1) xch[1 - p][l - 1][wave][1][lane] = d;
+                    const V c = st[l - 1][1 - p][j];
+                    V ym, yp;
+                    if (j == 0) ym = xch[p][l - 1][wave_up][1][lane]; else ym = st[l - 1][1 - p][j - 1];
+                    if (j == NR - 1) yp = xch[p][l - 1][wave_dn][0][lane]; else yp = st[l - 1][1 - p][j + 1];
+                    const T left = from_prev_lane_or_zero(c[NV - 1]);
+                    const T right = from_next_lane_or_zero(c[0]);
+                    // Dirichlet cells keep their value: whole planes and rows (wave-uniform), and the one
+                    // component of a ring lane that is the ring column.  Selects, not branches: branches
+                    // made the compiler copy the whole vector around at every level.
+                    const bool frozen_all = ring_plane[l] || ring_row[j];
+                    V nw;
+#pragma unroll
+                    for (int e = 0; e < NV; ++e) {
+                        const T xx = (e == 0 ? left : c[e - 1]) + (e == NV - 1 ? right : c[e + 1]);
+                        const T yy = ym[e] + yp[e];
+                        const T zz = zm[e] + d[e];
+                        const T sum = (xx + yy) + zz;
+                        const bool frozen = frozen_all || (e == NV - 1 && kind == 1) || (e == 0 && kind == 2);
+                        nw[e] = frozen ? c[e] : Coef<T>::sixth * sum;
+                        if constexpr (MODE == MODE_BOTH) {
+                            const int plane = kappa - 1;
+                            if (l == 1 && plane >= k0 && plane <= k1 && own_row[j] && owner) {
+                                const T res = sum - Coef<T>::six * c[e];
+                                const double rd = (double)res;
+                                acc += rd * rd;
+                            }
+                        }
+                    }
+                    d = nw;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // after TB levels `d` is u(t+TB) of plane kappa-TB
+                if (store_plane && own_row[j] && owner)
+                    __builtin_nontemporal_store(d, (V *)((char *)(dst + (out_plane + row_base[j])) + lane_bytes));
+                // keep the rows in program order: hoisting later rows' loads and LDS reads costs registers
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();                                 // next step reads what this one published
         }
     }
     if constexpr (MODE == MODE_BOTH) {

@@ -12,10 +12,9 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
     T *dst = (T *)a.dst;
     // Template arguments after the depth: rows loaded ahead (4), and the occupancy the compiler
     // must fit in wavefronts per SIMD - the largest that compiles without register spills
-    // (fp64: depth 8 needs 158 VGPRs, depth 6 126, with the residual a few more; the fp32 variants need one
-    // step more).
-    constexpr bool F32 = sizeof(T) == 4;
-#define JK_MINW(MODE_, TB_) (F32 ? ((TB_) >= 7 ? 2 : (TB_) >= 5 ? 3 : 4) : ((TB_) >= 7 || ((TB_) == 6 && MODE_ == MODE_BOTH) ? 3 : 4))
+    // (depth 8 needs 150 VGPRs, depth 6 118, with the residual about 18 more; only the
+    // depth-8 variants with the residual spill, 3 dwords, rather than drop to 2 wavefronts).
+#define JK_MINW(MODE_, TB_) ((TB_) >= 7 || ((TB_) == 6 && MODE_ == MODE_BOTH) ? 3 : 4)
 #define JK_L(MODE_, TB_) \
     hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(MODE_, TB_)>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
 #define JK_D(MODE_)                         \

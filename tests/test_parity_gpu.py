@@ -304,25 +304,34 @@ CASES_3D_TB = [
     ((40, 18, 256), (2, 3, 1), 10, 5),      # tw = 256: three column segments, last one ragged
     ((20, 14, 448), (1, 1, 4), 8, 8),       # 4 tiles of 112 columns = one wavefront of owned columns each
     ((33, 9, 64), (1, 1, 32), 5, 5),        # tw = 2 (one fp64 vector)
+    ((12, 60, 40), (3, 30, 1), 9, 4),       # th = 2: a workgroup's rows span a dozen tiles
+    ((10, 57, 24), (2, 57, 2), 6, 3),       # th = 1
+    ((9, 100, 16), (1, 4, 1), 8, 8),        # th = 25: row groups straddle tile boundaries at odd places
 ]
 
 
-@pytest.mark.parametrize("opts", [dict(tblock=2), dict(tblock=8, rows_per_wave=2), dict(tblock=2, rows_per_wave=4),
+@pytest.mark.parametrize("opts", [dict(tblock=2), dict(tblock=3), dict(tblock=4), dict(tblock=8, rows_per_strip=3),
                                   dict(tblock=2, rows_per_strip=1), dict(tblock=3, rows_per_strip=5, xcd_chunk=1),
-                                  dict(tblock=2, rows_per_strip=4096, rows_per_wave=2)])
+                                  dict(tblock=4, rows_per_strip=4096, nontemporal=0),
+                                  # one wavefront per row group instead of a workgroup sharing its rows
+                                  dict(tblock=2, cooperative=0), dict(tblock=8, rows_per_wave=2, cooperative=0),
+                                  dict(tblock=2, rows_per_wave=4, cooperative=0),
+                                  dict(tblock=2, rows_per_strip=1, cooperative=0),
+                                  dict(tblock=3, rows_per_strip=5, xcd_chunk=1, cooperative=0),
+                                  dict(tblock=2, rows_per_strip=4096, rows_per_wave=2, cooperative=0)])
 @pytest.mark.parametrize("dims,tiles,iters,every", CASES_3D_TB)
 def test_3d_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, iters, every, opts):
     a = random_padded(dims, seed=sum(dims) + iters)
     check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
 
 
-@pytest.mark.parametrize("tblock,rows_per_wave", [(2, 2), (2, 4), (3, 0)])
-def test_3d_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock, rows_per_wave):
+@pytest.mark.parametrize("tblock,rows_per_wave,cooperative", [(2, 2, 0), (2, 4, 0), (3, 0, 0), (2, 0, 1), (3, 0, 1), (4, 0, 1)])
+def test_3d_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock, rows_per_wave, cooperative):
     a = random_padded((24, 20, 72), dtype=np.float32, seed=17)
-    check(*run_case(H, oracle_mod, a, (2, 2, 3), 11, 4, tblock=tblock, rows_per_wave=rows_per_wave))
+    check(*run_case(H, oracle_mod, a, (2, 2, 3), 11, 4, tblock=tblock, rows_per_wave=rows_per_wave, cooperative=cooperative))
     b = random_padded((36, 22, 140), seed=19)
     ref, ref_res = oracle_mod.run(b, 13, 3)
-    r = H.JacobiRun((36, 22, 140), (3, 2, 5), tblock=tblock, rows_per_wave=rows_per_wave)
+    r = H.JacobiRun((36, 22, 140), (3, 2, 5), tblock=tblock, rows_per_wave=rows_per_wave, cooperative=cooperative)
     try:
         r.load(b)
         res = r.run(13, 3, fuse_residual=True)

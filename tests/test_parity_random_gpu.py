@@ -43,7 +43,8 @@ def make_cases(ndim, count, seed, blocked_3d=False):
         else:
             opts["rows_per_wave"] = int(rng.choice([0, 1, 2, 4]))
             if blocked_3d:
-                opts["tblock"] = int(rng.choice([2, 3, 8]))
+                opts["tblock"] = int(rng.choice([2, 3, 4, 8]))
+                opts["cooperative"] = int(rng.integers(0, 2))
         fuse_res = bool(rng.integers(0, 2))
         cases.append((dims, tiles, iters, every, opts, fuse_res))
     return cases
