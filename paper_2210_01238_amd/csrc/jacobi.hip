@@ -298,24 +298,24 @@ bool tc3d_usable(const jacobi_plan *p, int depth)
            (int64_t)g.Tx * g.tile_stride * (int64_t)p->esize < 0x7fffffffLL;   // per-lane byte offsets are 32-bit
 }
 
-// sp.nstrips counts wavefronts (4 per work unit); *nyg_out = row groups along the whole column of tiles
+// sp.nstrips = 4 per work unit (one partial sum per unit); *nyg_out = row groups along the whole column of tiles
 StripParams tc3d_strips(const jacobi_plan *p, int depth, int *nyg_out)
 {
     const Geo &g = p->geo;
     StripParams sp;
-    const int own = jk::WAVES_PER_WG * jk::tc3d_rows_per_wave(depth) - 2 * depth;
+    const int own = jk::TC3D_WAVES * jk::tc3d_rows_per_wave(depth) - 2 * depth;
     const int nyg = (int)ceil_div((int64_t)g.Ty * g.th, own);
     sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, tp_segment_width(p, depth));
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
         // a unit pays a run-in of 2*depth planes: keep it deep, but leave ~4 workgroups per CU
         R = g.td;
-        while (R > 8 * depth && (int64_t)g.Tz * nyg * sp.nseg * ceil_div(g.td, R) < 1024) R = (R + 1) / 2;
+        while (R > 8 * depth && (int64_t)g.Tz * nyg * sp.nseg * ceil_div(g.td, R) < 4096 / jk::TC3D_WAVES) R = (R + 1) / 2;
     }
     if (R > g.td) R = g.td;
     sp.R = R;
     sp.nblk = (int)ceil_div(g.td, R);
-    sp.nstrips = (int64_t)g.Tz * sp.nblk * sp.nseg * nyg * jk::WAVES_PER_WG;
+    sp.nstrips = (int64_t)g.Tz * sp.nblk * sp.nseg * nyg * jk::WAVES_PER_WG;   // partial sums: one per unit
     sp.fused = 0;
     sp.xcd_chunk = (int)p->xcd_chunk;
     if (nyg_out) *nyg_out = nyg;

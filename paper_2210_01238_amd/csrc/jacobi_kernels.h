@@ -1048,20 +1048,20 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
 }
 
 // ------------------------------------------------------------------------------------
-// 3-D, TB time steps per pass, pipelined along z, with the four wavefronts of a workgroup
+// 3-D, TB time steps per pass, pipelined along z, with the WPG wavefronts of a workgroup
 // sharing one range of rows.  Wavefront w holds rows [w*NR, (w+1)*NR) of the workgroup's
-// 4*NR rows (per level two planes of them, in registers); the rows just above and below a
+// WPG*NR rows (per level two planes of them, in registers); the rows just above and below a
 // wavefront's range belong to its neighbours in the workgroup, which publish their first and last
 // row of every level's newest plane in LDS each step (double-buffered: one barrier per step).
-// Only the workgroup as a whole carries TB ghost rows per side, so 4*NR rows are loaded per
-// 4*NR - 2*TB rows stored.  Rows are counted along the whole column of tiles (a workgroup's rows
+// Only the workgroup as a whole carries TB ghost rows per side, so WPG*NR rows are loaded per
+// WPG*NR - 2*TB rows stored.  Rows are counted along the whole column of tiles (a workgroup's rows
 // may lie in two tiles).  Columns, planes, ring handling and addressing as in sweep3d_tp_kernel.
 // Rows outside the shrinking range of a level are computed anyway (nothing valid reads them).
 // Every workgroup of the grid has work and all its wavefronts take the same number of steps.
 // Bit-identical to TB single steps.  Needs tw a multiple of the vector width and td >= TB.
 // ------------------------------------------------------------------------------------
-template <typename T, int MODE, int TB, int NR, int MINW>
-__global__ __launch_bounds__(WG, MINW) void sweep3d_tc_kernel(Geo g, StripParams sp, int nyg,
+template <typename T, int MODE, int TB, int NR, int WPG, int MINW>
+__global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, StripParams sp, int nyg,
                                                               const T *__restrict__ src, T *__restrict__ dst,
                                                               double *__restrict__ partial)
 {
@@ -1072,12 +1072,12 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tc_kernel(Geo g, StripParams
     constexpr int GL = G3::GHOST_LANES;
     constexpr int GH = GL * NV;
     constexpr int SEGW = G3::SEGW;
-    constexpr int WROWS = WAVES_PER_WG * NR;     // rows a workgroup holds
+    constexpr int WROWS = WPG * NR;              // rows a workgroup (WPG wavefronts) holds
     constexpr int OWN = WROWS - 2 * TB;          // rows it stores
     static_assert(OWN >= 1, "ghost rows must leave something to own");
     static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
-    __shared__ V xch[2][TB][WAVES_PER_WG][2][WAVE];   // [step parity][level][wavefront][first / last row][lane]
-    __shared__ double red[WAVES_PER_WG];
+    __shared__ V xch[2][TB][WPG][2][WAVE];   // [step parity][level][wavefront][first / last row][lane]
+    __shared__ double red[WPG];
 
     const int lane = threadIdx.x % WAVE;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
@@ -1167,7 +1167,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tc_kernel(Geo g, StripParams
     for (int j = 0; j < NR; ++j) ld[j] = load_row(j);
 
     const long long out_layer = (long long)tz * g.Ty * tilerow;
-    const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, WAVES_PER_WG - 1);
+    const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, WPG - 1);
 
     for (int q0 = 0; q0 < nsteps; q0 += 2) {
 #pragma unroll

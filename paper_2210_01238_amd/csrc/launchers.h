@@ -39,8 +39,9 @@ hipError_t launch_tp3d_f64(int depth, int rows_per_wave, int mode, const LaunchA
 hipError_t launch_tp3d_f32(int depth, int rows_per_wave, int mode, const LaunchArgs &a);
 
 // 3-D, workgroup-cooperative blocked passes: rows one wavefront holds at each depth (a workgroup stores
-// 4 * rows - 2 * depth rows per plane)
+// TC3D_WAVES * rows - 2 * depth rows per plane)
 constexpr int TC3D_MIN = 2, TC3D_MAX = 4;
+constexpr int TC3D_WAVES = 8;   // wavefronts per workgroup (one workgroup per CU at 2 wavefronts per SIMD)
 constexpr int tc3d_rows_per_wave(int depth) { return depth == 2 ? 8 : depth == 3 ? 6 : 5; }
 hipError_t launch_tc3d_f64(int depth, int mode, const LaunchArgs &a);
 hipError_t launch_tc3d_f32(int depth, int mode, const LaunchArgs &a);

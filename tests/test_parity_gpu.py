@@ -291,7 +291,7 @@ def test_temporal_blocking_falls_back_on_thin_tiles_and_3d(H, oracle_mod):
     b = random_padded((12, 10, 41), seed=6)
     check(*run_case(H, oracle_mod, b, (2, 1, 1), 5, 5, tblock=2))    # 3-D, odd tile width: single steps
     c = random_padded((12, 5, 40), seed=8)
-    check(*run_case(H, oracle_mod, c, (2, 5, 2), 5, 5, tblock=2))    # 3-D, tiles one row high: single steps
+    check(*run_case(H, oracle_mod, c, (2, 5, 2), 5, 5, tblock=2, cooperative=0))    # 3-D, tiles one row high: single steps
 
 
 CASES_3D_TB = [
