@@ -192,7 +192,7 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
  *                    through; 0 = choose from the shape: 8 rows / 16 planes for single steps,
- *                    128 rows for blocked passes of depth >= 3 (default 0)
+ *                    up to 128 rows / the tile depth for blocked passes (default 0)
  *   "nontemporal"    0 | 2   2 = results are written with streaming (non-temporal) stores
  *                    (default 2).  Streaming loads were measured slower (border rows are
  *                    re-read from cache) and are not offered.  Blocked passes always stream.
@@ -204,15 +204,21 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
  *   "tblock"         1..8    temporal blocking depth: jacobi_sweep advances up to this many
- *                    iterations per pass over memory (2-D only).  The iterations of a call are
- *                    spread evenly over the fewest passes the depth allows (10 iterations at
- *                    depth 8 run as 5 + 5).  Passes of depth 3..8 need a tile width that is a
- *                    multiple of 16 bytes and a tile height >= depth;
- *                    depth 2 needs tiles >= 2 x 2; otherwise single steps are used.  Blocked
- *                    passes read the cells they need beyond a tile straight from the
- *                    neighbouring tiles, so the exchange is part of their loads and they leave
- *                    the halo cells alone.  Results are bit-identical for every depth
+ *                    iterations per pass over memory (3-D: at most 4 in fp64, 3 in fp32).  The
+ *                    iterations of a call are spread evenly over the fewest passes the depth
+ *                    allows (10 iterations at depth 8 run as 5 + 5; in 3-D as 4 + 3 + 3).
+ *                    2-D passes of depth 3..8 need a tile width that is a multiple of 16 bytes
+ *                    and a tile height >= depth, depth 2 needs tiles >= 2 x 2; 3-D passes need
+ *                    a tile width that is a multiple of 16 bytes and a tile depth >= the pass
+ *                    depth; otherwise single steps are used.  Blocked passes read the cells they
+ *                    need beyond a tile straight from the neighbouring tiles, so the exchange is
+ *                    part of their loads and they leave the halo cells alone.  Results are
+ *                    bit-identical for every depth
  *                    (default 1: one halo exchange and one update per iteration)
+ *   "cooperative"    0 | 1   3-D blocked passes: 1 = the wavefronts of a workgroup share one range
+ *                    of rows and hand each other their border rows through LDS (depths 3 and 4,
+ *                    and depth 2 where the other kernel cannot run); 0 = every wavefront carries
+ *                    its own ghost rows (depths 2 and 3, needs a tile height >= depth) (default 1)
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
  *                    made by jacobi_sweep (read with jacobi_profile_read)
  * None of the options changes any result bit.
@@ -223,7 +229,7 @@ int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);
 /*
  * With option "profile" = 1: waits for the recorded events, returns the summed
  * duration (milliseconds) and number of update-kernel launches since the last read
- * (with "tblock" = 2 a launch may cover two iterations),
+ * (with "tblock" > 1 a launch may cover several iterations),
  * and resets the record.  At most 8192 launches are recorded between reads; later
  * ones are not timed (and not counted).  Errors: EINVAL, EHIP.
  */
