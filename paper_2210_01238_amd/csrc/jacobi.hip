@@ -308,9 +308,18 @@ StripParams tc3d_strips(const jacobi_plan *p, int depth, int *nyg_out)
     sp.nseg = (int)ceil_div((int64_t)g.Tx * g.tw, tp_segment_width(p, depth));
     int R = (int)p->rows_per_strip;
     if (R <= 0) {
-        // a unit pays a run-in of 2*depth planes: keep it deep, but leave ~4 workgroups per CU
+        // One workgroup runs per CU and all units of a launch take the same time (R + 2*depth plane
+        // steps), so the launch takes about ceil(units / CUs) rounds of that: pick the split of the tile
+        // depth that minimises rounds x steps (deep units amortise the run-in, more units fill the last round).
+        int64_t best = -1;
         R = g.td;
-        while (R > 8 * depth && (int64_t)g.Tz * nyg * sp.nseg * ceil_div(g.td, R) < 4096 / jk::TC3D_WAVES) R = (R + 1) / 2;
+        for (int nblk = 1; nblk <= 16 && nblk <= g.td; ++nblk) {
+            const int r = (int)ceil_div(g.td, nblk);
+            if ((int)ceil_div(g.td, r) != nblk) continue;
+            const int64_t units = (int64_t)g.Tz * nyg * sp.nseg * nblk;
+            const int64_t cost = ceil_div(units, jk::NUM_CU) * (r + 2 * depth);
+            if (best < 0 || cost < best) { best = cost; R = r; }
+        }
     }
     if (R > g.td) R = g.td;
     sp.R = R;

@@ -26,6 +26,7 @@ constexpr int WAVE = 64;
 constexpr int WAVES_PER_WG = 4;
 constexpr int WG = WAVE * WAVES_PER_WG;
 constexpr int NUM_XCD = 8;
+constexpr int NUM_CU = 256;         // compute units of the chip
 
 // Geometry of a plan, passed to kernels by value.
 struct Geo {
