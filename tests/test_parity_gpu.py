@@ -393,25 +393,29 @@ def test_sweep_can_be_captured_in_a_hip_graph(H, oracle_mod):
     caller may record it into a HIP graph and replay it; every replay must equal the eager result."""
     import torch
     w = gen.WORKLOADS["C1"]
-    a = gen.generate(w)
-    ref10, _ = oracle_mod.run(a, 10)
-    ref30, _ = oracle_mod.run(a, 30)
-    for opts in (dict(), dict(tblock=8)):
-        r = H.JacobiRun(w.dims, w.tiles, **opts)
+    a2 = gen.generate(w)
+    a3 = random_padded((24, 20, 36), seed=77)
+    # n iterations per call; an even number of passes, so the result is back in the source buffer
+    cases = [(a2, w.tiles, dict(), 10), (a2, w.tiles, dict(tblock=8), 10),
+             (a3, (2, 2, 3), dict(), 8), (a3, (2, 2, 3), dict(tblock=4), 8),
+             (a3, (2, 2, 3), dict(tblock=2, cooperative=0), 8)]
+    for a, tiles, opts, n in cases:
+        dims = [x - 2 for x in a.shape]
+        r = H.JacobiRun(dims, tiles, **opts)
         try:
             r.load(a)
             s = torch.cuda.Stream()
             s.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(s):
-                r.sweep(10)                       # eager, on the side stream (also warms up)
+                r.sweep(n)                        # eager, on the side stream (also warms up)
             torch.cuda.current_stream().wait_stream(s)
             torch.cuda.synchronize()
-            assert np.array_equal(r.fetch(), ref10)
-            # record 10 more iterations starting from the current buffer
+            assert np.array_equal(r.fetch(), oracle_mod.run(a, n)[0])
+            # record n more iterations starting from the current buffer
             src, dst = r.cur, r.other()
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=s):
-                fin = H.B.jacobi_sweep(r.plan, src.data_ptr(), dst.data_ptr(), 10,
+                fin = H.B.jacobi_sweep(r.plan, src.data_ptr(), dst.data_ptr(), n,
                                        int(torch.cuda.current_stream().cuda_stream))
             assert fin == src.data_ptr()          # even count: result back in the source buffer
             for k in range(2):                    # two replays with eager work in between
@@ -419,8 +423,7 @@ def test_sweep_can_be_captured_in_a_hip_graph(H, oracle_mod):
                 torch.cuda.synchronize()
                 got = r.fetch()
                 torch.cuda.synchronize()
-                exp, _ = oracle_mod.run(a, 20 + 10 * k)
+                exp, _ = oracle_mod.run(a, 2 * n + n * k)
                 assert np.array_equal(got, exp), (opts, k)
-            assert np.array_equal(r.fetch(), ref30)
         finally:
             r.close()
