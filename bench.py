@@ -72,6 +72,8 @@ def main() -> int:
                     help="depth limit of the extra temporal-blocking measurement (3-D passes advance 2 iterations)")
     ap.add_argument("--no-temporal-blocking", action="store_true",
                     help="skip the extra measurement with several iterations per pass")
+    ap.add_argument("--tasks", default="1,16", help="tiles per task and streams of the extra task-execution "
+                    "measurement (jacobi_sweep_tasks); empty string skips it")
     ap.add_argument("--separate-residual", action="store_true",
                     help="compute every residual with the stand-alone reduction pass")
     ap.add_argument("--option", action="append", default=[], help="key=value passed to jacobi_set_option")
@@ -167,9 +169,39 @@ def main() -> int:
             "passes_timed": tb_n,
             "iterations_per_pass": round(every * K / max(tb_n, 1), 3),
             "residuals_match_single_step_1e-12": all(abs(x - y) <= 1e-12 * abs(y) for x, y in zip(tb_res, residuals)),
-            "note": "same iterations, bit-identical grids; a pass advances up to `tblock` iterations (3-D: up to 3) "
+            "note": "same iterations, bit-identical grids; a pass advances up to `tblock` iterations (3-D: up to 4) "
                     "and reads the rim it needs from the neighbouring tiles itself instead of a halo exchange "
                     "per iteration",
+        }
+
+    # optional: the same schedule executed as per-tile tasks over several streams (the paper's execution model)
+    tasks = None
+    if args.tasks and fused:
+        grp, nstr = (int(x) for x in args.tasks.split(","))
+
+        def task_steps(n: int) -> None:
+            for i in range(n):
+                run.sweep_tasks(every, grp, nstr)
+                run.residual_async(res_dev[i:i + 1])
+
+        task_steps(W)
+        run.load(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        task_steps(K)
+        torch.cuda.synchronize()
+        t_tasks = time.perf_counter() - t0
+        t_res = res_dev[:K].cpu().tolist()
+        tasks = {
+            "tiles_per_task": grp,
+            "streams": nstr,
+            "tasks_per_iteration": -(-int(np.prod(w.tiles)) // grp),
+            "value": round(lups / t_tasks / 1e9, 3),
+            "unit": "GLUP/s",
+            "ms_per_step": round(t_tasks / K * 1e3, 4),
+            "residuals_match_single_launch_1e-12": all(abs(x - y) <= 1e-12 * abs(y) for x, y in zip(t_res, residuals)),
+            "note": "same iterations, bit-identical grids; every group of tiles is a task per iteration, ordered "
+                    "only by events on the tasks of the previous iteration that it reads from",
         }
 
     # practical ceiling: a plain streaming copy of one grid into the other (same bytes in and out)
@@ -228,6 +260,8 @@ def main() -> int:
 
     if tb is not None:
         out["temporal_blocking"] = tb
+    if tasks is not None:
+        out["task_execution"] = tasks
 
     if not args.no_cpu_baseline:
         import oracle

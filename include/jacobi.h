@@ -165,6 +165,25 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
                           void **final, double *residual_in_dev);
 
 /*
+ * jacobi_sweep_tasks: the same `iters` iterations as jacobi_sweep, executed as the paper
+ * structures them (Sec. IV-A "Heterogeneous Tasks", Sec. IV-B "Execution Model", Sec. VI-A
+ * "Enabling Concurrent GPU Operations"): every group of `tiles_per_task` consecutive tiles
+ * is one task per iteration (update of its tiles, which also pushes their edge cells into
+ * the neighbouring tiles' halo cells); a task's dependencies follow from what it reads and
+ * writes - it waits for the tasks of the previous iteration that own its tiles and their
+ * face neighbours - and the tasks are issued round-robin to `nstreams` streams owned by
+ * the plan (default priority), ordered among each other by events only.  The work is
+ * forked from and joined back into `stream`, so the call is asynchronous and in order
+ * with other work on `stream`.  It must not be recorded into a HIP graph (EINVAL while
+ * `stream` is capturing).  Results are bit-identical to jacobi_sweep.  Ignores "tblock".
+ * Needs option "fused" = 1; tiles_per_task >= 1 (values above the tile count mean one
+ * task); 1 <= nstreams <= 16.  Streams and events are created on first use (this call
+ * allocates) and live until jacobi_destroy.  Errors: EINVAL, EHIP.
+ */
+int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int tiles_per_task,
+                       int nstreams, void *stream, void **final);
+
+/*
  * halo_exchange: for every pair of face-adjacent tiles, copy each tile's edge cells
  * into the other's halo cells, in place in `grid` (paper Sec. VI-C: pack, transfer,
  * unpack - on one device the three collapse into one gather-scatter copy).

@@ -11,6 +11,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <algorithm>
 #include <vector>
 
 using jk::Geo;
@@ -36,6 +37,7 @@ int fail_hip(hipError_t e, const char *what)
         if (e_ != hipSuccess) return fail_hip(e_, #expr);    \
     } while (0)
 
+constexpr int MAX_TASK_STREAMS = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 
@@ -56,6 +58,11 @@ struct jacobi_plan {
     // profiling events around update launches
     std::vector<hipEvent_t> ev;   // pairs: 2*i start, 2*i+1 stop
     int64_t ev_used = 0;
+    // task-based execution (jacobi_sweep_tasks): stream pool, events, and the dependency lists
+    std::vector<hipStream_t> task_streams;
+    std::vector<hipEvent_t> task_events;            // 2 per task (iteration parity), then fork, then 1 per stream
+    int task_group = 0;                             // tiles per task the lists below were built for
+    std::vector<std::vector<int>> task_deps;        // tasks whose previous-iteration output a task reads
 };
 
 namespace {
@@ -122,10 +129,16 @@ int launch_checked(hipError_t e, const char *what)
     return JACOBI_OK;
 }
 
-// Single-step pass over `src` in the given mode (jk::Mode).
-int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *partial, hipStream_t st)
+// Single-step pass over `src` in the given mode (jk::Mode); with tile_count > 0 only over the tiles
+// [tile0, tile0 + tile_count).
+int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *partial, hipStream_t st,
+                 int tile0 = 0, int tile_count = 0)
 {
-    const SweepConfig c = make_config(p, mode);
+    SweepConfig c = make_config(p, mode);
+    if (tile_count > 0) {
+        c.sp.nstrips = c.sp.nstrips / p->geo.ntiles * tile_count;   // strips are laid out tile by tile
+        c.sp.tile0 = tile0;
+    }
     const int64_t nwg = ceil_div(c.sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, c.sp, src, dst, partial};
@@ -565,11 +578,13 @@ int jacobi_destroy(jacobi_plan *plan)
 {
     if (!plan) return JACOBI_OK;
     int rc = JACOBI_OK;
-    if (plan->partial || !plan->ev.empty()) {
+    if (plan->partial || !plan->ev.empty() || !plan->task_streams.empty() || !plan->task_events.empty()) {
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) rc = fail_hip(e, "hipDeviceSynchronize");
         if (plan->partial) (void)hipFree(plan->partial);
         for (hipEvent_t ev : plan->ev) (void)hipEventDestroy(ev);
+        for (hipEvent_t ev : plan->task_events) (void)hipEventDestroy(ev);
+        for (hipStream_t s : plan->task_streams) (void)hipStreamDestroy(s);
     }
     delete plan;
     return rc;
@@ -684,6 +699,105 @@ int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream
     if (final) *final = in;
     if (iters == 0) return JACOBI_OK;
     return sweep_common(plan, in, out, iters, (hipStream_t)stream, final, nullptr);
+}
+
+// Tasks of `group` consecutive tiles.  A task of iteration k+1 reads its tiles of the grid that
+// iteration k wrote - interiors (written by the same task) and halo cells (pushed there by the tasks
+// that own the face-neighbour tiles) - so it depends on exactly those tasks of iteration k.  The same
+// edges cover the write-after-read hazards of the ping-pong buffers.
+static void build_task_deps(jacobi_plan *p, int group)
+{
+    const Geo &g = p->geo;
+    const int ntasks = (int)ceil_div(g.ntiles, group);
+    p->task_deps.assign(ntasks, std::vector<int>());
+    for (int t = 0; t < g.ntiles; ++t) {
+        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+        std::vector<int> &d = p->task_deps[t / group];
+        auto add = [&](int z, int y, int x) {
+            if (z < 0 || z >= g.Tz || y < 0 || y >= g.Ty || x < 0 || x >= g.Tx) return;
+            const int task = ((z * g.Ty + y) * g.Tx + x) / group;
+            if (std::find(d.begin(), d.end(), task) == d.end()) d.push_back(task);
+        };
+        add(tz, ty, tx);
+        add(tz, ty, tx - 1); add(tz, ty, tx + 1);
+        add(tz, ty - 1, tx); add(tz, ty + 1, tx);
+        add(tz - 1, ty, tx); add(tz + 1, ty, tx);
+    }
+    p->task_group = group;
+}
+
+int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int tiles_per_task, int nstreams,
+                       void *stream, void **final)
+{
+    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
+    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (misaligned(in) || misaligned(out)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
+    if (grids_overlap(plan, in, out)) return fail(JACOBI_EINVAL, "in and out overlap");
+    if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
+    if (tiles_per_task < 1 || nstreams < 1 || nstreams > MAX_TASK_STREAMS)
+        return fail(JACOBI_EINVAL, "tiles_per_task must be >= 1 and nstreams in 1..16");
+    if (!plan->fused) return fail(JACOBI_EINVAL, "task execution needs option fused = 1 (tasks push their edge cells)");
+    if (final) *final = in;
+    if (iters == 0) return JACOBI_OK;
+    const Geo &g = plan->geo;
+    hipStream_t st = (hipStream_t)stream;
+    {
+        // Recording this fork / join pattern into a HIP graph crashed inside the runtime when the capture
+        // was ended (host-side segmentation fault, cause not found): refused until that is understood.
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        HIP_TRY(hipStreamIsCapturing(st, &cs));
+        if (cs != hipStreamCaptureStatusNone)
+            return fail(JACOBI_EINVAL, "jacobi_sweep_tasks cannot be recorded into a HIP graph");
+    }
+    const int group = tiles_per_task > g.ntiles ? g.ntiles : tiles_per_task;
+    const int ntasks = (int)ceil_div(g.ntiles, group);
+    const int S = nstreams < ntasks ? nstreams : ntasks;
+
+    if (plan->task_group != group) build_task_deps(plan, group);
+    while ((int)plan->task_streams.size() < S) {
+        hipStream_t s;
+        HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        plan->task_streams.push_back(s);
+    }
+    const size_t nev = 2 * (size_t)ntasks + 1 + MAX_TASK_STREAMS;
+    while (plan->task_events.size() < nev) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        plan->task_events.push_back(e);
+    }
+    hipEvent_t *done = plan->task_events.data();                  // done[2*task + parity]
+    const hipEvent_t fork = plan->task_events[2 * (size_t)ntasks];
+    hipEvent_t *joined = plan->task_events.data() + 2 * (size_t)ntasks + 1;
+
+    // on the caller's stream: the Dirichlet ring of `out`, and current halos of `in` for the first iteration
+    int rc = launch_boundary_sync(plan, in, out, st);
+    if (rc) return rc;
+    rc = launch_exchange(plan, in, st);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(fork, st));
+    for (int s = 0; s < S; ++s) HIP_TRY(hipStreamWaitEvent(plan->task_streams[s], fork, 0));
+
+    void *src = in, *dst = out;
+    for (int k = 0; k < iters; ++k) {
+        for (int a = 0; a < ntasks; ++a) {
+            hipStream_t s = plan->task_streams[a % S];
+            if (k > 0)
+                for (int b : plan->task_deps[a])
+                    if (b % S != a % S)                              // same stream: already in order
+                        HIP_TRY(hipStreamWaitEvent(s, done[2 * b + ((k - 1) & 1)], 0));
+            const int t0 = a * group, cnt = t0 + group <= g.ntiles ? group : g.ntiles - t0;
+            rc = launch_sweep(plan, jk::MODE_UPDATE, src, dst, nullptr, s, t0, cnt);
+            if (rc) return rc;
+            HIP_TRY(hipEventRecord(done[2 * a + (k & 1)], s));
+        }
+        void *t = src; src = dst; dst = t;
+    }
+    for (int s = 0; s < S; ++s) {
+        HIP_TRY(hipEventRecord(joined[s], plan->task_streams[s]));
+        HIP_TRY(hipStreamWaitEvent(st, joined[s], 0));
+    }
+    if (final) *final = src;
+    return JACOBI_OK;
 }
 
 int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final,

@@ -213,6 +213,7 @@ struct StripParams {
     int fused;           // update mode: push edge cells into neighbour halos of dst
     int xcd_chunk;       // G of xcd_logical_wg(): consecutive workgroups one XCD takes
     int rows_fastest = 0; // 3-D blocked passes: consecutive strips are neighbours in y (else in x)
+    int tile0 = 0;        // single-step kernels: first tile this launch covers (a task = a range of tiles)
 };
 
 // ------------------------------------------------------------------------------------
@@ -234,8 +235,9 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 
     if (s < sp.nstrips) {
         const int per_tile = sp.nblk * sp.nseg;
-        const int t = (int)(s / per_tile);
-        const int rem = (int)(s - (long long)t * per_tile);
+        const int tl = (int)(s / per_tile);                       // tile within this launch
+        const int rem = (int)(s - (long long)tl * per_tile);
+        const int t = sp.tile0 + tl;
         const int rb = rem / sp.nseg, seg = rem - rb * sp.nseg;
         const int ty = t / g.Tx, tx = t - ty * g.Tx;
         const int r0 = 1 + rb * sp.R;
@@ -712,8 +714,9 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
     if (s < sp.nstrips) {
         const int ngrp = (g.th + RW - 1) / RW;
         const long long per_tile = (long long)sp.nblk * ngrp * sp.nseg;
-        const int t = (int)(s / per_tile);
-        int rem = (int)(s - (long long)t * per_tile);
+        const int tl = (int)(s / per_tile);                       // tile within this launch
+        int rem = (int)(s - (long long)tl * per_tile);
+        const int t = sp.tile0 + tl;
         const int kb = rem / (ngrp * sp.nseg);
         rem -= kb * ngrp * sp.nseg;
         const int i0 = 1 + (rem / sp.nseg) * RW, seg = rem % sp.nseg;

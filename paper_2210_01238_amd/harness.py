@@ -68,6 +68,12 @@ class JacobiRun:
         fin = B.jacobi_sweep(self.plan, self.cur.data_ptr(), self.other().data_ptr(), iters, _stream())
         self.cur = self.a if fin == self.a.data_ptr() else self.b
 
+    def sweep_tasks(self, iters: int, tiles_per_task: int, nstreams: int) -> None:
+        """sweep(iters) executed as per-tile-group tasks over several streams."""
+        fin = B.jacobi_sweep_tasks(self.plan, self.cur.data_ptr(), self.other().data_ptr(), iters,
+                                   tiles_per_task, nstreams, _stream())
+        self.cur = self.a if fin == self.a.data_ptr() else self.b
+
     def sweep_residual(self, iters: int, out: torch.Tensor) -> None:
         """sweep(iters), and `out` (1-element float64 CUDA tensor) receives the residual norm
         of the field as it was BEFORE these iterations."""

@@ -427,3 +427,84 @@ def test_sweep_can_be_captured_in_a_hip_graph(H, oracle_mod):
                 assert np.array_equal(got, exp), (opts, k)
         finally:
             r.close()
+
+
+TASK_CASES = [
+    # (interior dims, tiles, tiles per task, streams, iterations)
+    ((96, 200), (3, 2), 1, 4, 7),            # one tile per task
+    ((96, 200), (3, 2), 2, 3, 8),
+    ((96, 200), (3, 2), 100, 1, 5),          # one task, one stream: the monolithic launch
+    ((48, 48), (48, 48), 37, 16, 6),         # 2304 one-cell tiles in ragged groups of 37
+    ((512, 512), (4, 4), 3, 5, 12),
+    ((24, 20, 36), (2, 2, 3), 1, 16, 9),     # 3-D, every tile a task
+    ((24, 20, 36), (2, 2, 3), 5, 2, 9),
+    ((8, 8, 8), (8, 8, 8), 64, 7, 5),
+    ((256, 256), (1, 1), 1, 4, 10),          # single tile
+]
+
+
+@pytest.mark.parametrize("dims,tiles,group,streams,iters", TASK_CASES)
+def test_task_execution_is_bit_identical(H, oracle_mod, dims, tiles, group, streams, iters):
+    """jacobi_sweep_tasks: per-tile-group tasks ordered only by events across several streams."""
+    for dtype in (np.float64, np.float32):
+        a = random_padded(dims, dtype=dtype, seed=sum(dims) + iters)
+        r = H.JacobiRun(dims, tiles, dtype)
+        try:
+            r.load(a)
+            r.sweep_tasks(iters, group, streams)
+            r.sweep_tasks(3, group, streams)              # a second call continues from the result
+            out = r.fetch()
+            res = [r.residual()]
+        finally:
+            r.close()
+        ref, ref_res = oracle_mod.run(a, iters + 3, iters + 3)
+        check(out, res, ref, ref_res)
+
+
+@pytest.mark.skip(reason="ending the capture of the multi-stream fork/join crashed inside the HIP runtime "
+                         "(host segmentation fault in hipStreamEndCapture, cause not found); "
+                         "jacobi_sweep_tasks now refuses a capturing stream")
+def test_task_execution_can_be_captured_in_a_hip_graph(H, oracle_mod):
+    """The fork / join over the plan's streams recorded into a graph: the graph would hold the task DAG."""
+    import torch
+    a = random_padded((128, 192), seed=41)
+    r = H.JacobiRun((128, 192), (4, 3))
+    try:
+        r.load(a)
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            r.sweep_tasks(6, 2, 4)                        # eager: creates the streams and events
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        assert np.array_equal(r.fetch(), oracle_mod.run(a, 6)[0])
+        src, dst = r.cur, r.other()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            fin = H.B.jacobi_sweep_tasks(r.plan, src.data_ptr(), dst.data_ptr(), 6, 2, 4,
+                                         int(torch.cuda.current_stream().cuda_stream))
+        assert fin == src.data_ptr()
+        for k in range(3):
+            g.replay()
+            torch.cuda.synchronize()
+            got = r.fetch()
+            torch.cuda.synchronize()
+            assert np.array_equal(got, oracle_mod.run(a, 12 + 6 * k)[0]), k
+    finally:
+        r.close()
+
+
+def test_task_execution_rejects_bad_arguments(H):
+    r = H.JacobiRun((32, 32), (2, 2))
+    try:
+        p, x, y = r.plan, r.cur.data_ptr(), r.other().data_ptr()
+        for bad in (lambda: H.B.jacobi_sweep_tasks(p, x, y, 1, 0, 2), lambda: H.B.jacobi_sweep_tasks(p, x, y, 1, 1, 0),
+                    lambda: H.B.jacobi_sweep_tasks(p, x, y, 1, 1, 17), lambda: H.B.jacobi_sweep_tasks(p, x, x, 1, 1, 2),
+                    lambda: H.B.jacobi_sweep_tasks(p, x, y, -1, 1, 2)):
+            with pytest.raises(H.B.JacobiError):
+                bad()
+        r.set_option("fused", 0)
+        with pytest.raises(H.B.JacobiError):
+            H.B.jacobi_sweep_tasks(p, x, y, 1, 1, 2)
+    finally:
+        r.close()
