@@ -165,6 +165,16 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
                           void **final, double *residual_in_dev);
 
 /*
+ * jacobi_pass_schedule: what jacobi_sweep(plan, ., ., iters) will launch with the current
+ * options - the number of passes over memory and how many iterations each one advances
+ * (1 = halo exchange + single-step update; > 1 = a blocked pass, option "tblock").
+ * Host-only: no device call.  *npasses receives the number of passes; the first
+ * min(*npasses, capacity) entries of depths[] are filled (depths may be NULL if capacity
+ * is 0).  Errors: EINVAL.
+ */
+int jacobi_pass_schedule(const jacobi_plan *plan, int iters, int *depths, int capacity, int *npasses);
+
+/*
  * jacobi_sweep_tasks: the same `iters` iterations as jacobi_sweep, executed as the paper
  * structures them (Sec. IV-A "Heterogeneous Tasks", Sec. IV-B "Execution Model", Sec. VI-A
  * "Enabling Concurrent GPU Operations"): every group of `tiles_per_task` consecutive tiles

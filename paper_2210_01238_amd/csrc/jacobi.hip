@@ -800,6 +800,21 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
     return JACOBI_OK;
 }
 
+int jacobi_pass_schedule(const jacobi_plan *plan, int iters, int *depths, int capacity, int *npasses)
+{
+    if (!plan || !npasses || (capacity > 0 && !depths)) return fail(JACOBI_EINVAL, "NULL argument");
+    if (iters < 0 || capacity < 0) return fail(JACOBI_EINVAL, "iters and capacity must be >= 0");
+    int n = 0;
+    for (int k = 0; k < iters;) {
+        const PassChoice pc = choose_pass(plan, iters - k);
+        if (n < capacity) depths[n] = pc.depth;
+        ++n;
+        k += pc.depth;
+    }
+    *npasses = n;
+    return JACOBI_OK;
+}
+
 int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final,
                           double *residual_in_dev)
 {

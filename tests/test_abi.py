@@ -104,3 +104,39 @@ def test_null_and_argument_errors_without_device(J):
     assert J.jacobi_grid_bytes(None) == 0
     J.jacobi_destroy(p)
     J.jacobi_destroy(None)
+
+
+def test_pass_schedule_host_logic(J):
+    """The pass planner (host only): iterations spread evenly over the fewest passes the depth allows."""
+    def sched(dims, tiles, dtype, iters, **opts):
+        p = J.jacobi_create(dims, tiles, dtype)
+        for k, v in opts.items():
+            J.jacobi_set_option(p, k, v)
+        try:
+            return J.jacobi_pass_schedule(p, iters)
+        finally:
+            J.jacobi_destroy(p)
+    assert sched((64, 64), (2, 2), 0, 7) == [1] * 7                       # default: one iteration per pass
+    assert sched((64, 64), (2, 2), 0, 0) == []
+    assert sched((64, 64), (2, 2), 0, 10, tblock=8) == [5, 5]             # not 8 + 2
+    assert sched((64, 64), (2, 2), 0, 17, tblock=8) == [6, 6, 5]
+    assert sched((64, 64), (2, 2), 0, 9, tblock=2) == [2, 2, 2, 2, 1]
+    assert sched((64, 64), (2, 2), 0, 3, tblock=8) == [3]
+    assert sched((40, 36), (1, 36), 0, 6, tblock=8) == [1] * 6            # tiles one column wide: single steps
+    assert sched((12, 63), (4, 1), 0, 8, tblock=8) == [2, 2, 2, 2]        # odd width, height 3: two-step kernel only
+    # 3-D: fp64 up to 4 iterations per pass, fp32 up to 3
+    assert sched((32, 32, 32), (2, 2, 2), 0, 10, tblock=8) == [4, 3, 3]
+    assert sched((32, 32, 32), (2, 2, 2), 1, 10, tblock=8) == [3, 3, 2, 2]
+    assert sched((32, 32, 32), (2, 2, 2), 0, 10, tblock=8, cooperative=0) == [3, 3, 2, 2]
+    assert sched((32, 32, 32), (2, 2, 2), 1, 10, tblock=8, cooperative=0) == [2] * 5
+    assert sched((32, 32, 33), (2, 2, 1), 0, 5, tblock=8) == [1] * 5      # odd tile width: single steps
+    assert sched((6, 32, 32), (3, 2, 2), 0, 9, tblock=4) == [2, 2, 2, 2, 1]   # tile depth 2 limits the pass depth
+    p = J.jacobi_create((8, 8), (1, 1))
+    raw = J.binding.lib
+    n = ctypes.c_int()
+    assert raw.jacobi_pass_schedule(p, 3, None, 0, None) == 1
+    assert raw.jacobi_pass_schedule(p, -1, None, 0, ctypes.byref(n)) == 1
+    assert raw.jacobi_pass_schedule(p, 3, None, 2, ctypes.byref(n)) == 1
+    buf = (ctypes.c_int * 2)(7, 7)
+    assert raw.jacobi_pass_schedule(p, 5, buf, 2, ctypes.byref(n)) == 0 and n.value == 5 and list(buf) == [1, 1]
+    J.jacobi_destroy(p)
