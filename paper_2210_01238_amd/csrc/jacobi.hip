@@ -38,6 +38,8 @@ int fail_hip(hipError_t e, const char *what)
     } while (0)
 
 constexpr int MAX_TASK_STREAMS = 16;
+constexpr int64_t MAX_GRAPH_NODES = 4096;
+constexpr int MAX_GRAPH_WIDTH = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 
@@ -63,6 +65,13 @@ struct jacobi_plan {
     std::vector<hipEvent_t> task_events;            // 2 per task (iteration parity), then fork, then 1 per stream
     int task_group = 0;                             // tiles per task the lists below were built for
     std::vector<std::vector<int>> task_deps;        // tasks whose previous-iteration output a task reads
+    // jacobi_sweep_task_graph: the last graph built, reused while the call and the options stay the same
+    hipGraph_t tg_graph = nullptr;
+    hipGraphExec_t tg_exec = nullptr;
+    hipEvent_t tg_done = nullptr;                   // recorded behind every launch of tg_exec
+    const void *tg_in = nullptr, *tg_out = nullptr;
+    int tg_iters = 0, tg_group = 0;
+    int64_t tg_options[6] = {0, 0, 0, 0, 0, 0};
 };
 
 namespace {
@@ -578,13 +587,17 @@ int jacobi_destroy(jacobi_plan *plan)
 {
     if (!plan) return JACOBI_OK;
     int rc = JACOBI_OK;
-    if (plan->partial || !plan->ev.empty() || !plan->task_streams.empty() || !plan->task_events.empty()) {
+    if (plan->partial || !plan->ev.empty() || !plan->task_streams.empty() || !plan->task_events.empty() || plan->tg_exec ||
+        plan->tg_graph || plan->tg_done) {
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) rc = fail_hip(e, "hipDeviceSynchronize");
         if (plan->partial) (void)hipFree(plan->partial);
         for (hipEvent_t ev : plan->ev) (void)hipEventDestroy(ev);
         for (hipEvent_t ev : plan->task_events) (void)hipEventDestroy(ev);
         for (hipStream_t s : plan->task_streams) (void)hipStreamDestroy(s);
+        if (plan->tg_exec) (void)hipGraphExecDestroy(plan->tg_exec);
+        if (plan->tg_graph) (void)hipGraphDestroy(plan->tg_graph);
+        if (plan->tg_done) (void)hipEventDestroy(plan->tg_done);
     }
     delete plan;
     return rc;
@@ -797,6 +810,103 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
         HIP_TRY(hipStreamWaitEvent(st, joined[s], 0));
     }
     if (final) *final = src;
+    return JACOBI_OK;
+}
+
+int jacobi_sweep_task_graph(jacobi_plan *plan, void *in, void *out, int iters, int tiles_per_task, void *stream,
+                            void **final)
+{
+    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
+    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (misaligned(in) || misaligned(out)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
+    if (grids_overlap(plan, in, out)) return fail(JACOBI_EINVAL, "in and out overlap");
+    if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
+    if (tiles_per_task < 1) return fail(JACOBI_EINVAL, "tiles_per_task must be >= 1");
+    if (!plan->fused) return fail(JACOBI_EINVAL, "task execution needs option fused = 1 (tasks push their edge cells)");
+    if (final) *final = in;
+    if (iters == 0) return JACOBI_OK;
+    const Geo &g = plan->geo;
+    hipStream_t st = (hipStream_t)stream;
+    const int group = tiles_per_task > g.ntiles ? g.ntiles : tiles_per_task;
+    const int ntasks = (int)ceil_div(g.ntiles, group);
+    // A DAG 63 tasks wide (378 nodes) made the runtime abort on the host when the launch was waited for
+    // (cause not found); DAGs up to 6 tasks wide ran.  Wider ones are refused.
+    if (ntasks > MAX_GRAPH_WIDTH)
+        return fail(JACOBI_EINVAL, "more than 16 tasks per iteration in a task graph: use coarser tasks");
+    if ((int64_t)ntasks * iters > MAX_GRAPH_NODES)
+        return fail(JACOBI_EINVAL, "more than 4096 tasks in one graph: use fewer iterations per call");
+
+    const int64_t opts[6] = {plan->rows_per_strip, plan->unroll, plan->nontemporal, plan->xcd_chunk, plan->rows_per_wave, 1};
+    const bool reuse = plan->tg_exec && plan->tg_in == in && plan->tg_out == out && plan->tg_iters == iters &&
+                       plan->tg_group == group && !memcmp(opts, plan->tg_options, sizeof(opts));
+    if (!plan->tg_done) HIP_TRY(hipEventCreateWithFlags(&plan->tg_done, hipEventDisableTiming));
+    if (!reuse) {
+        // the previous graph may still be running: it must not be destroyed under the device's feet
+        if (plan->tg_exec) HIP_TRY(hipEventSynchronize(plan->tg_done));
+        if (plan->tg_exec) { HIP_TRY(hipGraphExecDestroy(plan->tg_exec)); plan->tg_exec = nullptr; }
+        if (plan->tg_graph) { HIP_TRY(hipGraphDestroy(plan->tg_graph)); plan->tg_graph = nullptr; }
+        if (plan->task_group != group) build_task_deps(plan, group);
+
+        // the update kernel and its strip geometry, as launch_sweep would use them
+        SweepConfig c = make_config(plan, jk::MODE_UPDATE);
+        const int64_t strips_per_tile = c.sp.nstrips / g.ntiles;
+        const void *kernel = nullptr;
+        {
+            jk::LaunchArgs probe{0u, nullptr, g, c.sp, nullptr, nullptr, nullptr};
+            probe.symbol_out = &kernel;
+            const bool f64 = plan->lay.dtype == JACOBI_F64;
+            const int nt = (int)plan->nontemporal;
+            const hipError_t e = g.ndim == 2
+                ? (f64 ? jk::launch_sweep2d_f64(jk::MODE_UPDATE, c.unroll, nt, probe) : jk::launch_sweep2d_f32(jk::MODE_UPDATE, c.unroll, nt, probe))
+                : (f64 ? jk::launch_sweep3d_f64(jk::MODE_UPDATE, c.rows_per_wave, c.unroll, nt, probe)
+                       : jk::launch_sweep3d_f32(jk::MODE_UPDATE, c.rows_per_wave, c.unroll, nt, probe));
+            if (e == hipErrorInvalidValue || !kernel) return fail(JACOBI_EINVAL, "kernel variant not compiled for these options");
+        }
+
+        HIP_TRY(hipGraphCreate(&plan->tg_graph, 0));
+        std::vector<hipGraphNode_t> prev(ntasks), cur(ntasks), deps;
+        const void *src = in;
+        void *dst = out;
+        double *no_partial = nullptr;
+        Geo geo = g;
+        for (int k = 0; k < iters; ++k) {
+            for (int a = 0; a < ntasks; ++a) {
+                const int t0 = a * group, cnt = t0 + group <= g.ntiles ? group : g.ntiles - t0;
+                StripParams sp = c.sp;
+                sp.nstrips = strips_per_tile * cnt;
+                sp.tile0 = t0;
+                const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+                if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+                void *args[] = {&geo, &sp, &src, &dst, &no_partial};
+                hipKernelNodeParams np;
+                memset(&np, 0, sizeof(np));
+                np.func = const_cast<void *>(kernel);
+                np.gridDim = dim3((unsigned)nwg);
+                np.blockDim = dim3(jk::WG);
+                np.sharedMemBytes = 0;
+                np.kernelParams = args;
+                np.extra = nullptr;
+                deps.clear();
+                if (k > 0)
+                    for (int b : plan->task_deps[a]) deps.push_back(prev[b]);
+                HIP_TRY(hipGraphAddKernelNode(&cur[a], plan->tg_graph, deps.empty() ? nullptr : deps.data(), deps.size(), &np));
+            }
+            prev.swap(cur);
+            const void *t = src; src = dst; dst = const_cast<void *>(t);
+        }
+        HIP_TRY(hipGraphInstantiate(&plan->tg_exec, plan->tg_graph, nullptr, nullptr, 0));
+        plan->tg_in = in; plan->tg_out = out; plan->tg_iters = iters; plan->tg_group = group;
+        memcpy(plan->tg_options, opts, sizeof(opts));
+    }
+
+    // on the caller's stream: the Dirichlet ring of `out`, current halos of `in`, then the whole DAG
+    int rc = launch_boundary_sync(plan, in, out, st);
+    if (rc) return rc;
+    rc = launch_exchange(plan, in, st);
+    if (rc) return rc;
+    HIP_TRY(hipGraphLaunch(plan->tg_exec, st));
+    HIP_TRY(hipEventRecord(plan->tg_done, st));
+    if (final) *final = (iters & 1) ? out : in;
     return JACOBI_OK;
 }
 

@@ -11,8 +11,11 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
     const dim3 grid(a.nwg), block(WG);
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
-#define JK_L(MODE_, RW_, U_, NT_) \
-    hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+#define JK_L(MODE_, RW_, U_, NT_)                                                                                   \
+    do {                                                                                                            \
+        if (a.symbol_out) *a.symbol_out = (const void *)&sweep3d_kernel<T, MODE_, RW_, U_, NT_>;                    \
+        else hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial); \
+    } while (0)
 #define JK_NT(MODE_, RW_, U_)                 \
     do {                                      \
         if (nt & 2) JK_L(MODE_, RW_, U_, 2);  \

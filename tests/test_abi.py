@@ -140,3 +140,19 @@ def test_pass_schedule_host_logic(J):
     buf = (ctypes.c_int * 2)(7, 7)
     assert raw.jacobi_pass_schedule(p, 5, buf, 2, ctypes.byref(n)) == 0 and n.value == 5 and list(buf) == [1, 1]
     J.jacobi_destroy(p)
+
+
+def test_task_graph_limits_without_device(J):
+    """Width and size limits of jacobi_sweep_task_graph are checked before any device call."""
+    p = J.jacobi_create((48, 48), (48, 48))
+    nb = J.jacobi_grid_bytes(p)
+    for bad in (lambda: J.jacobi_sweep_task_graph(p, 256, 256 + nb, 6, 37),     # 63 tasks per iteration
+                lambda: J.jacobi_sweep_task_graph(p, 256, 256 + nb, 300, 144),  # 16 x 300 nodes
+                lambda: J.jacobi_sweep_task_graph(p, 256, 256 + nb, 1, 0),
+                lambda: J.jacobi_sweep_task_graph(p, 256, 256, 1, 144),
+                lambda: J.jacobi_sweep_tasks(p, 256, 256 + nb, 1, 1, 17)):
+        with pytest.raises(J.JacobiError) as e:
+            bad()
+        assert e.value.code == 1
+    assert J.jacobi_sweep_task_graph(p, 256, 256 + nb, 0, 144) == 256
+    J.jacobi_destroy(p)
