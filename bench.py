@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md
 # and profiles/sweep3d_update_C4.md.  Valid only for the library's default options on that
 # workload; otherwise reported as null.
-MEASURED_TRAFFIC_BYTES = {"C3": 4589109414, "C4": 2362445530}
+MEASURED_TRAFFIC_BYTES = {"C3": 4588799847, "C4": 2362803708}
 
 
 def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
@@ -72,8 +72,8 @@ def main() -> int:
                     help="depth limit of the extra temporal-blocking measurement (3-D passes advance 2 iterations)")
     ap.add_argument("--no-temporal-blocking", action="store_true",
                     help="skip the extra measurement with several iterations per pass")
-    ap.add_argument("--tasks", default="1,16", help="tiles per task and streams of the extra task-execution "
-                    "measurement (jacobi_sweep_tasks); empty string skips it")
+    ap.add_argument("--tasks", default="", help="G,S: also measure the schedule executed as tasks of G tiles over "
+                    "S streams (jacobi_sweep_tasks), e.g. 1,16; off by default")
     ap.add_argument("--separate-residual", action="store_true",
                     help="compute every residual with the stand-alone reduction pass")
     ap.add_argument("--option", action="append", default=[], help="key=value passed to jacobi_set_option")
