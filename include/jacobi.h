@@ -71,7 +71,9 @@ enum jacobi_status {
  *     columns [tw, pitch) are padding with unspecified contents.
  *   - the x halos are NOT stored beside the rows but in two dense arrays:
  *     x- halo of row (k, i) at xhalo_offset + k*(th+2) + i,
- *     x+ halo of row (k, i) at xhalo_offset + xhalo_pitch + k*(th+2) + i.
+ *     x+ halo of row (k, i) at xhalo_offset + xhalo_pitch + k*(th+2) + i;
+ *     each array is followed by at least 3 unused elements (xhalo_pitch is rounded up
+ *     to a multiple of 128 bytes after adding them).
  * A halo cell holds either a copy of the neighbouring tile's edge cell (refreshed
  * by halo_exchange) or, on the domain boundary, the Dirichlet value.
  */
@@ -134,8 +136,11 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  *            and Dirichlet boundary halos must be valid; inter-tile halos need not be
  *            (they are exchanged before the first update).  `out` may hold anything.
  *   iters    >= 0.  0 is a no-op (*final = in).
- *   final    nullable host pointer; receives the grid holding the result:
- *            `out` if iters is odd, `in` if even (the two buffers ping-pong).
+ *   final    nullable host pointer; receives the grid holding the result.  The two
+ *            buffers ping-pong once per pass over memory: with the default of one
+ *            iteration per pass the result is in `out` if iters is odd and in `in` if
+ *            even; with option "tblock" > 1 it depends on the number of passes (see
+ *            jacobi_pass_schedule), so read *final.
  * First copies the Dirichlet boundary halos in -> out so both buffers carry them, then
  * for each iteration: halo exchange on the source buffer, update into the other buffer.
  * (Option "tblock" > 1 replaces this per-iteration sequence by multi-iteration passes.)
