@@ -131,3 +131,21 @@ def test_full_P1_paper_domain_1024x1024x768(H, oracle_mod):
 
 def test_full_P1_paper_domain_blocked_passes(H, oracle_mod):
     full_size_check(H, oracle_mod, "P1", few=3, tblock=8)
+
+
+@pytest.mark.parametrize("name,few,group", [("C3", 3, 1), ("C4", 4, 4)])
+def test_full_size_task_execution(H, oracle_mod, name, few, group):
+    """The task paths at full size: whole grid, bit for bit, after a few iterations."""
+    w = gen.WORKLOADS[name]
+    a = gen.generate(w)
+    ref, _ = oracle_mod.run(a, few)
+    r = H.JacobiRun(w.dims, w.tiles)
+    try:
+        r.load(a)
+        r.sweep_tasks(few, group, 16)                 # tasks over 16 streams
+        assert np.array_equal(r.fetch(), ref), f"{name}: task execution differs"
+        r.load(a)
+        r.sweep_task_graph(few, 4)                    # 16 tasks per iteration as a HIP graph
+        assert np.array_equal(r.fetch(), ref), f"{name}: task graph differs"
+    finally:
+        r.close()
