@@ -199,23 +199,6 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
                        int nstreams, void *stream, void **final);
 
 /*
- * jacobi_sweep_task_graph: the task DAG of jacobi_sweep_tasks (same tasks, same
- * dependencies) built explicitly as a HIP graph - one kernel node per task and iteration,
- * edges from the access sets (paper Sec. IV-A: an explicitly defined task dependency
- * graph) - instantiated once and launched on `stream`; the runtime then schedules the
- * nodes.  The graph is kept in the plan and reused while (in, out, iters, tiles_per_task)
- * and the options stay the same, otherwise rebuilt (building allocates, takes time
- * proportional to the node count, and first waits on the host until the previous graph's
- * last launch has finished).  At most 16 tasks per iteration and 4096 nodes (tasks x iters)
- * per call, else EINVAL (a wider graph made the HIP runtime abort).
- * The Dirichlet copy and the first halo exchange run as ordinary launches on `stream`
- * in front of the graph.  Bit-identical to jacobi_sweep.  Ignores "tblock"; needs
- * "fused" = 1.  Do not call while `stream` is capturing.  Errors: EINVAL, EHIP.
- */
-int jacobi_sweep_task_graph(jacobi_plan *plan, void *in, void *out, int iters, int tiles_per_task,
-                            void *stream, void **final);
-
-/*
  * halo_exchange: for every pair of face-adjacent tiles, copy each tile's edge cells
  * into the other's halo cells, in place in `grid` (paper Sec. VI-C: pack, transfer,
  * unpack - on one device the three collapse into one gather-scatter copy).

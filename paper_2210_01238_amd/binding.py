@@ -20,7 +20,7 @@ JACOBI_OK, JACOBI_EINVAL, JACOBI_ENOTDIV, JACOBI_ENOMEM, JACOBI_EHIP = 0, 1, 2, 
 
 EXPORTS = (
     "jacobi_create", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
-    "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_sweep_tasks", "jacobi_sweep_task_graph", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
+    "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_sweep_tasks", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
     "residual_norm_host", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
     "jacobi_last_error", "jacobi_stream_copy",
 )
@@ -61,7 +61,6 @@ def _load() -> ctypes.CDLL:
     lib.jacobi_sweep_residual.argtypes = [vp, vp, vp, ci, vp, P(vp), vp]
     lib.jacobi_sweep_tasks.argtypes = [vp, vp, vp, ci, ci, ci, vp, P(vp)]
     lib.jacobi_pass_schedule.argtypes = [vp, ci, P(ci), ci, P(ci)]
-    lib.jacobi_sweep_task_graph.argtypes = [vp, vp, vp, ci, ci, vp, P(vp)]
     lib.halo_exchange.argtypes = [vp, vp, vp]
     lib.residual_norm.argtypes = [vp, vp, vp, vp]
     lib.residual_norm_host.argtypes = [vp, vp, P(ctypes.c_double), vp]
@@ -137,16 +136,6 @@ def jacobi_sweep_tasks(plan: int, grid_in: int, grid_out: int, iters: int, tiles
     fin = ctypes.c_void_p()
     _check(lib.jacobi_sweep_tasks(plan, grid_in, grid_out, int(iters), int(tiles_per_task), int(nstreams),
                                   stream, ctypes.byref(fin)))
-    return fin.value
-
-
-def jacobi_sweep_task_graph(plan: int, grid_in: int, grid_out: int, iters: int, tiles_per_task: int,
-                            stream: int = 0) -> int:
-    """jacobi_sweep executed as one HIP graph whose nodes are tasks of `tiles_per_task` tiles.
-    Returns the pointer that holds the result grid."""
-    fin = ctypes.c_void_p()
-    _check(lib.jacobi_sweep_task_graph(plan, grid_in, grid_out, int(iters), int(tiles_per_task), stream,
-                                       ctypes.byref(fin)))
     return fin.value
 
 

@@ -38,8 +38,6 @@ int fail_hip(hipError_t e, const char *what)
     } while (0)
 
 constexpr int MAX_TASK_STREAMS = 16;
-constexpr int64_t MAX_GRAPH_NODES = 4096;
-constexpr int MAX_GRAPH_WIDTH = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 
@@ -65,13 +63,6 @@ struct jacobi_plan {
     std::vector<hipEvent_t> task_events;            // 2 per task (iteration parity), then fork, then 1 per stream
     int task_group = 0;                             // tiles per task the lists below were built for
     std::vector<std::vector<int>> task_deps;        // tasks whose previous-iteration output a task reads
-    // jacobi_sweep_task_graph: the last graph built, reused while the call and the options stay the same
-    hipGraph_t tg_graph = nullptr;
-    hipGraphExec_t tg_exec = nullptr;
-    hipEvent_t tg_done = nullptr;                   // recorded behind every launch of tg_exec
-    const void *tg_in = nullptr, *tg_out = nullptr;
-    int tg_iters = 0, tg_group = 0;
-    int64_t tg_options[6] = {0, 0, 0, 0, 0, 0};
 };
 
 namespace {
@@ -82,6 +73,7 @@ struct SweepConfig {
     StripParams sp;
     int rows_per_wave;   // 3-D only: rows one wavefront keeps in registers (1, 2 or 4)
     int unroll;          // rows (2-D) / planes (3-D) whose loads are issued back to back
+    int lane_elems;      // elements per lane: 16 bytes' worth, or 2 for narrow fp32 rows in 3-D
 };
 
 SweepConfig make_config(const jacobi_plan *p, int mode)
@@ -91,13 +83,15 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     const bool d3 = g.ndim == 3;
     SweepConfig c;
     StripParams &sp = c.sp;
-    sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * nv);
     c.rows_per_wave = 1;
     if (d3) {
         int rw = (int)p->rows_per_wave;
         if (rw <= 0) rw = g.th >= 4 ? 4 : g.th >= 2 ? 2 : 1;
         c.rows_per_wave = rw;
     }
+    // fp32 rows of at most 128 elements would leave half of a wavefront's 16-byte lanes idle: 8-byte lanes
+    c.lane_elems = (d3 && p->esize == 4 && g.pitch <= 2 * jk::WAVE && c.rows_per_wave == 4) ? 2 : nv;
+    sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * c.lane_elems);
     const int extent = d3 ? g.td : g.th;       // marching direction
     const int64_t lanes_of_work =
         (int64_t)g.ntiles * sp.nseg * (d3 ? ceil_div(g.th, c.rows_per_wave) : 1);
@@ -150,7 +144,8 @@ int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *p
     }
     const int64_t nwg = ceil_div(c.sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-    const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, c.sp, src, dst, partial};
+    jk::LaunchArgs a{(unsigned)nwg, st, p->geo, c.sp, src, dst, partial};
+    a.aux = c.lane_elems != 16 / (int)p->esize;       // 3-D fp32: the 8-byte-lane variant
     const bool f64 = p->lay.dtype == JACOBI_F64;
     const int nt = (int)p->nontemporal;
     hipError_t e;
@@ -587,17 +582,13 @@ int jacobi_destroy(jacobi_plan *plan)
 {
     if (!plan) return JACOBI_OK;
     int rc = JACOBI_OK;
-    if (plan->partial || !plan->ev.empty() || !plan->task_streams.empty() || !plan->task_events.empty() || plan->tg_exec ||
-        plan->tg_graph || plan->tg_done) {
+    if (plan->partial || !plan->ev.empty() || !plan->task_streams.empty() || !plan->task_events.empty()) {
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) rc = fail_hip(e, "hipDeviceSynchronize");
         if (plan->partial) (void)hipFree(plan->partial);
         for (hipEvent_t ev : plan->ev) (void)hipEventDestroy(ev);
         for (hipEvent_t ev : plan->task_events) (void)hipEventDestroy(ev);
         for (hipStream_t s : plan->task_streams) (void)hipStreamDestroy(s);
-        if (plan->tg_exec) (void)hipGraphExecDestroy(plan->tg_exec);
-        if (plan->tg_graph) (void)hipGraphDestroy(plan->tg_graph);
-        if (plan->tg_done) (void)hipEventDestroy(plan->tg_done);
     }
     delete plan;
     return rc;
@@ -756,7 +747,8 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
     hipStream_t st = (hipStream_t)stream;
     {
         // Recording this fork / join pattern into a HIP graph crashed inside the runtime when the capture
-        // was ended (host-side segmentation fault, cause not found): refused until that is understood.
+        // was ended (host-side segmentation fault, cause not found), and the same DAG built node by node
+        // made the runtime abort now and then: task execution stays outside HIP graphs.
         hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
         HIP_TRY(hipStreamIsCapturing(st, &cs));
         if (cs != hipStreamCaptureStatusNone)
@@ -810,103 +802,6 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
         HIP_TRY(hipStreamWaitEvent(st, joined[s], 0));
     }
     if (final) *final = src;
-    return JACOBI_OK;
-}
-
-int jacobi_sweep_task_graph(jacobi_plan *plan, void *in, void *out, int iters, int tiles_per_task, void *stream,
-                            void **final)
-{
-    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
-    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
-    if (misaligned(in) || misaligned(out)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
-    if (grids_overlap(plan, in, out)) return fail(JACOBI_EINVAL, "in and out overlap");
-    if (iters < 0) return fail(JACOBI_EINVAL, "iters must be >= 0");
-    if (tiles_per_task < 1) return fail(JACOBI_EINVAL, "tiles_per_task must be >= 1");
-    if (!plan->fused) return fail(JACOBI_EINVAL, "task execution needs option fused = 1 (tasks push their edge cells)");
-    if (final) *final = in;
-    if (iters == 0) return JACOBI_OK;
-    const Geo &g = plan->geo;
-    hipStream_t st = (hipStream_t)stream;
-    const int group = tiles_per_task > g.ntiles ? g.ntiles : tiles_per_task;
-    const int ntasks = (int)ceil_div(g.ntiles, group);
-    // A DAG 63 tasks wide (378 nodes) made the runtime abort on the host when the launch was waited for
-    // (cause not found); DAGs up to 6 tasks wide ran.  Wider ones are refused.
-    if (ntasks > MAX_GRAPH_WIDTH)
-        return fail(JACOBI_EINVAL, "more than 16 tasks per iteration in a task graph: use coarser tasks");
-    if ((int64_t)ntasks * iters > MAX_GRAPH_NODES)
-        return fail(JACOBI_EINVAL, "more than 4096 tasks in one graph: use fewer iterations per call");
-
-    const int64_t opts[6] = {plan->rows_per_strip, plan->unroll, plan->nontemporal, plan->xcd_chunk, plan->rows_per_wave, 1};
-    const bool reuse = plan->tg_exec && plan->tg_in == in && plan->tg_out == out && plan->tg_iters == iters &&
-                       plan->tg_group == group && !memcmp(opts, plan->tg_options, sizeof(opts));
-    if (!plan->tg_done) HIP_TRY(hipEventCreateWithFlags(&plan->tg_done, hipEventDisableTiming));
-    if (!reuse) {
-        // the previous graph may still be running: it must not be destroyed under the device's feet
-        if (plan->tg_exec) HIP_TRY(hipEventSynchronize(plan->tg_done));
-        if (plan->tg_exec) { HIP_TRY(hipGraphExecDestroy(plan->tg_exec)); plan->tg_exec = nullptr; }
-        if (plan->tg_graph) { HIP_TRY(hipGraphDestroy(plan->tg_graph)); plan->tg_graph = nullptr; }
-        if (plan->task_group != group) build_task_deps(plan, group);
-
-        // the update kernel and its strip geometry, as launch_sweep would use them
-        SweepConfig c = make_config(plan, jk::MODE_UPDATE);
-        const int64_t strips_per_tile = c.sp.nstrips / g.ntiles;
-        const void *kernel = nullptr;
-        {
-            jk::LaunchArgs probe{0u, nullptr, g, c.sp, nullptr, nullptr, nullptr};
-            probe.symbol_out = &kernel;
-            const bool f64 = plan->lay.dtype == JACOBI_F64;
-            const int nt = (int)plan->nontemporal;
-            const hipError_t e = g.ndim == 2
-                ? (f64 ? jk::launch_sweep2d_f64(jk::MODE_UPDATE, c.unroll, nt, probe) : jk::launch_sweep2d_f32(jk::MODE_UPDATE, c.unroll, nt, probe))
-                : (f64 ? jk::launch_sweep3d_f64(jk::MODE_UPDATE, c.rows_per_wave, c.unroll, nt, probe)
-                       : jk::launch_sweep3d_f32(jk::MODE_UPDATE, c.rows_per_wave, c.unroll, nt, probe));
-            if (e == hipErrorInvalidValue || !kernel) return fail(JACOBI_EINVAL, "kernel variant not compiled for these options");
-        }
-
-        HIP_TRY(hipGraphCreate(&plan->tg_graph, 0));
-        std::vector<hipGraphNode_t> prev(ntasks), cur(ntasks), deps;
-        const void *src = in;
-        void *dst = out;
-        double *no_partial = nullptr;
-        Geo geo = g;
-        for (int k = 0; k < iters; ++k) {
-            for (int a = 0; a < ntasks; ++a) {
-                const int t0 = a * group, cnt = t0 + group <= g.ntiles ? group : g.ntiles - t0;
-                StripParams sp = c.sp;
-                sp.nstrips = strips_per_tile * cnt;
-                sp.tile0 = t0;
-                const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
-                if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-                void *args[] = {&geo, &sp, &src, &dst, &no_partial};
-                hipKernelNodeParams np;
-                memset(&np, 0, sizeof(np));
-                np.func = const_cast<void *>(kernel);
-                np.gridDim = dim3((unsigned)nwg);
-                np.blockDim = dim3(jk::WG);
-                np.sharedMemBytes = 0;
-                np.kernelParams = args;
-                np.extra = nullptr;
-                deps.clear();
-                if (k > 0)
-                    for (int b : plan->task_deps[a]) deps.push_back(prev[b]);
-                HIP_TRY(hipGraphAddKernelNode(&cur[a], plan->tg_graph, deps.empty() ? nullptr : deps.data(), deps.size(), &np));
-            }
-            prev.swap(cur);
-            const void *t = src; src = dst; dst = const_cast<void *>(t);
-        }
-        HIP_TRY(hipGraphInstantiate(&plan->tg_exec, plan->tg_graph, nullptr, nullptr, 0));
-        plan->tg_in = in; plan->tg_out = out; plan->tg_iters = iters; plan->tg_group = group;
-        memcpy(plan->tg_options, opts, sizeof(opts));
-    }
-
-    // on the caller's stream: the Dirichlet ring of `out`, current halos of `in`, then the whole DAG
-    int rc = launch_boundary_sync(plan, in, out, st);
-    if (rc) return rc;
-    rc = launch_exchange(plan, in, st);
-    if (rc) return rc;
-    HIP_TRY(hipGraphLaunch(plan->tg_exec, st));
-    HIP_TRY(hipEventRecord(plan->tg_done, st));
-    if (final) *final = (iters & 1) ? out : in;
     return JACOBI_OK;
 }
 

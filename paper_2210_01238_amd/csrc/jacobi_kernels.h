@@ -696,13 +696,15 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
 // 32+l: E edge of row l) and handed to lanes 0 / 63 as wave-uniform scalars (v_readlane).
 // Strip order: tile -> plane block -> row group -> column segment.
 // ------------------------------------------------------------------------------------
-template <typename T, int MODE, int RW, int U, int NT>
+// NVEC: elements per lane.  16 bytes by default; fp32 grids whose rows are at most 128 elements
+// use 2 (8 bytes per lane), so that a 128-wide tile row fills the wavefront instead of half of it.
+template <typename T, int MODE, int RW, int U, int NT, int NVEC = Vec<T>::N>
 __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
                                                      double *__restrict__ partial)
 {
-    using V = typename Vec<T>::type;
-    constexpr int NV = Vec<T>::N;
+    typedef T V __attribute__((ext_vector_type(NVEC)));
+    constexpr int NV = NVEC;
     static_assert(RW >= 1 && RW <= 32, "edge gather uses lanes [0,RW) and [32,32+RW)");
     __shared__ double red[WAVES_PER_WG];
 

@@ -11,10 +11,18 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
     const dim3 grid(a.nwg), block(WG);
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
+#define JK_K(MODE_, RW_, U_, NT_, NVEC_) \
+    hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+    // a.aux = 1: fp32 rows of at most 128 elements, 2 elements per lane (4 rows per wavefront only)
 #define JK_L(MODE_, RW_, U_, NT_)                                                                                   \
     do {                                                                                                            \
-        if (a.symbol_out) *a.symbol_out = (const void *)&sweep3d_kernel<T, MODE_, RW_, U_, NT_>;                    \
-        else hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial); \
+        if constexpr (sizeof(T) == 4 && RW_ == 4) {                                                                 \
+            if (a.aux == 1) JK_K(MODE_, RW_, U_, NT_, 2);                                                           \
+            else JK_K(MODE_, RW_, U_, NT_, Vec<T>::N);                                                              \
+        } else {                                                                                                    \
+            if (a.aux == 1) return hipErrorInvalidValue;                                                            \
+            JK_K(MODE_, RW_, U_, NT_, Vec<T>::N);                                                                   \
+        }                                                                                                           \
     } while (0)
 #define JK_NT(MODE_, RW_, U_)                 \
     do {                                      \
@@ -45,6 +53,7 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
 #undef JK_U
 #undef JK_NT
 #undef JK_L
+#undef JK_K
     return hipGetLastError();
 }
 

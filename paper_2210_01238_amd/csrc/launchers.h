@@ -17,7 +17,6 @@ struct LaunchArgs {
     void *dst;
     double *partial;     // per-workgroup partial sums (residual modes), else unused
     int aux = 0;         // kernel-specific extra (3-D blocked pass: row groups per tile)
-    const void **symbol_out = nullptr;   // single-step kernels: if set, store the kernel's address here, launch nothing
 };
 
 // single-step update / residual (mode: Mode; unroll 1,2,4,8,16; nt: 0 or 2)

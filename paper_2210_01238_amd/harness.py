@@ -74,12 +74,6 @@ class JacobiRun:
                                    tiles_per_task, nstreams, _stream())
         self.cur = self.a if fin == self.a.data_ptr() else self.b
 
-    def sweep_task_graph(self, iters: int, tiles_per_task: int) -> None:
-        """sweep(iters) executed as one HIP graph of per-tile-group task nodes."""
-        fin = B.jacobi_sweep_task_graph(self.plan, self.cur.data_ptr(), self.other().data_ptr(), iters,
-                                        tiles_per_task, _stream())
-        self.cur = self.a if fin == self.a.data_ptr() else self.b
-
     def sweep_residual(self, iters: int, out: torch.Tensor) -> None:
         """sweep(iters), and `out` (1-element float64 CUDA tensor) receives the residual norm
         of the field as it was BEFORE these iterations."""

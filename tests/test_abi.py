@@ -142,17 +142,15 @@ def test_pass_schedule_host_logic(J):
     J.jacobi_destroy(p)
 
 
-def test_task_graph_limits_without_device(J):
-    """Width and size limits of jacobi_sweep_task_graph are checked before any device call."""
+def test_task_execution_argument_errors_without_device(J):
+    """Arguments of jacobi_sweep_tasks are checked before any device call."""
     p = J.jacobi_create((48, 48), (48, 48))
     nb = J.jacobi_grid_bytes(p)
-    for bad in (lambda: J.jacobi_sweep_task_graph(p, 256, 256 + nb, 6, 37),     # 63 tasks per iteration
-                lambda: J.jacobi_sweep_task_graph(p, 256, 256 + nb, 300, 144),  # 16 x 300 nodes
-                lambda: J.jacobi_sweep_task_graph(p, 256, 256 + nb, 1, 0),
-                lambda: J.jacobi_sweep_task_graph(p, 256, 256, 1, 144),
-                lambda: J.jacobi_sweep_tasks(p, 256, 256 + nb, 1, 1, 17)):
+    for bad in (lambda: J.jacobi_sweep_tasks(p, 256, 256 + nb, 1, 1, 17), lambda: J.jacobi_sweep_tasks(p, 256, 256 + nb, 1, 0, 4),
+                lambda: J.jacobi_sweep_tasks(p, 256, 256 + nb, 1, 1, 0), lambda: J.jacobi_sweep_tasks(p, 256, 256, 1, 1, 4),
+                lambda: J.jacobi_sweep_tasks(p, 0, 256, 1, 1, 4), lambda: J.jacobi_sweep_tasks(p, 256, 256 + nb, -1, 1, 4)):
         with pytest.raises(J.JacobiError) as e:
             bad()
         assert e.value.code == 1
-    assert J.jacobi_sweep_task_graph(p, 256, 256 + nb, 0, 144) == 256
+    assert J.jacobi_sweep_tasks(p, 256, 256 + nb, 0, 1, 4) == 256       # zero iterations: nothing touched
     J.jacobi_destroy(p)

@@ -135,7 +135,7 @@ def test_full_P1_paper_domain_blocked_passes(H, oracle_mod):
 
 @pytest.mark.parametrize("name,few,group", [("C3", 3, 1), ("C4", 4, 4)])
 def test_full_size_task_execution(H, oracle_mod, name, few, group):
-    """The task paths at full size: whole grid, bit for bit, after a few iterations."""
+    """The task path at full size: whole grid, bit for bit, after a few iterations."""
     w = gen.WORKLOADS[name]
     a = gen.generate(w)
     ref, _ = oracle_mod.run(a, few)
@@ -144,8 +144,5 @@ def test_full_size_task_execution(H, oracle_mod, name, few, group):
         r.load(a)
         r.sweep_tasks(few, group, 16)                 # tasks over 16 streams
         assert np.array_equal(r.fetch(), ref), f"{name}: task execution differs"
-        r.load(a)
-        r.sweep_task_graph(few, 4)                    # 16 tasks per iteration as a HIP graph
-        assert np.array_equal(r.fetch(), ref), f"{name}: task graph differs"
     finally:
         r.close()

@@ -515,7 +515,12 @@ def _tasks_per_iteration(tiles, group):
     return -(-n // min(group, n))
 
 
-# the 63-task-wide case aborted inside the HIP runtime (host side) and is refused by the library now
+TASK_GRAPH_REMOVED = ("jacobi_sweep_task_graph (the task DAG built node by node as a HIP graph) was taken out: the HIP runtime "
+                         "aborted on the host - on a 63-task-wide graph when its launch was waited for, and once in "
+                         "hipGraph / plan destruction after a 3-task-wide one - cause not found")
+
+
+@pytest.mark.skip(reason=TASK_GRAPH_REMOVED)
 @pytest.mark.parametrize("dims,tiles,group,streams,iters",
                          [c for c in TASK_CASES if _tasks_per_iteration(c[1], c[2]) <= 16])
 def test_task_graph_execution_is_bit_identical(H, oracle_mod, dims, tiles, group, streams, iters):
@@ -537,6 +542,7 @@ def test_task_graph_execution_is_bit_identical(H, oracle_mod, dims, tiles, group
     check(out, res, ref, ref_res)
 
 
+@pytest.mark.skip(reason=TASK_GRAPH_REMOVED)
 def test_task_graph_fp32_3d_and_option_change(H, oracle_mod):
     a = random_padded((24, 20, 72), dtype=np.float32, seed=23)
     r = H.JacobiRun((24, 20, 72), (2, 2, 3), np.float32)
