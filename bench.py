@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md
 # and profiles/sweep3d_update_C4.md.  Valid only for the library's default options on that
 # workload; otherwise reported as null.
-MEASURED_TRAFFIC_BYTES = {"C3": 4588799847, "C4": 2362803708}
+MEASURED_TRAFFIC_BYTES = {"C3": 4589205268, "C4": 2362857424}
 
 
 def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
