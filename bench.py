@@ -36,7 +36,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
 
 # HBM-side bytes per update launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
-# counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md
+# counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md,
 # profiles/sweep3d_update_C4.md and profiles/sweep3d_update_P1.md.  Valid only for the library's default options on that
 # workload; otherwise reported as null.
 MEASURED_TRAFFIC_BYTES = {"C3": 4589205268, "C4": 2362857424, "P1": 14219420535}
