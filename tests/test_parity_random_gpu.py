@@ -79,3 +79,38 @@ def test_random_3d(H, oracle_mod, n, case):
 @pytest.mark.parametrize("n,case", list(enumerate(make_cases(3, 80, 20221003, blocked_3d=True))))
 def test_random_3d_blocked(H, oracle_mod, n, case):
     run_random(H, oracle_mod, case, 3000 + n)
+
+
+def make_task_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for n in range(count):
+        if n % 2 == 0:
+            dims = (int(rng.integers(1, 120)), int(rng.integers(1, 400)))
+        else:
+            dims = (int(rng.integers(1, 20)), int(rng.integers(1, 30)), int(rng.integers(1, 200)))
+        tiles = tuple(int(rng.choice(divisors(d))) for d in dims)
+        ntiles = int(np.prod(tiles))
+        group = int(rng.integers(1, ntiles + 2))
+        streams = int(rng.integers(1, 17))
+        iters = int(rng.integers(1, 12))
+        opts = dict(rows_per_strip=int(rng.choice([0, 0, 1, 3, 8, 33])), xcd_chunk=int(rng.choice([0, 1, 8])))
+        cases.append((dims, tiles, group, streams, iters, opts))
+    return cases
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_task_cases(60, 20221004))))
+def test_random_task_execution(H, oracle_mod, n, case):
+    """jacobi_sweep_tasks on random shapes, tilings, task sizes and stream counts."""
+    dims, tiles, group, streams, iters, opts = case
+    a = random_padded(dims, seed=4000 + n)
+    r = H.JacobiRun(dims, tiles, **opts)
+    try:
+        r.load(a)
+        r.sweep_tasks(iters, group, streams)
+        out = r.fetch()
+        res = [r.residual()]
+    finally:
+        r.close()
+    ref, ref_res = oracle_mod.run(a, iters, iters)
+    check(out, res, ref, ref_res)
