@@ -552,6 +552,64 @@ template <typename T, int TB, int NDIM> struct TpGeometry {
     static constexpr int SEGW = OWN_LANES * NV;            // columns a wavefront owns
 };
 
+// Where a lane of a blocked pass sits along a row of tiles.  A wavefront's 64 lanes cover the columns
+// [seg*SEGW - GH, seg*SEGW - GH + 64*NV) counted along the whole row of tiles (0 .. Tx*tw-1; -1 and Tx*tw
+// are the Dirichlet ring).  kind: 0 cells of some tile, 1 the W ring cell in the last component, 2 the E
+// ring cell in the first component, 3 nothing there.  `bytes` is the per-lane byte offset, the same for
+// every row (relative to the row's first cell in the first tile of the row of tiles): the lane's cells,
+// or (ring lanes) the place in the first / last tile's x-halo array from which a vector read puts the ring
+// value into the component next to the tile cells (a ring lane's other components are never used).
+struct TpLane {
+    int kind;
+    unsigned bytes;
+    bool ring_lane;       // kind 1 or 2
+    bool wave_has_ring;   // some lane of the wavefront is a ring lane
+    bool owner;           // the lane stores its columns (not a ghost lane, and there are cells)
+};
+template <typename T, int NV, int GL, int SEGW>
+__device__ __forceinline__ TpLane tp_lane(const Geo &g, int seg, int lane)
+{
+    const int wrow = g.Tx * g.tw;
+    const int gc = seg * SEGW - GL * NV + lane * NV;
+    TpLane L;
+    int txx = 0, cc = 0;
+    L.kind = 0;
+    if (gc < 0) L.kind = gc == -NV ? 1 : 3;
+    else if (gc >= wrow) L.kind = gc == wrow ? 2 : 3;
+    else { txx = gc / g.tw; cc = gc - txx * g.tw; }
+    long long elems = 0;
+    if (L.kind == 0) elems = (long long)txx * g.tile_stride + cc;
+    else if (L.kind == 1) elems = g.xoff - (NV - 1);
+    else if (L.kind == 2) elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
+    L.bytes = (unsigned)(elems * (long long)sizeof(T));
+    L.ring_lane = L.kind == 1 || L.kind == 2;
+    L.wave_has_ring = __any(L.ring_lane) != 0;
+    L.owner = lane >= GL && lane < WAVE - GL && L.kind == 0;
+    return L;
+}
+
+// Plane kappa of u(t), counted from a tile of z-layer tz and clamped onto the Dirichlet planes: the
+// element offset of its cells (z-layer of tiles + plane), and the distance from a row's first cell to
+// the row's x-halo entry that the plane contributes.  kappa in (-td, 2*td]: at most one tile away.
+struct TpPlane { long long cells; int to_halo; };
+__device__ __forceinline__ TpPlane tp_locate_plane(const Geo &g, int tz, bool z_lo_ring, bool z_hi_ring,
+                                                   long long layer_stride, int kappa, int max_beyond)
+{
+    int tzz = tz, kk;
+    kappa = min(kappa, g.td + max_beyond);
+    if (kappa <= 0) {
+        if (!z_lo_ring) { tzz = tz - 1; kk = g.td + kappa; }
+        else kk = 0;
+    } else if (kappa > g.td) {
+        if (!z_hi_ring) { tzz = tz + 1; kk = kappa - g.td; }
+        else kk = g.td + 1;
+    } else kk = kappa;
+    TpPlane P;
+    P.cells = (long long)tzz * layer_stride + (long long)kk * g.plane;
+    P.to_halo = kk * g.rows - (int)((long long)kk * g.plane);
+    return P;
+}
+
 template <typename T, int MODE, int TB, int PF, int MINW>
 __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams sp,
                                                               const T *__restrict__ src, T *__restrict__ dst,
@@ -561,7 +619,6 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
     constexpr int NV = Vec<T>::N;
     typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
     constexpr int GL = TpGeometry<T, TB, 2>::GHOST_LANES;
-    constexpr int GH = GL * NV;
     constexpr int SEGW = TpGeometry<T, TB, 2>::SEGW;
     static_assert(PF >= 2 && PF % 2 == 0, "the two-row windows swap roles every step");
     static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
@@ -583,27 +640,10 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
         const int r0 = 1 + rb * sp.R;
         const int r1 = min(g.th, r0 + sp.R - 1);
 
-        // ---- columns of this lane, counted along the row of tiles (0 .. Tx*tw-1; -1 and Tx*tw are
-        // the Dirichlet ring).  kind: 0 cells of some tile, 1 W ring in the last component,
-        // 2 E ring in the first component, 3 nothing there
-        const int wrow = g.Tx * g.tw;
-        const int gc = seg * SEGW - GH + lane * NV;
-        int kind = 0, txx = 0, cc = 0;
-        if (gc < 0) kind = gc == -NV ? 1 : 3;
-        else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
-        else { txx = gc / g.tw; cc = gc - txx * g.tw; }
-        // Per-lane byte offset, the same for every row (relative to the row's first cell in the first
-        // tile of the row of tiles): the lane's cells, or (ring lanes) the place in the first / last
-        // tile's x-halo array from which a vector read puts the ring value into the component next to
-        // the tile cells (a ring lane's other components are never used).
-        long long lane_elems = 0;
-        if (kind == 0) lane_elems = (long long)txx * g.tile_stride + cc;
-        else if (kind == 1) lane_elems = g.xoff - (NV - 1);
-        else if (kind == 2) lane_elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
-        const unsigned lane_bytes = (unsigned)(lane_elems * (long long)sizeof(T));
-        const bool ring_lane = kind == 1 || kind == 2;
-        const bool wave_has_ring = __any(ring_lane) != 0;
-        const bool owner = lane >= GL && lane < WAVE - GL && kind == 0;
+        const TpLane L = tp_lane<T, NV, GL, SEGW>(g, seg, lane);
+        const int kind = L.kind;
+        const unsigned lane_bytes = L.bytes;
+        const bool ring_lane = L.ring_lane, wave_has_ring = L.wave_has_ring, owner = L.owner;
         const bool top_ring = ty == 0, bottom_ring = ty == g.Ty - 1;
         const long long tilerow = (long long)g.Tx * g.tile_stride;
         T *trow = dst + (long long)ty * tilerow;                 // first tile of this row of tiles
@@ -874,7 +914,6 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
     constexpr int NV = Vec<T>::N;
     typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
     constexpr int GL = G3::GHOST_LANES;
-    constexpr int GH = GL * NV;
     constexpr int SEGW = G3::SEGW;
     constexpr int NRW = RW + 2 * TB;
     static_assert(MODE != MODE_RESIDUAL, "stand-alone residual uses the single-step kernel");
@@ -902,24 +941,10 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
         const int i0 = 1 + rg * RW;
         const long long tilerow = (long long)g.Tx * g.tile_stride;     // elements in one row of tiles
 
-        // ---- columns of this lane along the row of tiles
-        const int wrow = g.Tx * g.tw;
-        const int gc = seg * SEGW - GH + lane * NV;
-        int kind = 0, txx = 0, cc = 0;   // 0 tile cells, 1 W ring in last component, 2 E ring in first, 3 nothing
-        if (gc < 0) kind = gc == -NV ? 1 : 3;
-        else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
-        else { txx = gc / g.tw; cc = gc - txx * g.tw; }
-        // Per-lane byte offset that never changes: the lane's cells, or (ring lanes) the place in the
-        // first / last tile's x-halo array from which a vector read puts the ring value into the
-        // component next to the tile cells (the other components of a ring lane are never used).
-        long long lane_elems = 0;
-        if (kind == 0) lane_elems = (long long)txx * g.tile_stride + cc;
-        else if (kind == 1) lane_elems = g.xoff - (NV - 1);
-        else if (kind == 2) lane_elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
-        const unsigned lane_bytes = (unsigned)(lane_elems * (long long)sizeof(T));
-        const bool ring_lane = kind == 1 || kind == 2;
-        const bool wave_has_ring = __any(ring_lane) != 0;
-        const bool owner = lane >= GL && lane < WAVE - GL && kind == 0;
+        const TpLane L = tp_lane<T, NV, GL, SEGW>(g, seg, lane);
+        const int kind = L.kind;
+        const unsigned lane_bytes = L.bytes;
+        const bool ring_lane = L.ring_lane, wave_has_ring = L.wave_has_ring, owner = L.owner;
         const bool z_lo_ring = tz == 0, z_hi_ring = tz == g.Tz - 1;
 
         // ---- rows j = 0..NRW-1 <-> tile row iota = i0 - TB + j, followed into the tiles above / below
@@ -941,22 +966,13 @@ __global__ __launch_bounds__(WG, MINW) void sweep3d_tp_kernel(Geo g, StripParams
             row_base[j] = (long long)tyy * tilerow + (long long)rr * g.pitch;
             row_to_halo[j] = rr - rr * g.pitch;
         }
-        // plane kappa of u(t) (relative to this tile, clamped): offset of its cells, and the distance from
-        // a row's first cell to the row's x-halo entry
+        // plane kappa of u(t), relative to this tile: where its cells and x-halo entries are
         long long pl_cells;
         int pl_to_halo;
         auto locate_plane = [&](int kappa) {
-            int tzz = tz, kk;
-            kappa = min(kappa, g.td + TB);
-            if (kappa <= 0) {
-                if (!z_lo_ring) { tzz = tz - 1; kk = g.td + kappa; }
-                else kk = 0;
-            } else if (kappa > g.td) {
-                if (!z_hi_ring) { tzz = tz + 1; kk = kappa - g.td; }
-                else kk = g.td + 1;
-            } else kk = kappa;
-            pl_cells = (long long)tzz * g.Ty * tilerow + (long long)kk * g.plane;
-            pl_to_halo = kk * g.rows - (int)((long long)kk * g.plane);
+            const TpPlane P = tp_locate_plane(g, tz, z_lo_ring, z_hi_ring, g.Ty * tilerow, kappa, TB);
+            pl_cells = P.cells;
+            pl_to_halo = P.to_halo;
         };
         auto load_row = [&](int j) -> V {
             const T *rowp = src + (pl_cells + row_base[j]);
@@ -1076,7 +1092,6 @@ __global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, Str
     constexpr int NV = Vec<T>::N;
     typedef T VU __attribute__((ext_vector_type(NV), aligned(sizeof(T))));
     constexpr int GL = G3::GHOST_LANES;
-    constexpr int GH = GL * NV;
     constexpr int SEGW = G3::SEGW;
     constexpr int WROWS = WPG * NR;              // rows a workgroup (WPG wavefronts) holds
     constexpr int OWN = WROWS - 2 * TB;          // rows it stores
@@ -1102,21 +1117,10 @@ __global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, Str
     const int y0 = 1 + yg * OWN;                 // first row this workgroup stores
     const long long tilerow = (long long)g.Tx * g.tile_stride;
 
-    // ---- columns of this lane along the row of tiles (see sweep3d_tp_kernel)
-    const int wrow = g.Tx * g.tw;
-    const int gc = seg * SEGW - GH + lane * NV;
-    int kind = 0, txx = 0, cc = 0;   // 0 tile cells, 1 W ring in last component, 2 E ring in first, 3 nothing
-    if (gc < 0) kind = gc == -NV ? 1 : 3;
-    else if (gc >= wrow) kind = gc == wrow ? 2 : 3;
-    else { txx = gc / g.tw; cc = gc - txx * g.tw; }
-    long long lane_elems = 0;
-    if (kind == 0) lane_elems = (long long)txx * g.tile_stride + cc;
-    else if (kind == 1) lane_elems = g.xoff - (NV - 1);
-    else if (kind == 2) lane_elems = (long long)(g.Tx - 1) * g.tile_stride + g.xoff + g.hpitch;
-    const unsigned lane_bytes = (unsigned)(lane_elems * (long long)sizeof(T));
-    const bool ring_lane = kind == 1 || kind == 2;
-    const bool wave_has_ring = __any(ring_lane) != 0;
-    const bool owner = lane >= GL && lane < WAVE - GL && kind == 0;
+    const TpLane L = tp_lane<T, NV, GL, SEGW>(g, seg, lane);
+    const int kind = L.kind;
+    const unsigned lane_bytes = L.bytes;
+    const bool ring_lane = L.ring_lane, wave_has_ring = L.wave_has_ring, owner = L.owner;
     const bool z_lo_ring = tz == 0, z_hi_ring = tz == g.Tz - 1;
 
     // ---- this wavefront's rows j = 0..NR-1: row y0 - TB + wave*NR + j of the column of tiles
@@ -1139,17 +1143,9 @@ __global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, Str
     long long pl_cells;
     int pl_to_halo;
     auto locate_plane = [&](int kappa) {
-        int tzz = tz, kk;
-        kappa = min(kappa, g.td + TB);
-        if (kappa <= 0) {
-            if (!z_lo_ring) { tzz = tz - 1; kk = g.td + kappa; }
-            else kk = 0;
-        } else if (kappa > g.td) {
-            if (!z_hi_ring) { tzz = tz + 1; kk = kappa - g.td; }
-            else kk = g.td + 1;
-        } else kk = kappa;
-        pl_cells = (long long)tzz * g.Ty * tilerow + (long long)kk * g.plane;
-        pl_to_halo = kk * g.rows - (int)((long long)kk * g.plane);
+        const TpPlane P = tp_locate_plane(g, tz, z_lo_ring, z_hi_ring, g.Ty * tilerow, kappa, TB);
+        pl_cells = P.cells;
+        pl_to_halo = P.to_halo;
     };
     auto load_row = [&](int j) -> V {
         const T *rowp = src + (pl_cells + row_base[j]);

@@ -18,8 +18,11 @@ static hipError_t tc3d_dispatch(int depth, int mode, const LaunchArgs &a)
     do {                                         \
         if (depth == 2) JK_L(MODE_, 2);          \
         else if (depth == 3) JK_L(MODE_, 3);     \
-        else if (depth == 4) JK_L(MODE_, 4);     \
-        else return hipErrorInvalidValue;        \
+        else if (depth == 4) {                   \
+            /* fp32 passes stop at depth 3 */      \
+            if constexpr (sizeof(T) == 8) JK_L(MODE_, 4); \
+            else return hipErrorInvalidValue;    \
+        } else return hipErrorInvalidValue;      \
     } while (0)
     if (mode == MODE_UPDATE) JK_V(MODE_UPDATE);
     else if (mode == MODE_BOTH) JK_V(MODE_BOTH);

@@ -18,7 +18,11 @@ static hipError_t tp3d_dispatch(int depth, int rows_per_wave, int mode, const La
     do {                                                                   \
         if (depth == 2 && rows_per_wave == 2) JK_L(MODE_, 2, 2, 1, 3);     \
         else if (depth == 2 && rows_per_wave == 4) JK_L(MODE_, 2, 4, 1, 2);\
-        else if (sizeof(T) == 8 && depth == 3 && rows_per_wave == 2) JK_L(MODE_, 3, 2, 1, 2);\
+        else if (depth == 3 && rows_per_wave == 2) {                       \
+            /* fp32 passes of this kernel stop at depth 2 */                 \
+            if constexpr (sizeof(T) == 8) JK_L(MODE_, 3, 2, 1, 2);         \
+            else return hipErrorInvalidValue;                              \
+        }                                                                  \
         else return hipErrorInvalidValue;                                  \
     } while (0)
     if (mode == MODE_UPDATE) JK_V(MODE_UPDATE);
