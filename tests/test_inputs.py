@@ -56,3 +56,17 @@ def test_workload_table_matches_shapes():
     assert W["P1"].dims == (768, 1024, 1024) and W["P1"].points == 1024 * 1024 * 768
     for w in W.values():
         assert all(d % t == 0 for d, t in zip(w.dims, w.tiles))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU; asking for more exits with a message before touching any device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 2 and r.stdout.strip() == ""
