@@ -70,7 +70,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tblock", type=int, default=8,
+    ap.add_argument("--tblock", type=int, default=12,
                     help="depth limit of the extra temporal-blocking measurement (3-D passes advance 2 iterations)")
     ap.add_argument("--no-temporal-blocking", action="store_true",
                     help="skip the extra measurement with several iterations per pass")

@@ -237,11 +237,11 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *                    (0 = 4 where the tile allows; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
- *   "tblock"         1..8    temporal blocking depth: jacobi_sweep advances up to this many
+ *   "tblock"         1..12   temporal blocking depth: jacobi_sweep advances up to this many
  *                    iterations per pass over memory (3-D: at most 4 in fp64, 3 in fp32).  The
  *                    iterations of a call are spread evenly over the fewest passes the depth
  *                    allows (10 iterations at depth 8 run as 5 + 5; in 3-D as 4 + 3 + 3).
- *                    2-D passes of depth 3..8 need a tile width that is a multiple of 16 bytes
+ *                    2-D passes of depth 3..12 need a tile width that is a multiple of 16 bytes
  *                    and a tile height >= depth, depth 2 needs tiles >= 2 x 2; 3-D passes need
  *                    a tile width that is a multiple of 16 bytes and a tile depth >= the pass
  *                    depth; otherwise single steps are used.  Blocked passes read the cells they

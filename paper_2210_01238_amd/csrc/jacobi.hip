@@ -363,9 +363,9 @@ int launch_tc3d(jacobi_plan *p, int depth, const void *src, void *dst, bool with
 }
 
 // What the next pass does with `left` iterations to go.  The iterations are spread evenly over
-// the fewest passes the requested depth allows (10 iterations at depth 8 run as 5 + 5, not
-// 8 + 2: a pass costs little more for being deeper).  kernel: 0 single step (needs current
-// halos), 1 two-step kernel (2-D), 2 pipelined kernel (2-D, depths 3..8), 3 / 4 pipelined 3-D
+// few passes of equal depth (10 iterations at depth 8 run as 5 + 5, not 8 + 2: up to depth 8 a
+// pass costs no more for being deeper).  kernel: 0 single step (needs current
+// halos), 1 two-step kernel (2-D), 2 pipelined kernel (2-D, depths 3..12), 3 / 4 pipelined 3-D
 // kernels (depths 2..4).
 struct PassChoice { int depth; int kernel; };
 
@@ -395,9 +395,20 @@ PassChoice choose_pass(const jacobi_plan *p, int left)
                 if (const int k = pick_3d_kernel(p, d)) return {d, k};
         }
     } else if (maxd >= 2) {
-        const int passes = (left + maxd - 1) / maxd;
-        const int d = (left + passes - 1) / passes;
-        if (tp_usable(p, d)) return {d, 2};
+        int deepest = 0;                 // low tiles limit the depth (a pass reaches at most one tile up and down)
+        for (int d = maxd; d >= jk::TP_MIN && !deepest; --d)
+            if (tp_usable(p, d)) deepest = d;
+        if (deepest) {
+            // A pass is bound by memory up to about depth 8 (it costs the same whatever its depth) and by
+            // arithmetic beyond (cost proportional to the depth).  Cheapest plan: as many passes as fit at 8 or
+            // more iterations each, equally deep, none deeper than `deepest` (10 iterations: one pass of 10, not
+            // 5 + 5; 50: 9 + 9 + 8 + 8 + 8 + 8).
+            const int cap = deepest < 8 ? deepest : 8;
+            int passes = left / cap > 0 ? left / cap : 1;
+            if ((left + passes - 1) / passes > deepest) passes = (left + deepest - 1) / deepest;
+            const int best_d = (left + passes - 1) / passes;
+            if (best_d >= jk::TP_MIN) return {best_d, 2};
+        }
         if (t2_usable(p)) return {2, 1};
     }
     return {1, 0};
@@ -858,12 +869,12 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? 8 : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
     if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
     if (slot == &plan->nontemporal && value == 1) return fail(JACOBI_EINVAL, "nontemporal must be 0 or 2");
-    if (slot == &plan->tblock && value < 1) return fail(JACOBI_EINVAL, "tblock must be 1..8");
+    if (slot == &plan->tblock && value < 1) return fail(JACOBI_EINVAL, "tblock must be 1..12");
     if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)
         return fail(JACOBI_EINVAL, "rows_per_wave must be 0, 1, 2 or 4");
     *slot = value;

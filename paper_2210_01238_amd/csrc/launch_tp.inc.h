@@ -12,9 +12,9 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
     T *dst = (T *)a.dst;
     // Template arguments after the depth: rows loaded ahead (4), and the occupancy the compiler
     // must fit in wavefronts per SIMD - the largest that compiles without register spills
-    // (depth 8 needs 150 VGPRs, depth 6 118, with the residual about 18 more; only the
+    // (depth 8 needs 150 VGPRs, depth 6 118, depth 12 215, with the residual about 18 more; only the
     // depth-8 variants with the residual spill, 3 dwords, rather than drop to 2 wavefronts).
-#define JK_MINW(MODE_, TB_) ((TB_) >= 7 || ((TB_) == 6 && MODE_ == MODE_BOTH) ? 3 : 4)
+#define JK_MINW(MODE_, TB_) ((TB_) >= 9 ? 2 : (TB_) >= 7 || ((TB_) == 6 && MODE_ == MODE_BOTH) ? 3 : 4)
 #define JK_L(MODE_, TB_) \
     hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(MODE_, TB_)>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
 #define JK_D(MODE_)                         \
@@ -25,6 +25,10 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
     case 6: JK_L(MODE_, 6); break;          \
     case 7: JK_L(MODE_, 7); break;          \
     case 8: JK_L(MODE_, 8); break;          \
+    case 9: JK_L(MODE_, 9); break;          \
+    case 10: JK_L(MODE_, 10); break;        \
+    case 11: JK_L(MODE_, 11); break;        \
+    case 12: JK_L(MODE_, 12); break;        \
     default: return hipErrorInvalidValue;   \
     }
     if (mode == MODE_UPDATE) { JK_D(MODE_UPDATE) }

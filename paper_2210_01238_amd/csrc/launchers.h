@@ -29,7 +29,7 @@ hipError_t launch_sweep3d_f32(int mode, int rows_per_wave, int unroll, int nt, c
 constexpr int T2_ROWS = 8;
 hipError_t launch_t2(bool f64, int mode, const LaunchArgs &a);
 // TP_MIN..TP_MAX iterations per pass, pipelined down tall strips (overlapped wavefronts)
-constexpr int TP_MIN = 3, TP_MAX = 8;
+constexpr int TP_MIN = 3, TP_MAX = 12;
 hipError_t launch_tp_f64(int depth, int mode, const LaunchArgs &a);
 hipError_t launch_tp_f32(int depth, int mode, const LaunchArgs &a);
 

@@ -91,7 +91,7 @@ def test_null_and_argument_errors_without_device(J):
                  lambda: J.jacobi_scatter(p, 0, 256), lambda: J.jacobi_gather(p, 256, 0),
                  lambda: J.jacobi_set_option(p, "no_such_option", 1),
                  lambda: J.jacobi_set_option(p, "fused", 2), lambda: J.jacobi_set_option(p, "nontemporal", 1),
-                 lambda: J.jacobi_set_option(p, "tblock", 0), lambda: J.jacobi_set_option(p, "tblock", 9),
+                 lambda: J.jacobi_set_option(p, "tblock", 0), lambda: J.jacobi_set_option(p, "tblock", 13),
                  lambda: J.jacobi_set_option(p, "unroll", 3),
                  lambda: J.jacobi_set_option(p, "rows_per_strip", 5000),
                  lambda: J.jacobi_get_option(p, "bogus")):
@@ -122,6 +122,15 @@ def test_pass_schedule_host_logic(J):
     assert sched((64, 64), (2, 2), 0, 17, tblock=8) == [6, 6, 5]
     assert sched((64, 64), (2, 2), 0, 9, tblock=2) == [2, 2, 2, 2, 1]
     assert sched((64, 64), (2, 2), 0, 3, tblock=8) == [3]
+    # passes of 8 or more iterations cost the same per iteration: as many passes as fit at >= 8 each
+    assert sched((64, 64), (2, 2), 0, 10, tblock=12) == [10]
+    assert sched((64, 64), (2, 2), 0, 13, tblock=12) == [7, 6]
+    assert sched((64, 64), (2, 2), 0, 17, tblock=12) == [9, 8]
+    assert sched((64, 64), (2, 2), 0, 20, tblock=12) == [10, 10]
+    assert sched((64, 64), (2, 2), 0, 50, tblock=12) == [9, 9, 8, 8, 8, 8]
+    assert sched((64, 64), (2, 2), 0, 100, tblock=12) == [9] * 4 + [8] * 8
+    assert sched((64, 64), (8, 8), 0, 24, tblock=12) == [8, 8, 8]          # tile height 8 limits the depth
+    assert sched((64, 64), (16, 16), 0, 10, tblock=12) == [4, 3, 3]        # tile height 4
     assert sched((40, 36), (1, 36), 0, 6, tblock=8) == [1] * 6            # tiles one column wide: single steps
     assert sched((12, 63), (4, 1), 0, 8, tblock=8) == [2, 2, 2, 2]        # odd width, height 3: two-step kernel only
     # 3-D: fp64 up to 4 iterations per pass, fp32 up to 3

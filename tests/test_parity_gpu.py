@@ -355,7 +355,7 @@ def test_fused_residual_schedule_equals_separate(H, oracle_mod, tblock):
     check(out, res, ref, ref_res)
 
 
-@pytest.mark.parametrize("opts", [dict(tblock=d) for d in (3, 4, 5, 6, 7, 8)] +
+@pytest.mark.parametrize("opts", [dict(tblock=d) for d in (3, 4, 5, 6, 7, 8, 9, 10, 11, 12)] +
                          [dict(tblock=8, xcd_chunk=1), dict(tblock=4, nontemporal=0), dict(tblock=8, rows_per_strip=16),
                           dict(tblock=5, rows_per_strip=7), dict(tblock=8, rows_per_strip=4096)])
 @pytest.mark.parametrize("dims,tiles,iters,every", T2_CASES + [
@@ -372,7 +372,7 @@ def test_deep_temporal_blocking_is_bit_identical(H, oracle_mod, dims, tiles, ite
     check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
 
 
-@pytest.mark.parametrize("tblock", [3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("tblock", [3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
 def test_deep_temporal_blocking_fp32_and_fused_residual(H, oracle_mod, tblock):
     a = random_padded((96, 256), dtype=np.float32, seed=7)
     check(*run_case(H, oracle_mod, a, (3, 2), 21, 5, tblock=tblock))

@@ -39,7 +39,7 @@ def make_cases(ndim, count, seed, blocked_3d=False):
                     xcd_chunk=int(rng.choice([0, 1, 2, 8, 8, 64])),
                     nontemporal=int(rng.choice([0, 2, 2])))
         if ndim == 2:
-            opts["tblock"] = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8]))
+            opts["tblock"] = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8, 10, 12]))
         else:
             opts["rows_per_wave"] = int(rng.choice([0, 1, 2, 4]))
             if blocked_3d:
