@@ -40,6 +40,8 @@ int fail_hip(hipError_t e, const char *what)
 constexpr int MAX_TASK_STREAMS = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
+constexpr unsigned TP_LDS_PAD = 53 * 1024;   // 3 of these fit the 160 KiB of LDS of a CU, 4 do not
+constexpr int64_t TP_LDS_PAD_MIN_GRID = 1LL << 30;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -241,7 +243,12 @@ int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_r
     const StripParams sp = tp_strips(p, depth);
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
-    const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
+    jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
+    // On a grid much larger than the caches a blocked pass streams best with at most 3 workgroups on a CU
+    // (more wavefronts marching through memory at once slow the memory system down: 0.86 -> 0.80 ms per pass
+    // on 16384^2), so a third of the CU's LDS, which the kernel never touches, is requested with each
+    // workgroup.  Grids of 0.5 GB and less measured faster without the limit; deeper passes fit 2 anyway.
+    a.lds = depth <= 8 && p->lay.grid_bytes >= TP_LDS_PAD_MIN_GRID ? TP_LDS_PAD : 0;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
     return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp_f64(depth, mode, a) : jk::launch_tp_f32(depth, mode, a),
                           "pipelined blocked-pass kernel launch");

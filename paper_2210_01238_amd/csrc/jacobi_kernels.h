@@ -18,6 +18,7 @@
 // xcd_logical_wg() for how runs of workgroups are pinned to one XCD's L2.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace jk {
@@ -84,6 +85,27 @@ template <bool NT, typename V> __device__ __forceinline__ void stv(V *p, V v)
 {
     if constexpr (NT) __builtin_nontemporal_store(v, p);
     else *p = v;
+}
+
+// ---- buffer stores ----------------------------------------------------------------
+// A store through a buffer descriptor (base, size in bytes) with a per-lane byte offset: the
+// hardware drops every lane whose offset lies beyond the size.  A pipelined loop can therefore
+// issue exactly one store per step, whoever has something to store (lanes and steps that have
+// not are given BUF_SKIP), and the compiler can count the outstanding memory operations: with
+// stores inside branches it cannot, and every wait for a prefetched row then also waits for the
+// stores issued after that row's load.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned BUF_SKIP = 0x80000000u;          // beyond any buffer used here (sizes stay below 2 GiB)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(void *base, unsigned bytes)
+{
+    // 4th descriptor word: raw 32-bit data format, no swizzle, offsets checked against the size
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
+}
+template <typename V>
+__device__ __forceinline__ void buffer_store_stream(V v, __amdgpu_buffer_rsrc_t buf, unsigned byte_offset)
+{
+    static_assert(sizeof(V) == 16, "one 16-byte vector per lane");
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), buf, (int)byte_offset, 0, 2 /* streaming */);
 }
 
 // ---- cross-lane moves -------------------------------------------------------------
@@ -510,7 +532,7 @@ __global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
 }
 
 // ------------------------------------------------------------------------------------
-// 2-D, TB time steps per pass over memory (temporal blocking, depths 3..8), pipelined down
+// 2-D, TB time steps per pass over memory (temporal blocking, depths 3..12), pipelined down
 // the rows.
 //
 // Overlapped wavefronts: a wavefront still loads 64 lanes x 16 bytes per row, but only its
@@ -528,10 +550,13 @@ __global__ __launch_bounds__(WG) void sweep2d_t2_kernel(Geo g, StripParams sp,
 // (rho - l) from the three rows (rho-l-1, rho-l, rho-l+1) of level l-1, the last of which the
 // level before has just produced.  Only two rows per level stay in registers (2*TB vectors),
 // whatever the strip height, and the only redundant work is the 2*TB-row run-in of a strip.
-// Ring cells keep their value by copying the centre value (the same cell one level down),
-// under wave-uniform branches that ordinary wavefronts skip.  Every value is formed by the
-// single-step expression, so a pass is bit-identical to TB single steps.
-// Needs tw a multiple of the vector width and th >= TB.
+// Ring cells keep their value by selecting the centre value (the same cell one level down);
+// strips that cannot reach a ring cell run a copy of the loop without the selects.  Every
+// value is formed by the single-step expression, so a pass is bit-identical to TB single steps.
+// Memory operations in the loop are unconditional and counted: one load per row PF rows ahead
+// and one buffer store per row (see buffer_store_stream), so the only wait of a trip is for
+// its own loads and a trip's stores stay in flight during the next one.
+// Needs tw a multiple of the vector width, th >= TB, and a row of tiles smaller than 2 GiB.
 // ------------------------------------------------------------------------------------
 // Column geometry of a blocked pass of depth TB: every level loses one ghost column per side,
 // so at least ceil(TB / vector width) lanes per side are ghosts and the rest own their columns.
@@ -610,8 +635,8 @@ __device__ __forceinline__ TpPlane tp_locate_plane(const Geo &g, int tz, bool z_
     return P;
 }
 
-template <typename T, int MODE, int TB, int PF, int MINW>
-__global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams sp,
+template <typename T, int MODE, int TB, int PF, int MINW, int MAXW>
+__global__ __attribute__((amdgpu_flat_work_group_size(WG, WG), amdgpu_waves_per_eu(MINW, MAXW))) void sweep2d_tp_kernel(Geo g, StripParams sp,
                                                               const T *__restrict__ src, T *__restrict__ dst,
                                                               double *__restrict__ partial)
 {
@@ -647,6 +672,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
         const bool top_ring = ty == 0, bottom_ring = ty == g.Ty - 1;
         const long long tilerow = (long long)g.Tx * g.tile_stride;
         T *trow = dst + (long long)ty * tilerow;                 // first tile of this row of tiles
+        const __amdgpu_buffer_rsrc_t out_rows = buffer_of(trow, (unsigned)(tilerow * (long long)sizeof(T)));
 
         // u(t) row rho (relative to this tile; clamped to [-(TB), th+1+TB] and onto the ring)
         auto load_row = [&](int rho) -> V {
@@ -665,60 +691,76 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
             return *(const VU *)((const char *)rowp + off);      // ring lanes read element-aligned
         };
 
-        V w[TB][2];                      // per level l (0..TB-1): the two newest rows, roles swap each step
+        // The strip's pipeline, compiled twice: with the selects that keep Dirichlet cells (FREEZE), and
+        // without them for the strips that can never produce one - no ring lane in the wavefront and no
+        // ring row within reach of the strip's rows (a level-l row matters up to TB - l rows beyond them).
+        // The selects are a quarter of the loop's vector instructions.
+        auto run_strip = [&](auto freeze) {
+            constexpr bool FREEZE = decltype(freeze)::value;
+            V w[TB][2];                      // per level l (0..TB-1): the two newest rows, roles swap each step
 #pragma unroll
-        for (int l = 0; l < TB; ++l) w[l][0] = w[l][1] = V(0);
+            for (int l = 0; l < TB; ++l) w[l][0] = w[l][1] = V(0);
 
-        const int nsteps = (r1 - r0 + 1) + 2 * TB;          // rows rho = r0-TB .. r1+TB
-        const int nblocks = (nsteps + PF - 1) / PF;
-        V cur[PF], nxt[PF];
+            const int nsteps = (r1 - r0 + 1) + 2 * TB;          // rows rho = r0-TB .. r1+TB
+            const int nblocks = (nsteps + PF - 1) / PF;
+            V cur[PF], nxt[PF];
 #pragma unroll
-        for (int u = 0; u < PF; ++u) cur[u] = load_row(r0 - TB + u);
+            for (int u = 0; u < PF; ++u) cur[u] = load_row(r0 - TB + u);
+            // The first rows have to have arrived before the loop is entered: the compiler places the loop's
+            // waits for the longer-waiting of the two ways into it, and entered with loads still in flight the
+            // loop would wait at every row for the stores of the row before as well.
+#pragma unroll
+            for (int u = 0; u < PF; ++u) asm volatile("" : "+v"(cur[u]));
 
-        for (int b = 0; b < nblocks; ++b) {
+            for (int b = 0; b < nblocks; ++b) {
 #pragma unroll
-            for (int u = 0; u < PF; ++u) nxt[u] = load_row(r0 - TB + (b + 1) * PF + u);
+                for (int u = 0; u < PF; ++u) nxt[u] = load_row(r0 - TB + (b + 1) * PF + u);
 #pragma unroll
-            for (int u = 0; u < PF; ++u) {
-                const int q = b * PF + u;
-                const int rho = r0 - TB + q;             // row of u(t) entering the pipeline
-                const int p = u & 1;                     // slot holding the OLDER row of every level
-                V down = cur[u];
+                for (int u = 0; u < PF; ++u) {
+                    const int q = b * PF + u;
+                    const int rho = r0 - TB + q;             // row of u(t) entering the pipeline
+                    const int p = u & 1;                     // slot holding the OLDER row of every level
+                    V down = cur[u];
 #pragma unroll
-                for (int l = 1; l <= TB; ++l) {
-                    const V up = w[l - 1][p], c = w[l - 1][1 - p];
-                    const int row = rho - l;             // the row this level produces
-                    // Dirichlet cells keep their value: whole rows (wave-uniform) and the one component of
-                    // a ring lane that is the ring column.  Selects, not branches: with branches the
-                    // compiler copied the whole vector around at every level (9 moves per level and row).
-                    const bool frozen_all = (top_ring && row == 0) || (bottom_ring && row == g.th + 1);
-                    const T left = from_prev_lane_or_zero(c[NV - 1]);
-                    const T right = from_next_lane_or_zero(c[0]);
-                    V nw;
+                    for (int l = 1; l <= TB; ++l) {
+                        const V up = w[l - 1][p], c = w[l - 1][1 - p];
+                        const int row = rho - l;             // the row this level produces
+                        // Dirichlet cells keep their value: whole rows (wave-uniform) and the one component of
+                        // a ring lane that is the ring column.  Selects, not branches: with branches the
+                        // compiler copied the whole vector around at every level (9 moves per level and row).
+                        const bool frozen_all = FREEZE && ((top_ring && row == 0) || (bottom_ring && row == g.th + 1));
+                        const T left = from_prev_lane_or_zero(c[NV - 1]);
+                        const T right = from_next_lane_or_zero(c[0]);
+                        V nw;
 #pragma unroll
-                    for (int j = 0; j < NV; ++j) {
-                        const T we = (j == 0 ? left : c[j - 1]) + (j == NV - 1 ? right : c[j + 1]);
-                        const T sn = up[j] + down[j];
-                        const bool frozen = frozen_all || (j == NV - 1 && kind == 1) || (j == 0 && kind == 2);
-                        nw[j] = frozen ? c[j] : Coef<T>::quarter * (we + sn);
-                        if constexpr (MODE == MODE_BOTH) {
-                            if (l == 1 && row >= r0 && row <= r1 && owner) {
-                                const T res = (we + sn) - Coef<T>::four * c[j];
-                                const double rd = (double)res;
-                                acc += rd * rd;
+                        for (int j = 0; j < NV; ++j) {
+                            const T we = (j == 0 ? left : c[j - 1]) + (j == NV - 1 ? right : c[j + 1]);
+                            const T sn = up[j] + down[j];
+                            const bool frozen = frozen_all || (j == NV - 1 && kind == 1) || (j == 0 && kind == 2);
+                            nw[j] = FREEZE && frozen ? c[j] : Coef<T>::quarter * (we + sn);
+                            if constexpr (MODE == MODE_BOTH) {
+                                if (l == 1 && row >= r0 && row <= r1 && owner) {
+                                    const T res = (we + sn) - Coef<T>::four * c[j];
+                                    const double rd = (double)res;
+                                    acc += rd * rd;
+                                }
                             }
                         }
+                        w[l - 1][p] = down;                  // the older row is dead: its slot takes the newest
+                        down = nw;
                     }
-                    w[l - 1][p] = down;                  // the older row is dead: its slot takes the newest
-                    down = nw;
+                    const int orow = rho - TB;               // `down` is now u(t+TB) of this row
+                    const bool stores = q >= 2 * TB && orow <= r1;
+                    const unsigned row_bytes = (unsigned)orow * (unsigned)(g.pitch * (int)sizeof(T));
+                    buffer_store_stream(down, out_rows, stores && owner ? lane_bytes + row_bytes : BUF_SKIP);
                 }
-                const int orow = rho - TB;               // `down` is now u(t+TB) of this row
-                if (q >= 2 * TB && orow <= r1 && owner)
-                    __builtin_nontemporal_store(down, (V *)((char *)(trow + (long long)orow * g.pitch) + lane_bytes));
-            }
 #pragma unroll
-            for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
-        }
+                for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
+            }
+        };
+        const bool reaches_ring = wave_has_ring || (top_ring && r0 <= TB) || (bottom_ring && r1 + TB > g.th);
+        if (reaches_ring) run_strip(std::true_type{});
+        else run_strip(std::false_type{});
     }
     if constexpr (MODE == MODE_BOTH) {
         const double tot = wg_sum(acc, red);

@@ -12,7 +12,7 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
 #define JK_K(MODE_, RW_, U_, NT_, NVEC_) \
-    hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+    hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial)
     // a.aux = 1: fp32 rows of at most 128 elements, 2 elements per lane (4 rows per wavefront only)
 #define JK_L(MODE_, RW_, U_, NT_)                                                                                   \
     do {                                                                                                            \

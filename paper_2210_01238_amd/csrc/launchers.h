@@ -17,6 +17,7 @@ struct LaunchArgs {
     void *dst;
     double *partial;     // per-workgroup partial sums (residual modes), else unused
     int aux = 0;         // kernel-specific extra (3-D blocked pass: row groups per tile)
+    unsigned lds = 0;    // dynamic LDS bytes nobody uses: they only limit how many workgroups share a CU
 };
 
 // single-step update / residual (mode: Mode; unroll 1,2,4,8,16; nt: 0 or 2)
