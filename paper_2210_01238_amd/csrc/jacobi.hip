@@ -42,6 +42,7 @@ constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 constexpr unsigned TP_LDS_PAD = 53 * 1024;   // 3 of these fit the 160 KiB of LDS of a CU, 4 do not
 constexpr int64_t TP_LDS_PAD_MIN_GRID = 1LL << 30;
+constexpr unsigned WHOLE_CU_LDS = 159 * 1024;   // with a kernel's own few bytes: no second workgroup fits in 160 KiB
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -76,6 +77,7 @@ struct SweepConfig {
     int rows_per_wave;   // 3-D only: rows one wavefront keeps in registers (1, 2 or 4)
     int unroll;          // rows (2-D) / planes (3-D) whose loads are issued back to back
     int lane_elems;      // elements per lane: 16 bytes' worth, or 2 for narrow fp32 rows in 3-D
+    bool whole_cu;       // 3-D update of a large grid: one workgroup per CU
 };
 
 SweepConfig make_config(const jacobi_plan *p, int mode)
@@ -117,8 +119,11 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     sp.fused = (int)p->fused;
     sp.xcd_chunk = (int)p->xcd_chunk;
     int u = (int)p->unroll;
+    // (fp64 rows that fill a wavefront's 64 x 16 bytes only: fp32, and tiles narrower than 128 cells, lose with it)
+    c.whole_cu = d3 && mode != jk::MODE_RESIDUAL && p->esize == 8 && g.pitch >= jk::WAVE * nv &&
+                 p->lay.grid_bytes >= TP_LDS_PAD_MIN_GRID;
     if (d3) {
-        if (u <= 0) u = 2;
+        if (u <= 0) u = c.whole_cu ? 1 : 2;     // planes per trip of the pipeline
         if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
     } else if (u <= 0) {
         u = R >= 16 ? 16 : R >= 8 ? 8 : R >= 4 ? 4 : R >= 2 ? 2 : 1;   // all of a short strip at once
@@ -148,6 +153,11 @@ int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *p
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     jk::LaunchArgs a{(unsigned)nwg, st, p->geo, c.sp, src, dst, partial};
     a.aux = c.lane_elems != 16 / (int)p->esize;       // 3-D fp32: the 8-byte-lane variant
+    // The 3-D march over a grid much larger than the caches runs fastest with ONE workgroup on a CU (0.418 ->
+    // 0.402 ms on 512^3: fewer wavefronts marching through memory at once suit the memory system better, and
+    // the pipeline keeps each one's loads in flight), so the update asks for all of the CU's LDS, which it never
+    // touches.  Small grids, and the read-only residual pass, measured faster without the limit.
+    a.lds = c.whole_cu ? WHOLE_CU_LDS : 0;
     const bool f64 = p->lay.dtype == JACOBI_F64;
     const int nt = (int)p->nontemporal;
     hipError_t e;
@@ -578,6 +588,10 @@ int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64
     if (L.tile_stride > lim || L.ntiles > lim || L.dims[0] + 2 > lim || L.dims[1] + 2 > lim || L.dims[2] + 2 > lim) {
         delete p;
         return fail(JACOBI_EINVAL, "tile or tile count too large (32-bit index limit inside a tile)");
+    }
+    if (ndim == 3 && L.plane * (int64_t)p->esize >= 0x80000000LL) {
+        delete p;
+        return fail(JACOBI_EINVAL, "tile too large (a plane of a 3-D tile must be smaller than 2 GiB)");
     }
     Geo &g = p->geo;
     g.ndim = ndim;

@@ -107,6 +107,27 @@ __device__ __forceinline__ void buffer_store_stream(V v, __amdgpu_buffer_rsrc_t 
     static_assert(sizeof(V) == 16, "one 16-byte vector per lane");
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), buf, (int)byte_offset, 0, 2 /* streaming */);
 }
+// The same with a second, wave-uniform offset (on this chip it counts towards the checked offset like the
+// per-lane one: measured); 16 or 8 bytes per lane.  Loads of lanes beyond the size return zero.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <typename V>
+__device__ __forceinline__ V buffer_load(__amdgpu_buffer_rsrc_t buf, unsigned byte_offset, unsigned row_offset)
+{
+    static_assert(sizeof(V) == 16 || sizeof(V) == 8, "8 or 16 bytes per lane");
+    if constexpr (sizeof(V) == 16)
+        return __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(buf, (int)byte_offset, (int)row_offset, 0));
+    else
+        return __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(buf, (int)byte_offset, (int)row_offset, 0));
+}
+template <bool STREAM, typename V>
+__device__ __forceinline__ void buffer_store(V v, __amdgpu_buffer_rsrc_t buf, unsigned byte_offset, unsigned row_offset)
+{
+    static_assert(sizeof(V) == 16 || sizeof(V) == 8, "8 or 16 bytes per lane");
+    if constexpr (sizeof(V) == 16)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), buf, (int)byte_offset, (int)row_offset, STREAM ? 2 : 0);
+    else
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), buf, (int)byte_offset, (int)row_offset, STREAM ? 2 : 0);
+}
 
 // ---- cross-lane moves -------------------------------------------------------------
 // DPP wave shifts (full-rate VALU moves, no LDS traffic): lane i receives the value of
@@ -780,6 +801,14 @@ __global__ __attribute__((amdgpu_flat_work_group_size(WG, WG), amdgpu_waves_per_
 // ------------------------------------------------------------------------------------
 // NVEC: elements per lane.  16 bytes by default; fp32 grids whose rows are at most 128 elements
 // use 2 (8 bytes per lane), so that a 128-wide tile row fills the wavefront instead of half of it.
+//
+// The march is a software pipeline: everything a trip of U planes needs from memory (the U planes
+// above, the two border rows and the edge cells of its own planes) is requested one trip ahead, and
+// every memory operation of the loop is unconditional - rows are read and written through a buffer
+// descriptor of their plane, lanes beyond the row and rows that must not be stored get BUF_SKIP -
+// so that the compiler can count what is outstanding: a trip waits for its own data only, while
+// its stores and the next trip's loads stay in flight.  (With loads and stores under branches every
+// trip began by waiting for all of them.)  Needs planes smaller than 2 GiB.
 template <typename T, int MODE, int RW, int U, int NT, int NVEC = Vec<T>::N>
 __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
@@ -787,10 +816,12 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
 {
     typedef T V __attribute__((ext_vector_type(NVEC)));
     constexpr int NV = NVEC;
+    constexpr bool STORES = MODE != MODE_RESIDUAL;
     static_assert(RW >= 1 && RW <= 32, "edge gather uses lanes [0,RW) and [32,32+RW)");
     __shared__ double red[WAVES_PER_WG];
 
-    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    const int lane = threadIdx.x % WAVE;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);   // uniform: keeps the strip's geometry scalar
     const long long lwg = xcd_logical_wg(sp.xcd_chunk);
     const long long s = lwg * WAVES_PER_WG + wave;
     double acc = 0.0;
@@ -798,13 +829,16 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
     if (s < sp.nstrips) {
         const int ngrp = (g.th + RW - 1) / RW;
         const long long per_tile = (long long)sp.nblk * ngrp * sp.nseg;
-        const int tl = (int)(s / per_tile);                       // tile within this launch
+        // (the divisions run on the vector unit; their results are uniform and go back to scalar registers)
+        const int tl = __builtin_amdgcn_readfirstlane((int)(s / per_tile));      // tile within this launch
         int rem = (int)(s - (long long)tl * per_tile);
         const int t = sp.tile0 + tl;
-        const int kb = rem / (ngrp * sp.nseg);
+        const int kb = __builtin_amdgcn_readfirstlane(rem / (ngrp * sp.nseg));
         rem -= kb * ngrp * sp.nseg;
-        const int i0 = 1 + (rem / sp.nseg) * RW, seg = rem % sp.nseg;
-        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+        const int rg = __builtin_amdgcn_readfirstlane(rem / sp.nseg);
+        const int i0 = 1 + rg * RW, seg = rem - rg * sp.nseg;
+        const int tz = __builtin_amdgcn_readfirstlane(t / (g.Ty * g.Tx));
+        const int ty = __builtin_amdgcn_readfirstlane((t / g.Tx) % g.Ty), tx = __builtin_amdgcn_readfirstlane(t % g.Tx);
         const int k0 = 1 + kb * sp.R;
         const int k1 = min(g.td, k0 + sp.R - 1);
         const int col0 = (seg * WAVE + lane) * NV;
@@ -835,94 +869,127 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
         // register row after the last real row IS that row's y+ neighbour; clamped rows never store
         auto row_of = [&](int rw) { return min(i0 + rw, g.th + 1); };
 
-        V below[RW], cur[RW];
-#pragma unroll
-        for (int rw = 0; rw < RW; ++rw) {
-            below[rw] = cur[rw] = V(0);
-            if (active) {
-                below[rw] = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0 - 1, row_of(rw), col0)));
-                cur[rw] = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, k0, row_of(rw), col0)));
-            }
-        }
-        for (int k = k0; k <= k1; k += U) {
-            V up[U][RW], ym[U], yp[U];
-            T edge[U];
+        // one plane of a tile as a buffer: the lane's column and the row's start add up to the checked offset;
+        // lanes at or beyond the pitch get BUF_SKIP (they read zeros and store nothing)
+        const unsigned row_bytes = (unsigned)g.pitch * (unsigned)sizeof(T);
+        const unsigned plane_bytes = (unsigned)(g.plane * (long long)sizeof(T));       // below 2 GiB
+        const unsigned col_bytes = active ? (unsigned)col0 * (unsigned)sizeof(T) : BUF_SKIP;
+        auto src_plane = [&](int k) { return buffer_of(const_cast<T *>(tsrc) + (long long)k * g.plane, plane_bytes); };
+        auto dst_plane = [&](int k) { return buffer_of(tdst + (long long)k * g.plane, plane_bytes); };
+        auto row_start = [&](int row) { return (unsigned)row * row_bytes; };
+
+        // x-edge gather: lane l < RW fetches the W edge of row l, lane 32+l the E edge - from the x-halo
+        // arrays, or from the neighbouring segment's cells; the other lanes re-read the tile's first cell.
+        // (selects, not branches: a branch on the lane would drag wave-uniform values into vector registers)
+        const int el = lane & 31, ir = row_of(el);
+        const bool fetches = el < RW, w_side = lane < 32;
+        const long long w_off = w_halo ? xm_off(g, 0, ir) : main_off(g, 0, ir, seg_c0 - 1);
+        const long long e_off = seg_has_last ? xp_off(g, 0, ir) : e_in_row ? main_off(g, 0, ir, e_col) : 0;
+        const long long w_step = w_halo ? (long long)g.rows : g.plane;
+        const long long e_step = seg_has_last ? (long long)g.rows : e_in_row ? g.plane : 0;
+        const long long edge_off = fetches ? (w_side ? w_off : e_off) : 0;      // element offset in plane 0
+        const long long edge_step = fetches ? (w_side ? w_step : e_step) : 0;   // and per plane
+
+        // what the planes k .. k+U-1 need beyond the two planes already in registers
+        struct PlaneIn { V up[RW]; V ym, yp; T edge; };
+        auto fetch = [&](PlaneIn (&P)[U], int k) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int kn = min(k + u + 1, g.td + 1);   // clamped: stays inside the tile
-                const int kc = min(k + u, g.td + 1);
+                const int kc = min(k + u, g.td + 1);          // clamped: stays inside the tile
+                const int kn = min(k + u + 1, g.td + 1);
+                const __amdgpu_buffer_rsrc_t above = src_plane(kn), here = src_plane(kc);
 #pragma unroll
-                for (int rw = 0; rw < RW; ++rw)
-                    up[u][rw] = active ? ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, kn, row_of(rw), col0))) : V(0);
-                ym[u] = yp[u] = V(0);
-                if (active) {
-                    ym[u] = *(const V *)(tsrc + main_off(g, kc, i0 - 1, col0));
-                    yp[u] = *(const V *)(tsrc + main_off(g, kc, row_of(RW), col0));
-                }
-                // x-edge gather for plane kc: lane l < RW -> W edge of row l, lane 32+l -> E edge
-                edge[u] = T(0);
-                const int el = lane & 31;
-                if (el < RW) {
-                    const int ir = row_of(el);
-                    if (lane < 32) {
-                        edge[u] = w_halo ? tsrc[xm_off(g, kc, ir)] : tsrc[main_off(g, kc, ir, seg_c0 - 1)];
-                    } else if (seg_has_last) {
-                        edge[u] = tsrc[xp_off(g, kc, ir)];
-                    } else if (e_in_row) {
-                        edge[u] = tsrc[main_off(g, kc, ir, e_col)];
-                    }
-                }
+                for (int rw = 0; rw < RW; ++rw) P[u].up[rw] = buffer_load<V>(above, col_bytes, row_start(row_of(rw)));
+                P[u].ym = buffer_load<V>(here, col_bytes, row_start(i0 - 1));
+                P[u].yp = buffer_load<V>(here, col_bytes, row_start(row_of(RW)));
+                P[u].edge = tsrc[edge_off + (long long)kc * edge_step];
             }
+        };
+
+        V below[RW], cur[RW];
+        {
+            const __amdgpu_buffer_rsrc_t b0 = src_plane(k0 - 1), b1 = src_plane(k0);
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                below[rw] = buffer_load<V>(b0, col_bytes, row_start(row_of(rw)));
+                cur[rw] = buffer_load<V>(b1, col_bytes, row_start(row_of(rw)));
+            }
+        }
+
+        // planes k .. k+U-1 from the registers and P; stores nothing for planes beyond the strip
+        auto advance = [&](PlaneIn (&P)[U], int k) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int kk = k + u;
+                const __amdgpu_buffer_rsrc_t out_plane = dst_plane(min(kk, g.td + 1));
 #pragma unroll
                 for (int rw = 0; rw < RW; ++rw) {
                     const int i = i0 + rw;
+                    const bool wanted = kk <= k1 && i <= g.th;               // wave-uniform
                     const V c = cur[rw];
-                    const T ew = lane_value(edge[u], rw), ee = lane_value(edge[u], 32 + rw);
+                    const T ew = lane_value(P[u].edge, rw), ee = lane_value(P[u].edge, 32 + rw);
                     const T left = from_prev_lane(c[NV - 1], ew);    // lane 0 keeps the W edge
                     const T right = from_next_lane(c[0], ee);        // lane 63 keeps the E edge
-                    if (kk <= k1 && i <= g.th) {
-                        const V ymv = rw == 0 ? ym[u] : cur[rw == 0 ? 0 : rw - 1];
-                        const V ypv = rw == RW - 1 ? yp[u] : cur[rw == RW - 1 ? rw : rw + 1];
-                        V out;
+                    const V ymv = rw == 0 ? P[u].ym : cur[rw == 0 ? 0 : rw - 1];
+                    const V ypv = rw == RW - 1 ? P[u].yp : cur[rw == RW - 1 ? rw : rw + 1];
+                    V out;
 #pragma unroll
-                        for (int j = 0; j < NV; ++j) {
-                            const T w = j == 0 ? left : c[j - 1];
-                            T e = j == NV - 1 ? right : c[j + 1];
-                            if (has_last && j == jlast) e = ee;
-                            const T xx = w + e;
-                            const T yy = ymv[j] + ypv[j];
-                            const T zz = below[rw][j] + up[u][rw][j];
-                            if constexpr (MODE != MODE_RESIDUAL) out[j] = Coef<T>::sixth * ((xx + yy) + zz);
-                            if constexpr (MODE != MODE_UPDATE) {
-                                const T res = ((xx + yy) + zz) - Coef<T>::six * c[j];
-                                const double rd = (double)res;
-                                if (col0 + j <= last) acc += rd * rd;
-                            }
+                    for (int j = 0; j < NV; ++j) {
+                        const T w = j == 0 ? left : c[j - 1];
+                        T e = j == NV - 1 ? right : c[j + 1];
+                        if (has_last && j == jlast) e = ee;
+                        const T xx = w + e;
+                        const T yy = ymv[j] + ypv[j];
+                        const T zz = below[rw][j] + P[u].up[rw][j];
+                        out[j] = Coef<T>::sixth * ((xx + yy) + zz);
+                        if constexpr (MODE != MODE_UPDATE) {
+                            const T res = ((xx + yy) + zz) - Coef<T>::six * c[j];
+                            const double rd = (double)res;
+                            if (wanted && col0 + j <= last) acc += rd * rd;
                         }
-                        if constexpr (MODE != MODE_RESIDUAL) {
-                            if (active) {
-                                stv<(NT & 2) != 0>((V *)(tdst + main_off(g, kk, i, col0)), out);
-                                if (push) {
-                                    if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
-                                    if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
-                                    if (i == 1 && dst_ym) *(V *)(dst_ym + main_off(g, kk, g.th + 1, col0)) = out;
-                                    if (i == g.th && dst_yp) *(V *)(dst_yp + main_off(g, kk, 0, col0)) = out;
-                                    if (dst_xm) dst_xm[xp_off(g, kk, i)] = out[0];
-                                    if (dst_xp) dst_xp[xm_off(g, kk, i)] = out[jlast];
-                                }
-                            }
+                    }
+                    if constexpr (STORES) {
+                        buffer_store<(NT & 2) != 0>(out, out_plane, wanted ? col_bytes : BUF_SKIP, row_start(min(i, g.th + 1)));
+                        if (push && wanted && active) {
+                            if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
+                            if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
+                            if (i == 1 && dst_ym) *(V *)(dst_ym + main_off(g, kk, g.th + 1, col0)) = out;
+                            if (i == g.th && dst_yp) *(V *)(dst_yp + main_off(g, kk, 0, col0)) = out;
+                            if (dst_xm) dst_xm[xp_off(g, kk, i)] = out[0];
+                            if (dst_xp) dst_xp[xm_off(g, kk, i)] = out[jlast];
                         }
                     }
                 }
 #pragma unroll
                 for (int rw = 0; rw < RW; ++rw) {
                     below[rw] = cur[rw];
-                    cur[rw] = up[u][rw];
+                    cur[rw] = P[u].up[rw];
                 }
             }
+        };
+
+        // Two sets of inputs take turns, so that no register is copied.  The first set has to have arrived
+        // before the loop: entered with loads in flight, the loop's waits would be placed for that longer wait.
+        PlaneIn A[U], B[U];
+        fetch(A, k0);
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) {
+            asm volatile("" : "+v"(below[rw]));
+            asm volatile("" : "+v"(cur[rw]));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) asm volatile("" : "+v"(A[u].up[rw]));
+            asm volatile("" : "+v"(A[u].ym));
+            asm volatile("" : "+v"(A[u].yp));
+            asm volatile("" : "+v"(A[u].edge));
+        }
+        for (int k = k0; k <= k1; k += 2 * U) {
+            fetch(B, k + U);
+            advance(A, k);
+            fetch(A, k + 2 * U);
+            advance(B, k + U);
         }
     }
     if constexpr (MODE != MODE_UPDATE) {
