@@ -55,7 +55,8 @@ enum jacobi_status {
     JACOBI_OK = 0,
     JACOBI_EINVAL = 1,  /* null or misaligned pointer, ndim not 2/3, dim <= 0, tiles <= 0, bad
                            dtype, in == out or overlapping, iters < 0, unknown option or value,
-                           tile too large */
+                           tile too large (2^31 elements or more, or a plane of a 3-D tile of
+                           2 GiB or more) */
     JACOBI_ENOTDIV = 2, /* dims[d] % tiles[d] != 0 */
     JACOBI_ENOMEM = 3,  /* host or device allocation failed */
     JACOBI_EHIP = 4     /* a HIP call failed; text in jacobi_last_error() */

@@ -1277,7 +1277,12 @@ __global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, Str
 #pragma unroll
     for (int j = 0; j < NR; ++j) ld[j] = load_row(j);
 
+    // the first plane has to have arrived before the loop (its waits are placed for the longer-waiting entry)
+#pragma unroll
+    for (int j = 0; j < NR; ++j) asm volatile("" : "+v"(ld[j]));
+
     const long long out_layer = (long long)tz * g.Ty * tilerow;
+    const unsigned tilerow_bytes = (unsigned)(tilerow * (long long)sizeof(T));      // below 2 GiB
     const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, WPG - 1);
 
     for (int q0 = 0; q0 < nsteps; q0 += 2) {
@@ -1336,9 +1341,10 @@ __global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, Str
                     d = nw;
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // after TB levels `d` is u(t+TB) of plane kappa-TB
-                if (store_plane && own_row[j] && owner)
-                    __builtin_nontemporal_store(d, (V *)((char *)(dst + (out_plane + row_base[j])) + lane_bytes));
+                // after TB levels `d` is u(t+TB) of plane kappa-TB: one counted store per row, dropped where
+                // there is nothing to store (see buffer_store_stream)
+                buffer_store_stream(d, buffer_of(dst + (out_plane + row_base[j]), tilerow_bytes),
+                                    store_plane && own_row[j] && owner ? lane_bytes : BUF_SKIP);
                 // keep the rows in program order: hoisting later rows' loads and LDS reads costs registers
                 __builtin_amdgcn_sched_barrier(0);
             }

@@ -65,6 +65,7 @@ def test_layout_ragged_and_f32_and_3d(J):
     ((10, 10), (3, 2), 0, 2), ((0, 10), (1, 1), 0, 1), ((10, 10), (0, 1), 0, 1),
     ((10, 10), (1, 1), 7, 1), ((10,), (1,), 0, 1), ((4, 4, 4, 4), (1, 1, 1, 1), 0, 1),
     ((-5, 10), (1, 1), 0, 1), ((8, 8, 9), (2, 2, 2), 1, 2),
+    ((1, 20000, 20000), (1, 1, 1), 0, 1),       # a plane of a 3-D tile must stay below 2 GiB
 ])
 def test_create_rejects(J, dims, tiles, dtype, code):
     with pytest.raises(J.JacobiError) as e:
