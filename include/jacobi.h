@@ -232,7 +232,8 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *                    (default 2).  Streaming loads were measured slower (border rows are
  *                    re-read from cache) and are not offered.  Blocked passes always stream.
  *   "unroll"         0 | 1 | 2 | 4 | 8  rows (planes) whose loads a wavefront issues back to
- *                    back before computing; 0 = choose: 2-D the whole strip, up to 8; 3-D 2
+ *                    back before computing (3-D: planes per trip of the load pipeline); 0 = choose:
+ *                    2-D the whole strip, up to 8; 3-D 2, or 1 on fp64 grids of 1 GiB and more
  *                    (3-D accepts at most 4) (default 0)
  *   "rows_per_wave"  0 | 1 | 2 | 4  3-D: rows of a plane one wavefront keeps in registers
  *                    (0 = 4 where the tile allows; default 0)

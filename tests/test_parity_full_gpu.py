@@ -146,3 +146,42 @@ def test_full_size_task_execution(H, oracle_mod, name, few, group):
         assert np.array_equal(r.fetch(), ref), f"{name}: task execution differs"
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("name,opts,n", [("C4", {}, 4), ("C3", dict(tblock=8), 16), ("C3", {}, 2)])
+def test_full_size_sweep_in_a_hip_graph(H, name, opts, n):
+    """On large grids some launches request LDS only to limit the workgroups per CU (and one kernel
+    has to be allowed the larger request first).  Recorded into a HIP graph they must behave the
+    same: every replay equals the eager run, bit for bit."""
+    import torch
+    w = gen.WORKLOADS[name]
+    a = gen.generate(w)
+    r = H.JacobiRun(w.dims, w.tiles, **opts)
+    try:
+        r.load(a)
+        r.sweep(3 * n)
+        eager3 = r.fetch_device().clone()
+        r.load(a)
+        r.sweep(2 * n)
+        eager2 = r.fetch_device().clone()
+        r.load(a)
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            r.sweep(n)                                # eager, on the side stream
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        src, dst = r.cur, r.other()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            fin = H.B.jacobi_sweep(r.plan, src.data_ptr(), dst.data_ptr(), n,
+                                   int(torch.cuda.current_stream().cuda_stream))
+        assert fin == src.data_ptr()                  # an even number of passes
+        for expect in (eager2, eager3):               # two replays with eager work in between
+            g.replay()
+            torch.cuda.synchronize()
+            got = r.fetch_device()
+            torch.cuda.synchronize()
+            assert torch.equal(got, expect), f"{name} {opts}: replay differs from the eager run"
+    finally:
+        r.close()
