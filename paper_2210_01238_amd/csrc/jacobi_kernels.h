@@ -733,7 +733,8 @@ __global__ __attribute__((amdgpu_flat_work_group_size(WG, WG), amdgpu_waves_per_
 #pragma unroll
             for (int u = 0; u < PF; ++u) asm volatile("" : "+v"(cur[u]));
 
-            for (int b = 0; b < nblocks; ++b) {
+            // one block of PF rows; `storing`: whether the block can contain a row to store
+            auto block = [&](int b, auto storing) {
 #pragma unroll
                 for (int u = 0; u < PF; ++u) nxt[u] = load_row(r0 - TB + (b + 1) * PF + u);
 #pragma unroll
@@ -773,11 +774,17 @@ __global__ __attribute__((amdgpu_flat_work_group_size(WG, WG), amdgpu_waves_per_
                     const int orow = rho - TB;               // `down` is now u(t+TB) of this row
                     const bool stores = q >= 2 * TB && orow <= r1;
                     const unsigned row_bytes = (unsigned)orow * (unsigned)(g.pitch * (int)sizeof(T));
-                    buffer_store_stream(down, out_rows, stores && owner ? lane_bytes + row_bytes : BUF_SKIP);
+                    if constexpr (decltype(storing)::value)
+                        buffer_store_stream(down, out_rows, stores && owner ? lane_bytes + row_bytes : BUF_SKIP);
                 }
 #pragma unroll
                 for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
-            }
+            };
+            // the run-in blocks (rows that only fill the pipeline) issue no stores at all; every later block
+            // issues exactly PF, so that they can be counted
+            const int run_in = min(2 * TB / PF, nblocks);
+            for (int b = 0; b < run_in; ++b) block(b, std::false_type{});
+            for (int b = run_in; b < nblocks; ++b) block(b, std::true_type{});
         };
         const bool reaches_ring = wave_has_ring || (top_ring && r0 <= TB) || (bottom_ring && r1 + TB > g.th);
         if (reaches_ring) run_strip(std::true_type{});
