@@ -41,7 +41,7 @@ constexpr int MAX_TASK_STREAMS = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 constexpr unsigned TP_LDS_PAD = 53 * 1024;   // 3 of these fit the 160 KiB of LDS of a CU, 4 do not
-constexpr int64_t TP_LDS_PAD_MIN_GRID = 1LL << 30;
+constexpr int64_t LARGE_GRID_BYTES = 1LL << 30;   // grids from this size on get the workgroup-per-CU limits
 constexpr unsigned WHOLE_CU_LDS = 159 * 1024;   // with a kernel's own few bytes: no second workgroup fits in 160 KiB
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -121,7 +121,7 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     int u = (int)p->unroll;
     // (fp64 rows that fill a wavefront's 64 x 16 bytes only: fp32, and tiles narrower than 128 cells, lose with it)
     c.whole_cu = d3 && mode != jk::MODE_RESIDUAL && p->esize == 8 && g.pitch >= jk::WAVE * nv &&
-                 p->lay.grid_bytes >= TP_LDS_PAD_MIN_GRID;
+                 p->lay.grid_bytes >= LARGE_GRID_BYTES;
     if (d3) {
         if (u <= 0) u = c.whole_cu ? 1 : 2;     // planes per trip of the pipeline
         if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
@@ -258,7 +258,7 @@ int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_r
     // (more wavefronts marching through memory at once slow the memory system down: 0.86 -> 0.80 ms per pass
     // on 16384^2), so a third of the CU's LDS, which the kernel never touches, is requested with each
     // workgroup.  Grids of 0.5 GB and less measured faster without the limit; deeper passes fit 2 anyway.
-    a.lds = depth <= 8 && p->lay.grid_bytes >= TP_LDS_PAD_MIN_GRID ? TP_LDS_PAD : 0;
+    a.lds = depth <= 8 && p->lay.grid_bytes >= LARGE_GRID_BYTES ? TP_LDS_PAD : 0;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
     return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp_f64(depth, mode, a) : jk::launch_tp_f32(depth, mode, a),
                           "pipelined blocked-pass kernel launch");

@@ -656,8 +656,8 @@ __device__ __forceinline__ TpPlane tp_locate_plane(const Geo &g, int tz, bool z_
     return P;
 }
 
-template <typename T, int MODE, int TB, int PF, int MINW, int MAXW>
-__global__ __attribute__((amdgpu_flat_work_group_size(WG, WG), amdgpu_waves_per_eu(MINW, MAXW))) void sweep2d_tp_kernel(Geo g, StripParams sp,
+template <typename T, int MODE, int TB, int PF, int MINW>
+__global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams sp,
                                                               const T *__restrict__ src, T *__restrict__ dst,
                                                               double *__restrict__ partial)
 {

@@ -14,10 +14,9 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
     // wavefronts per SIMD the compiler has to fit the kernel's registers into: 3 up to depth 8 (150
     // VGPRs at depth 8, about 18 more with the residual), 2 beyond (215 at depth 12).  Three per SIMD
     // is also what the launch allows to run (see the LDS padding in launch_tp).
-#define JK_MINW(MODE_, TB_) ((TB_) >= 9 ? 2 : 3)
-#define JK_PF(TB_) 4
+#define JK_MINW(TB_) ((TB_) >= 9 ? 2 : 3)
 #define JK_L(MODE_, TB_) \
-    hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, JK_PF(TB_), JK_MINW(MODE_, TB_), JK_MINW(MODE_, TB_)>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial)
+    hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial)
 #define JK_D(MODE_)                         \
     switch (depth) {                        \
     case 3: JK_L(MODE_, 3); break;          \
@@ -38,7 +37,6 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
 #undef JK_D
 #undef JK_L
 #undef JK_MINW
-#undef JK_PF
     return hipGetLastError();
 }
 
