@@ -40,9 +40,7 @@ int fail_hip(hipError_t e, const char *what)
 constexpr int MAX_TASK_STREAMS = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
-constexpr unsigned TP_LDS_PAD = 53 * 1024;   // 3 of these fit the 160 KiB of LDS of a CU, 4 do not
 constexpr int64_t LARGE_GRID_BYTES = 1LL << 30;   // grids from this size on get the workgroup-per-CU limits
-constexpr unsigned WHOLE_CU_LDS = 159 * 1024;   // with a kernel's own few bytes: no second workgroup fits in 160 KiB
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -55,6 +53,7 @@ struct jacobi_plan {
     size_t esize;
     // options
     int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0, tblock = 1, cooperative = 1;
+    int64_t cu_lds = -1;      // LDS bytes of a CU of the device (queried on first use; 0: unknown, no limits)
     // residual scratch (device), sized for the residual launch
     double *partial = nullptr;
     int64_t partial_cap = 0;
@@ -79,6 +78,27 @@ struct SweepConfig {
     int lane_elems;      // elements per lane: 16 bytes' worth, or 2 for narrow fp32 rows in 3-D
     bool whole_cu;       // 3-D update of a large grid: one workgroup per CU
 };
+
+// Dynamic LDS to request with a launch so that at most `per_cu` workgroups share a CU.  Nobody touches
+// those bytes: the hardware offers no other way to cap the workgroups per CU at launch time (the compiler's
+// waves-per-SIMD hints only steer its register allocation).  0 if the device's LDS size is unknown.
+unsigned lds_to_limit_workgroups(jacobi_plan *p, int per_cu)
+{
+    if (p->cu_lds < 0) {
+        int dev = 0, bytes = 0;
+        p->cu_lds = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && bytes >= 65536)
+            p->cu_lds = bytes;                      // 160 KiB on gfx950: a workgroup may use all of a CU's LDS
+        else
+            (void)hipGetLastError();
+    }
+    if (p->cu_lds == 0) return 0;
+    // Measured with 256-thread workgroups that only wait: requests up to 20000 bytes let 8 share a CU, 26000: 6,
+    // 30000-32000: 5, 36000-40000: 4, 44000-53589: 3, 54000-81000: 2, 100000 and more: 1 - slightly less than
+    // 160 KiB is there to hand out.  4 KiB below an n-th of the nominal size lies well inside the range for n.
+    return (unsigned)(p->cu_lds / per_cu - 4096);
+}
 
 SweepConfig make_config(const jacobi_plan *p, int mode)
 {
@@ -157,7 +177,7 @@ int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *p
     // 0.402 ms on 512^3: fewer wavefronts marching through memory at once suit the memory system better, and
     // the pipeline keeps each one's loads in flight), so the update asks for all of the CU's LDS, which it never
     // touches.  Small grids, and the read-only residual pass, measured faster without the limit.
-    a.lds = c.whole_cu ? WHOLE_CU_LDS : 0;
+    a.lds = c.whole_cu ? lds_to_limit_workgroups(p, 1) : 0;
     const bool f64 = p->lay.dtype == JACOBI_F64;
     const int nt = (int)p->nontemporal;
     hipError_t e;
@@ -254,11 +274,12 @@ int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_r
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
     if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
     jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, with_residual ? p->partial : nullptr};
-    // On a grid much larger than the caches a blocked pass streams best with at most 3 workgroups on a CU
-    // (more wavefronts marching through memory at once slow the memory system down: 0.86 -> 0.80 ms per pass
-    // on 16384^2), so a third of the CU's LDS, which the kernel never touches, is requested with each
-    // workgroup.  Grids of 0.5 GB and less measured faster without the limit; deeper passes fit 2 anyway.
-    a.lds = depth <= 8 && p->lay.grid_bytes >= LARGE_GRID_BYTES ? TP_LDS_PAD : 0;
+    // On a grid much larger than the caches a blocked pass streams best with at most 2 workgroups on a CU
+    // (more wavefronts marching through memory at once slow the memory system down: 16384^2 at depth 4 takes
+    // 0.86 ms per pass with the 5 that fit, 0.83 with 3, 0.80 with 2, 0.85 with 1), so half of the CU's LDS,
+    // which the kernel never touches, is requested with each workgroup.  Grids of 0.5 GB and less measured
+    // faster without the limit; passes deeper than 8 fit 2 anyway.
+    a.lds = depth <= 8 && p->lay.grid_bytes >= LARGE_GRID_BYTES ? lds_to_limit_workgroups(p, 2) : 0;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
     return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp_f64(depth, mode, a) : jk::launch_tp_f32(depth, mode, a),
                           "pipelined blocked-pass kernel launch");

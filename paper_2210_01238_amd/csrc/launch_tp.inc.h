@@ -12,11 +12,20 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
     T *dst = (T *)a.dst;
     // Template arguments after the depth: rows loaded ahead (4; 8 measured no faster), and the
     // wavefronts per SIMD the compiler has to fit the kernel's registers into: 3 up to depth 8 (150
-    // VGPRs at depth 8, about 18 more with the residual), 2 beyond (215 at depth 12).  Three per SIMD
-    // is also what the launch allows to run (see the LDS padding in launch_tp).
+    // VGPRs at depth 8, about 18 more with the residual), 2 beyond (215 at depth 12).  On large grids the
+    // launch lets only 2 per SIMD run (see the LDS request in launch_tp).
 #define JK_MINW(TB_) ((TB_) >= 9 ? 2 : 3)
-#define JK_L(MODE_, TB_) \
-    hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial)
+    // a.lds above 64 KiB (it only limits the workgroups per CU) has to be allowed for the kernel first
+#define JK_L(MODE_, TB_)                                                                                           \
+    do {                                                                                                           \
+        if (a.lds > 65536) {                                                                                       \
+            const hipError_t e_ = hipFuncSetAttribute((const void *)sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>, \
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);     \
+            if (e_ != hipSuccess) return e_;                                                                       \
+        }                                                                                                          \
+        hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>), grid, block, a.lds, a.st, a.g,     \
+                           a.sp, src, dst, a.partial);                                                             \
+    } while (0)
 #define JK_D(MODE_)                         \
     switch (depth) {                        \
     case 3: JK_L(MODE_, 3); break;          \
