@@ -47,7 +47,8 @@ def windows_for(w, iters, extra=12):
 
 def full_size_check(H, oracle, name, few, fuse_residual=True, **options):
     import torch
-    w = gen.WORKLOADS[name]
+    w = gen.WORKLOADS[name] if isinstance(name, str) else name
+    name = w.name
     a = gen.generate(w)
     amin, amax = float(a.min()), float(a.max())
     r = H.JacobiRun(w.dims, w.tiles, **options)
@@ -185,3 +186,25 @@ def test_full_size_sweep_in_a_hip_graph(H, name, opts, n):
             assert torch.equal(got, expect), f"{name} {opts}: replay differs from the eager run"
     finally:
         r.close()
+
+
+# Grids of more than 1 GiB - from that size on the launches limit the workgroups per CU - whose extents
+# divide by nothing convenient: ragged strips, row groups, plane blocks and column segments.
+LARGE_RAGGED_2D = gen.WORKLOADS["C3"].scaled((11000, 12200), (5, 4), iters=24, residual_every=8)      # tiles 2200 x 3050
+LARGE_RAGGED_3D = gen.WORKLOADS["C4"].scaled((250, 520, 1060), (2, 4, 5), iters=10, residual_every=5)  # tiles 125 x 130 x 212
+
+
+def test_large_ragged_2d(H, oracle_mod):
+    full_size_check(H, oracle_mod, LARGE_RAGGED_2D, few=2)
+
+
+def test_large_ragged_2d_blocked_passes(H, oracle_mod):
+    full_size_check(H, oracle_mod, LARGE_RAGGED_2D, few=3, tblock=8)
+
+
+def test_large_ragged_3d(H, oracle_mod):
+    full_size_check(H, oracle_mod, LARGE_RAGGED_3D, few=2)
+
+
+def test_large_ragged_3d_blocked_passes(H, oracle_mod):
+    full_size_check(H, oracle_mod, LARGE_RAGGED_3D, few=3, tblock=4)
