@@ -1270,94 +1270,106 @@ __global__ __launch_bounds__(WPG * WAVE, MINW) void sweep3d_tc_kernel(Geo g, Str
         return *(const VU *)((const char *)rowp + off);
     };
 
-    V st[TB][2][NR];                 // per level l-1: the two newest planes; roles swap each step
+    // The pipeline, compiled twice: with the selects that keep Dirichlet cells, and without them for the
+    // wavefronts that can never produce one (no ring lane, no ring row among their rows, no ring plane within
+    // reach of the unit's planes).  Both copies pass the same barriers, so the wavefronts of a workgroup may
+    // run different ones.
+    auto run_unit = [&](auto freeze) {
+        constexpr bool FREEZE = decltype(freeze)::value;
+        V st[TB][2][NR];                 // per level l-1: the two newest planes; roles swap each step
 #pragma unroll
-    for (int l = 0; l < TB; ++l)
+        for (int l = 0; l < TB; ++l)
 #pragma unroll
-        for (int j = 0; j < NR; ++j) st[l][0][j] = st[l][1][j] = V(0);
+            for (int j = 0; j < NR; ++j) st[l][0][j] = st[l][1][j] = V(0);
 
-    const int nsteps = (k1 - k0 + 1) + 2 * TB;              // planes kappa = k0-TB .. k1+TB
-    // The plane entering the pipeline, loaded one step ahead: as soon as a row has been taken, the load
-    // of the same row of the next plane is issued in its place, so only ONE plane of loads is live.
-    V ld[NR];
-    locate_plane(k0 - TB);
+        const int nsteps = (k1 - k0 + 1) + 2 * TB;              // planes kappa = k0-TB .. k1+TB
+        // The plane entering the pipeline, loaded one step ahead: as soon as a row has been taken, the load
+        // of the same row of the next plane is issued in its place, so only ONE plane of loads is live.
+        V ld[NR];
+        locate_plane(k0 - TB);
 #pragma unroll
-    for (int j = 0; j < NR; ++j) ld[j] = load_row(j);
+        for (int j = 0; j < NR; ++j) ld[j] = load_row(j);
 
-    // the first plane has to have arrived before the loop (its waits are placed for the longer-waiting entry)
+        // the first plane has to have arrived before the loop (its waits are placed for the longer-waiting entry)
 #pragma unroll
-    for (int j = 0; j < NR; ++j) asm volatile("" : "+v"(ld[j]));
+        for (int j = 0; j < NR; ++j) asm volatile("" : "+v"(ld[j]));
 
-    const long long out_layer = (long long)tz * g.Ty * tilerow;
-    const unsigned tilerow_bytes = (unsigned)(tilerow * (long long)sizeof(T));      // below 2 GiB
-    const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, WPG - 1);
+        const long long out_layer = (long long)tz * g.Ty * tilerow;
+        const unsigned tilerow_bytes = (unsigned)(tilerow * (long long)sizeof(T));      // below 2 GiB
+        const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, WPG - 1);
 
-    for (int q0 = 0; q0 < nsteps; q0 += 2) {
+        for (int q0 = 0; q0 < nsteps; q0 += 2) {
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {                        // p: slot holding the OLDER plane of every level
-            const int q = q0 + p;
-            if (q >= nsteps) break;
-            const int kappa = k0 - TB + q;                   // plane of u(t) entering the pipeline
-            locate_plane(kappa + 1);
-            bool ring_plane[TB + 1];
+            for (int p = 0; p < 2; ++p) {                        // p: slot holding the OLDER plane of every level
+                const int q = q0 + p;
+                if (q >= nsteps) break;
+                const int kappa = k0 - TB + q;                   // plane of u(t) entering the pipeline
+                locate_plane(kappa + 1);
+                bool ring_plane[TB + 1];
 #pragma unroll
-            for (int l = 1; l <= TB; ++l)
-                ring_plane[l] = (z_lo_ring && kappa - l == 0) || (z_hi_ring && kappa - l == g.td + 1);
-            const int oplane = kappa - TB;
-            const bool store_plane = q >= 2 * TB && oplane <= k1;
-            const long long out_plane = out_layer + (long long)oplane * g.plane;
+                for (int l = 1; l <= TB; ++l)
+                    ring_plane[l] = (z_lo_ring && kappa - l == 0) || (z_hi_ring && kappa - l == g.td + 1);
+                const int oplane = kappa - TB;
+                const bool store_plane = q >= 2 * TB && oplane <= k1;
+                const long long out_plane = out_layer + (long long)oplane * g.plane;
 #pragma unroll
-            for (int j = 0; j < NR; ++j) {
-                V d = ld[j];                                 // newest plane of the level below, row j
-                ld[j] = load_row(j);                         // same row of the next plane, for the next step
+                for (int j = 0; j < NR; ++j) {
+                    V d = ld[j];                                 // newest plane of the level below, row j
+                    ld[j] = load_row(j);                         // same row of the next plane, for the next step
 #pragma unroll
-                for (int l = 1; l <= TB; ++l) {
-                    const V zm = st[l - 1][p][j];
-                    st[l - 1][p][j] = d;                     // the older plane is dead: its slot takes the newest
-                    // the neighbouring wavefronts need this plane of our first and last row in the next step
-                    if (j == 0) xch[1 - p][l - 1][wave][0][lane] = d;
-                    if (j == NR - 1) xch[1 - p][l - 1][wave][1][lane] = d;
-                    const V c = st[l - 1][1 - p][j];
-                    V ym, yp;
-                    if (j == 0) ym = xch[p][l - 1][wave_up][1][lane]; else ym = st[l - 1][1 - p][j - 1];
-                    if (j == NR - 1) yp = xch[p][l - 1][wave_dn][0][lane]; else yp = st[l - 1][1 - p][j + 1];
-                    const T left = from_prev_lane_or_zero(c[NV - 1]);
-                    const T right = from_next_lane_or_zero(c[0]);
-                    // Dirichlet cells keep their value: whole planes and rows (wave-uniform), and the one
-                    // component of a ring lane that is the ring column.  Selects, not branches: branches
-                    // made the compiler copy the whole vector around at every level.
-                    const bool frozen_all = ring_plane[l] || ring_row[j];
-                    V nw;
+                    for (int l = 1; l <= TB; ++l) {
+                        const V zm = st[l - 1][p][j];
+                        st[l - 1][p][j] = d;                     // the older plane is dead: its slot takes the newest
+                        // the neighbouring wavefronts need this plane of our first and last row in the next step
+                        if (j == 0) xch[1 - p][l - 1][wave][0][lane] = d;
+                        if (j == NR - 1) xch[1 - p][l - 1][wave][1][lane] = d;
+                        const V c = st[l - 1][1 - p][j];
+                        V ym, yp;
+                        if (j == 0) ym = xch[p][l - 1][wave_up][1][lane]; else ym = st[l - 1][1 - p][j - 1];
+                        if (j == NR - 1) yp = xch[p][l - 1][wave_dn][0][lane]; else yp = st[l - 1][1 - p][j + 1];
+                        const T left = from_prev_lane_or_zero(c[NV - 1]);
+                        const T right = from_next_lane_or_zero(c[0]);
+                        // Dirichlet cells keep their value: whole planes and rows (wave-uniform), and the one
+                        // component of a ring lane that is the ring column.  Selects, not branches: branches
+                        // made the compiler copy the whole vector around at every level.
+                        const bool frozen_all = FREEZE && (ring_plane[l] || ring_row[j]);
+                        V nw;
 #pragma unroll
-                    for (int e = 0; e < NV; ++e) {
-                        const T xx = (e == 0 ? left : c[e - 1]) + (e == NV - 1 ? right : c[e + 1]);
-                        const T yy = ym[e] + yp[e];
-                        const T zz = zm[e] + d[e];
-                        const T sum = (xx + yy) + zz;
-                        const bool frozen = frozen_all || (e == NV - 1 && kind == 1) || (e == 0 && kind == 2);
-                        nw[e] = frozen ? c[e] : Coef<T>::sixth * sum;
-                        if constexpr (MODE == MODE_BOTH) {
-                            const int plane = kappa - 1;
-                            if (l == 1 && plane >= k0 && plane <= k1 && own_row[j] && owner) {
-                                const T res = sum - Coef<T>::six * c[e];
-                                const double rd = (double)res;
-                                acc += rd * rd;
+                        for (int e = 0; e < NV; ++e) {
+                            const T xx = (e == 0 ? left : c[e - 1]) + (e == NV - 1 ? right : c[e + 1]);
+                            const T yy = ym[e] + yp[e];
+                            const T zz = zm[e] + d[e];
+                            const T sum = (xx + yy) + zz;
+                            const bool frozen = frozen_all || (e == NV - 1 && kind == 1) || (e == 0 && kind == 2);
+                            nw[e] = FREEZE && frozen ? c[e] : Coef<T>::sixth * sum;
+                            if constexpr (MODE == MODE_BOTH) {
+                                const int plane = kappa - 1;
+                                if (l == 1 && plane >= k0 && plane <= k1 && own_row[j] && owner) {
+                                    const T res = sum - Coef<T>::six * c[e];
+                                    const double rd = (double)res;
+                                    acc += rd * rd;
+                                }
                             }
                         }
+                        d = nw;
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    d = nw;
+                    // after TB levels `d` is u(t+TB) of plane kappa-TB: one counted store per row, dropped where
+                    // there is nothing to store (see buffer_store_stream)
+                    buffer_store_stream(d, buffer_of(dst + (out_plane + row_base[j]), tilerow_bytes),
+                                        store_plane && own_row[j] && owner ? lane_bytes : BUF_SKIP);
+                    // keep the rows in program order: hoisting later rows' loads and LDS reads costs registers
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // after TB levels `d` is u(t+TB) of plane kappa-TB: one counted store per row, dropped where
-                // there is nothing to store (see buffer_store_stream)
-                buffer_store_stream(d, buffer_of(dst + (out_plane + row_base[j]), tilerow_bytes),
-                                    store_plane && own_row[j] && owner ? lane_bytes : BUF_SKIP);
-                // keep the rows in program order: hoisting later rows' loads and LDS reads costs registers
-                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();                                 // next step reads what this one published
             }
-            __syncthreads();                                 // next step reads what this one published
         }
-    }
+    };
+    bool reaches_ring = wave_has_ring || (z_lo_ring && k0 <= 2 * TB) || (z_hi_ring && k1 + 2 * TB > g.td);
+#pragma unroll
+    for (int j = 0; j < NR; ++j) reaches_ring = reaches_ring || ring_row[j];
+    if (reaches_ring) run_unit(std::true_type{});
+    else run_unit(std::false_type{});
     if constexpr (MODE == MODE_BOTH) {
         const double tot = wg_sum(acc, red);
         if (threadIdx.x == 0) partial[lwg] = tot;
