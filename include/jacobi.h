@@ -238,7 +238,8 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *   "rows_per_wave"  0 | 1 | 2 | 4  3-D: rows of a plane one wavefront keeps in registers
  *                    (0 = 4 where the tile allows; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
- *                    takes G consecutive ones (0 or 1 = hardware order; default 8)
+ *                    takes G consecutive ones (1 = hardware order; 0 = choose: 8, or 16 for the
+ *                    launches that run one workgroup per CU; default 0)
  *   "tblock"         1..12   temporal blocking depth: jacobi_sweep advances up to this many
  *                    iterations per pass over memory (3-D: at most 4 in fp64, 3 in fp32).  The
  *                    iterations of a call are cut into equally deep passes: in 2-D as many as fit

@@ -52,7 +52,7 @@ struct jacobi_plan {
     Geo geo;
     size_t esize;
     // options
-    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 8, rows_per_wave = 0, tblock = 1, cooperative = 1;
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
     int64_t cu_lds = -1;      // LDS bytes of a CU of the device (queried on first use; 0: unknown, no limits)
     // residual scratch (device), sized for the residual launch
     double *partial = nullptr;
@@ -78,6 +78,13 @@ struct SweepConfig {
     int lane_elems;      // elements per lane: 16 bytes' worth, or 2 for narrow fp32 rows in 3-D
     bool whole_cu;       // 3-D update of a large grid: one workgroup per CU
 };
+
+// Consecutive workgroups one XCD takes (jk::xcd_logical_wg): the option, or 8 - 16 for launches that run one
+// workgroup per CU (measured: 512^3 0.401 -> 0.396 ms, 1024 x 1024 x 768 2.40 -> 2.36; 24 and more: as 8).
+int xcd_chunk_of(const jacobi_plan *p, bool one_workgroup_per_cu = false)
+{
+    return p->xcd_chunk > 0 ? (int)p->xcd_chunk : one_workgroup_per_cu ? 16 : 8;
+}
 
 // Dynamic LDS to request with a launch so that at most `per_cu` workgroups share a CU.  Nobody touches
 // those bytes: the hardware offers no other way to cap the workgroups per CU at launch time (the compiler's
@@ -137,11 +144,12 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     sp.nblk = (int)ceil_div(extent, R);
     sp.nstrips = lanes_of_work * sp.nblk;
     sp.fused = (int)p->fused;
-    sp.xcd_chunk = (int)p->xcd_chunk;
+    sp.xcd_chunk = xcd_chunk_of(p);
     int u = (int)p->unroll;
     // (fp64 rows that fill a wavefront's 64 x 16 bytes only: fp32, and tiles narrower than 128 cells, lose with it)
     c.whole_cu = d3 && mode != jk::MODE_RESIDUAL && p->esize == 8 && g.pitch >= jk::WAVE * nv &&
                  p->lay.grid_bytes >= LARGE_GRID_BYTES;
+    sp.xcd_chunk = xcd_chunk_of(p, c.whole_cu);
     if (d3) {
         if (u <= 0) u = c.whole_cu ? 1 : 2;     // planes per trip of the pipeline
         if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
@@ -216,7 +224,7 @@ StripParams t2_strips(const jacobi_plan *p)
     sp.nblk = (int)ceil_div(g.th, sp.R);
     sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk;
     sp.fused = 0;
-    sp.xcd_chunk = (int)p->xcd_chunk;
+    sp.xcd_chunk = xcd_chunk_of(p);
     return sp;
 }
 
@@ -264,7 +272,7 @@ StripParams tp_strips(const jacobi_plan *p, int depth)
     sp.nblk = (int)ceil_div(g.th, sp.R);
     sp.nstrips = (int64_t)g.Ty * sp.nseg * sp.nblk;
     sp.fused = 0;
-    sp.xcd_chunk = (int)p->xcd_chunk;
+    sp.xcd_chunk = xcd_chunk_of(p);
     return sp;
 }
 
@@ -320,7 +328,7 @@ StripParams tp3d_strips(const jacobi_plan *p, int depth, int *nrg_out)
     sp.nblk = (int)ceil_div(g.td, R);
     sp.nstrips = (int64_t)g.Tz * g.Ty * sp.nblk * nrg * sp.nseg;
     sp.fused = 0;
-    sp.xcd_chunk = (int)p->xcd_chunk;
+    sp.xcd_chunk = xcd_chunk_of(p);
     // depth 3 (2 owned rows of 8 loaded) runs faster when a workgroup's wavefronts are neighbours in y;
     // depth 2 (4 of 8) when they are neighbours in x
     sp.rows_fastest = depth >= 3;
@@ -381,7 +389,7 @@ StripParams tc3d_strips(const jacobi_plan *p, int depth, int *nyg_out)
     sp.nblk = (int)ceil_div(g.td, R);
     sp.nstrips = (int64_t)g.Tz * sp.nblk * sp.nseg * nyg * jk::WAVES_PER_WG;   // partial sums: one per unit
     sp.fused = 0;
-    sp.xcd_chunk = (int)p->xcd_chunk;
+    sp.xcd_chunk = xcd_chunk_of(p);
     if (nyg_out) *nyg_out = nyg;
     return sp;
 }
