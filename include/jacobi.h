@@ -151,7 +151,9 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  * separate exchange; results are identical.
  * After return, the inter-tile halos of the result are unspecified (stale or fresh
  * depending on the option); call halo_exchange if they are needed.
- * Asynchronous on `stream`; allocates nothing; does not synchronise.
+ * Asynchronous on `stream`; allocates no memory (with option "profile" = 1 the first call creates
+ * its HIP events); does not synchronise.  Large-grid launches request LDS they never touch, to limit
+ * the workgroups per CU.
  * Errors: EINVAL (null, in == out or overlapping, misaligned, iters < 0), EHIP.
  */
 int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final);
