@@ -114,3 +114,30 @@ def test_random_task_execution(H, oracle_mod, n, case):
         r.close()
     ref, ref_res = oracle_mod.run(a, iters, iters)
     check(out, res, ref, ref_res)
+
+
+def make_medium_cases(count, seed):
+    """Shapes large enough for several strips, column segments and row groups per tile, with few tiles."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for n in range(count):
+        if n % 2 == 0:
+            dims = (int(rng.integers(300, 2500)), int(rng.integers(300, 4000)))
+        else:
+            dims = (int(rng.integers(20, 140)), int(rng.integers(20, 200)), int(rng.integers(50, 700)))
+        tiles = tuple(int(rng.choice([d for d in divisors(x) if d <= 8])) for x in dims)
+        iters = int(rng.integers(1, 26))
+        every = int(rng.integers(1, iters + 1))
+        opts = dict(fused=int(rng.integers(0, 2)), tblock=int(rng.choice([1, 2, 3, 4, 8, 10, 12])),
+                    rows_per_strip=int(rng.choice([0, 0, 0, 7, 32, 100])), unroll=int(rng.choice([0, 0, 1, 2, 4])),
+                    xcd_chunk=int(rng.choice([0, 0, 1, 16])))
+        if len(dims) == 3:
+            opts["cooperative"] = int(rng.integers(0, 2))
+            opts["rows_per_wave"] = int(rng.choice([0, 0, 1, 2, 4]))
+        cases.append((dims, tiles, iters, every, opts, bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_medium_cases(40, 20221005))))
+def test_random_medium_sizes(H, oracle_mod, n, case):
+    run_random(H, oracle_mod, case, 5000 + n)
