@@ -144,8 +144,8 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     sp.nblk = (int)ceil_div(extent, R);
     sp.nstrips = lanes_of_work * sp.nblk;
     sp.fused = (int)p->fused;
-    sp.xcd_chunk = xcd_chunk_of(p);
     int u = (int)p->unroll;
+    // one workgroup per CU for the 3-D update of a large grid (see launch_sweep)
     // (fp64 rows that fill a wavefront's 64 x 16 bytes only: fp32, and tiles narrower than 128 cells, lose with it)
     c.whole_cu = d3 && mode != jk::MODE_RESIDUAL && p->esize == 8 && g.pitch >= jk::WAVE * nv &&
                  p->lay.grid_bytes >= LARGE_GRID_BYTES;
