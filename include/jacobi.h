@@ -246,8 +246,9 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
  *                    iterations per pass over memory (3-D: at most 4 in fp64, 3 in fp32).  The
  *                    iterations of a call are cut into equally deep passes: in 2-D as many as fit
  *                    at 8 or more iterations each (10 iterations at depth 12 run as one pass, at
- *                    depth 8 as 5 + 5; 50 as 9 + 9 + 8 + 8 + 8 + 8), in 3-D the fewest the depth
- *                    allows (10 as 4 + 3 + 3); see jacobi_pass_schedule.
+ *                    depth 8 as 5 + 5; 50 as 9 + 9 + 8 + 8 + 8 + 8) - at 10 or more each on grids of
+ *                    1 GiB and more (50 as 5 x 10) -, in 3-D the fewest the depth allows (10 as
+ *                    4 + 3 + 3); see jacobi_pass_schedule.
  *                    2-D passes of depth 3..12 need a tile width that is a multiple of 16 bytes
  *                    and a tile height >= depth, depth 2 needs tiles >= 2 x 2; 3-D passes need
  *                    a tile width that is a multiple of 16 bytes and a tile depth >= the pass

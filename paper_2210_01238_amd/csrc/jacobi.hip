@@ -445,11 +445,15 @@ PassChoice choose_pass(const jacobi_plan *p, int left)
         for (int d = maxd; d >= jk::TP_MIN && !deepest; --d)
             if (tp_usable(p, d)) deepest = d;
         if (deepest) {
-            // A pass is bound by memory up to about depth 8 (it costs the same whatever its depth) and by
+            // A pass is bound by memory up to about depth 8 (it costs nearly the same whatever its depth) and by
             // arithmetic beyond (cost proportional to the depth).  Cheapest plan: as many passes as fit at 8 or
             // more iterations each, equally deep, none deeper than `deepest` (10 iterations: one pass of 10, not
-            // 5 + 5; 50: 9 + 9 + 8 + 8 + 8 + 8).
-            const int cap = deepest < 8 ? deepest : 8;
+            // 5 + 5; 50: 9 + 9 + 8 + 8 + 8 + 8).  On grids much larger than the caches passes of 10 run the most
+            // iterations per second (16384^2: 0.094 ms per iteration in passes of 10, 0.106 in passes of 8, 0.110
+            // in passes of 9), so there the passes are made 10 or more deep (50: 5 x 10); smaller grids lose
+            // with that (4096^2: 0.0104 against 0.0092-0.0097).
+            const int target = p->lay.grid_bytes >= LARGE_GRID_BYTES ? 10 : 8;
+            const int cap = deepest < target ? deepest : target;
             int passes = left / cap > 0 ? left / cap : 1;
             if ((left + passes - 1) / passes > deepest) passes = (left + deepest - 1) / deepest;
             const int best_d = (left + passes - 1) / passes;

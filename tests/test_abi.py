@@ -131,6 +131,12 @@ def test_pass_schedule_host_logic(J):
     assert sched((64, 64), (2, 2), 0, 50, tblock=12) == [9, 9, 8, 8, 8, 8]
     assert sched((64, 64), (2, 2), 0, 100, tblock=12) == [9] * 4 + [8] * 8
     assert sched((64, 64), (8, 8), 0, 24, tblock=12) == [8, 8, 8]          # tile height 8 limits the depth
+    # grids of 1 GiB and more: passes of 10 or more
+    assert sched((16384, 16384), (8, 8), 0, 50, tblock=12) == [10] * 5
+    assert sched((16384, 16384), (8, 8), 0, 100, tblock=12) == [10] * 10
+    assert sched((16384, 16384), (8, 8), 0, 24, tblock=12) == [12, 12]
+    assert sched((16384, 16384), (8, 8), 0, 17, tblock=12) == [9, 8]
+    assert sched((16384, 16384), (8, 8), 0, 10, tblock=8) == [5, 5]
     assert sched((64, 64), (16, 16), 0, 10, tblock=12) == [4, 3, 3]        # tile height 4
     assert sched((40, 36), (1, 36), 0, 6, tblock=8) == [1] * 6            # tiles one column wide: single steps
     assert sched((12, 63), (4, 1), 0, 8, tblock=8) == [2, 2, 2, 2]        # odd width, height 3: two-step kernel only
