@@ -286,8 +286,9 @@ int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_r
     // (more wavefronts marching through memory at once slow the memory system down: 16384^2 at depth 4 takes
     // 0.86 ms per pass with the 5 that fit, 0.83 with 3, 0.80 with 2, 0.85 with 1), so half of the CU's LDS,
     // which the kernel never touches, is requested with each workgroup.  Grids of 0.5 GB and less measured
-    // faster without the limit; passes deeper than 8 fit 2 anyway.
-    a.lds = depth <= 8 && p->lay.grid_bytes >= LARGE_GRID_BYTES ? lds_to_limit_workgroups(p, 2) : 0;
+    // faster without the limit.  (Depth 9, at 167 registers, would otherwise run 3 per CU: 0.99 ms per pass
+    // against 0.94 for depth 10.)
+    a.lds = p->lay.grid_bytes >= LARGE_GRID_BYTES ? lds_to_limit_workgroups(p, 2) : 0;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
     return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp_f64(depth, mode, a) : jk::launch_tp_f32(depth, mode, a),
                           "pipelined blocked-pass kernel launch");
