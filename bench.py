@@ -41,7 +41,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md,
 # profiles/sweep3d_update_C4.md and profiles/sweep3d_update_P1.md.  Valid only for the library's default options on that
 # workload; otherwise reported as null.
-MEASURED_TRAFFIC_BYTES = {"C3": 4588523750, "C4": 2411462494, "P1": 14474894756}
+MEASURED_TRAFFIC_BYTES = {"C3": 4588478592, "C4": 2411674806, "P1": 14474894756}
 
 
 def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
