@@ -66,12 +66,18 @@ def test_lattice_harmonic_fixed_point_2d_bit_exact(oracle_mod, kind, dtype):
 
 
 @pytest.mark.parametrize("kind", ["i+j+k", "i2+j2-2k2"])
-def test_lattice_harmonic_fixed_point_3d(oracle_mod, kind):
-    a = gen.lattice_field((11, 14, 19), kind)
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_lattice_harmonic_fixed_point_3d(oracle_mod, kind, dtype):
+    a = gen.lattice_field((11, 14, 19), kind, dtype)
     b = oracle_mod.sweep(a)
-    # exact up to the single multiplication by fl(1/6)
+    assert b.dtype == a.dtype
+    # exact up to the single multiplication by fl(1/6) (all sums are small integers, exact in fp32 too)
     assert np.max(np.abs(b - a)) <= 2 * np.spacing(np.max(np.abs(a)))
     assert oracle_mod.residual(a) == 0.0  # integer arithmetic, exactly zero
+    # the multiplier is fl(1/6) in the WORKING precision: on a cell whose neighbour sum is 6*m the
+    # result is fl(fl(1/6) * 6m), which a correctly rounded product in that precision reproduces
+    s6 = interior(a) * dtype(6)
+    assert np.array_equal(interior(b), (dtype(1) / dtype(6)) * s6)
 
 
 def test_unit_square_harmonic_is_fixed_point_and_attractor(oracle_mod):
@@ -91,8 +97,9 @@ def test_unit_square_harmonic_is_fixed_point_and_attractor(oracle_mod):
 
 # ------------------------------------------- I2: discrete maximum principle -
 @pytest.mark.parametrize("shape", [(20, 33), (9, 10, 12)])
-def test_maximum_principle(oracle_mod, shape):
-    a = random_padded(shape, lo=-3.0, hi=5.0)
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_maximum_principle(oracle_mod, shape, dtype):
+    a = random_padded(shape, dtype, lo=-3.0, hi=5.0)
     lo, hi = a.min(), a.max()
     tol = 0.0 if len(shape) == 2 else 2 * np.spacing(max(abs(lo), abs(hi)))
     u = a
@@ -121,22 +128,30 @@ def test_tiled_rejects_non_divisible(oracle_mod):
 
 
 # ------------------------------------------- I4: eigenmodes -----------------
+# fp32: the closed forms hold to a few fp32 roundings (2^-24 = 6e-8 each) of values of size <= 1
+EIGEN_TOL = {np.float64: (1e-14, 1e-12), np.float32: (5e-7, 2e-6)}
+
+
 @pytest.mark.parametrize("Ny,Nx,p,q", [(15, 22, 1, 1), (15, 22, 3, 5), (8, 8, 8, 1)])
-def test_eigenmode_2d(oracle_mod, Ny, Nx, p, q):
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_eigenmode_2d(oracle_mod, Ny, Nx, p, q, dtype):
     i = np.arange(Ny + 2)[:, None]
     j = np.arange(Nx + 2)[None, :]
     u = np.sin(p * np.pi * i / (Ny + 1)) * np.sin(q * np.pi * j / (Nx + 1))
     u[0] = u[-1] = 0.0
     u[:, 0] = u[:, -1] = 0.0
-    u = np.ascontiguousarray(u)
+    u = np.ascontiguousarray(u.astype(dtype))
     lam = 0.5 * (np.cos(p * np.pi / (Ny + 1)) + np.cos(q * np.pi / (Nx + 1)))
     v = oracle_mod.sweep(u)
-    assert np.max(np.abs(interior(v) - lam * interior(u))) < 1e-14
+    tol_u, tol_r = EIGEN_TOL[dtype]
+    assert v.dtype == u.dtype
+    assert np.max(np.abs(interior(v) - lam * interior(u).astype(np.float64))) < tol_u
     norm = np.sqrt((Ny + 1) * (Nx + 1) / 4.0)
-    assert abs(oracle_mod.residual(u) - 4.0 * (1.0 - lam) * norm) < 1e-12 * norm
+    assert abs(oracle_mod.residual(u) - 4.0 * (1.0 - lam) * norm) < tol_r * norm
 
 
-def test_eigenmode_3d(oracle_mod):
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_eigenmode_3d(oracle_mod, dtype):
     Nz, Ny, Nx, p, q, r = 7, 9, 12, 2, 1, 3
     k = np.arange(Nz + 2)[:, None, None]
     i = np.arange(Ny + 2)[None, :, None]
@@ -149,49 +164,84 @@ def test_eigenmode_3d(oracle_mod):
         u[tuple(sl)] = 0.0
         sl[ax] = -1
         u[tuple(sl)] = 0.0
-    u = np.ascontiguousarray(u)
+    u = np.ascontiguousarray(u.astype(dtype))
     lam = (np.cos(p * np.pi / (Nz + 1)) + np.cos(q * np.pi / (Ny + 1))
            + np.cos(r * np.pi / (Nx + 1))) / 3.0
     v = oracle_mod.sweep(u)
-    assert np.max(np.abs(interior(v) - lam * interior(u))) < 1e-14
+    tol_u, tol_r = EIGEN_TOL[dtype]
+    assert v.dtype == u.dtype
+    assert np.max(np.abs(interior(v) - lam * interior(u).astype(np.float64))) < tol_u
     norm = np.sqrt((Nz + 1) * (Ny + 1) * (Nx + 1) / 8.0)
-    assert abs(oracle_mod.residual(u) - 6.0 * (1.0 - lam) * norm) < 1e-12 * norm
+    assert abs(oracle_mod.residual(u) - 6.0 * (1.0 - lam) * norm) < tol_r * norm
 
 
 # ------------------------------------------- I5: brute force ----------------
+# fp32 runs are compared with the fp64 dense iteration of the same (fp32-representable) data:
+# every value stays within [-1, 1] and a step adds at most ~3 roundings of 6e-8, which the
+# iteration (a contraction) does not amplify
+DENSE_TOL = {np.float64: (1e-14, 1e-12), np.float32: (2e-6, 5e-6)}
+
+
 @pytest.mark.parametrize("Ny,Nx", [(8, 8), (5, 9)])
-def test_dense_matrix_brute_force_2d(oracle_mod, Ny, Nx):
-    a = random_padded((Ny + 2, Nx + 2), lo=-1.0, hi=1.0)
-    M, c = dense_iteration_2d(Ny, Nx, a)
-    v = interior(a).reshape(-1).copy()
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_dense_matrix_brute_force_2d(oracle_mod, Ny, Nx, dtype):
+    a = random_padded((Ny + 2, Nx + 2), dtype, lo=-1.0, hi=1.0)
+    M, c = dense_iteration_2d(Ny, Nx, a.astype(np.float64))
+    v = interior(a).reshape(-1).astype(np.float64)
+    tol_k, tol_inf = DENSE_TOL[dtype]
     for k in range(1, 21):
         v = M @ v + c
         u, _ = oracle_mod.run(a, k)
-        assert np.max(np.abs(interior(u).reshape(-1) - v)) < 1e-14
+        assert u.dtype == a.dtype
+        assert np.max(np.abs(interior(u).reshape(-1) - v)) < tol_k
     # long run converges to the direct solve of (I - M) u = c
     u, _ = oracle_mod.run(a, 900)
     direct = np.linalg.solve(np.eye(Ny * Nx) - M, c)
-    assert np.max(np.abs(interior(u).reshape(-1) - direct)) < 1e-12
+    assert np.max(np.abs(interior(u).reshape(-1) - direct)) < tol_inf
+    # residual against the dense form: sum_nbrs u - 4u = 4 (M u + c - u)
+    u0 = interior(a).reshape(-1).astype(np.float64)
+    dense_res = 4.0 * np.linalg.norm(M @ u0 + c - u0)
+    assert abs(oracle_mod.residual(a) - dense_res) < (1e-12 if dtype is np.float64 else 2e-6) * dense_res
 
 
-def test_dense_matrix_brute_force_3d(oracle_mod):
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_dense_matrix_brute_force_3d(oracle_mod, dtype):
     Nz, Ny, Nx = 3, 4, 5
-    a = random_padded((Nz + 2, Ny + 2, Nx + 2), lo=-1.0, hi=1.0)
-    M, c = dense_iteration_3d(Nz, Ny, Nx, a)
-    v = interior(a).reshape(-1).copy()
+    a = random_padded((Nz + 2, Ny + 2, Nx + 2), dtype, lo=-1.0, hi=1.0)
+    M, c = dense_iteration_3d(Nz, Ny, Nx, a.astype(np.float64))
+    v = interior(a).reshape(-1).astype(np.float64)
+    tol_k, tol_inf = DENSE_TOL[dtype]
     for k in range(1, 13):
         v = M @ v + c
         u, _ = oracle_mod.run(a, k)
-        assert np.max(np.abs(interior(u).reshape(-1) - v)) < 1e-14
+        assert u.dtype == a.dtype
+        assert np.max(np.abs(interior(u).reshape(-1) - v)) < tol_k
+    u, _ = oracle_mod.run(a, 400)
+    direct = np.linalg.solve(np.eye(Nz * Ny * Nx) - M, c)
+    assert np.max(np.abs(interior(u).reshape(-1) - direct)) < tol_inf
     # residual against the dense form: sum_nbrs u - 6u = 6 (M u + c - u)
-    u0 = interior(a).reshape(-1)
-    assert abs(oracle_mod.residual(a) - 6.0 * np.linalg.norm(M @ u0 + c - u0)) < 1e-12
+    u0 = interior(a).reshape(-1).astype(np.float64)
+    dense_res = 6.0 * np.linalg.norm(M @ u0 + c - u0)
+    assert abs(oracle_mod.residual(a) - dense_res) < (1e-12 if dtype is np.float64 else 2e-6) * dense_res
 
 
-def test_residual_against_numpy_slices(oracle_mod):
-    a = random_padded((13, 17))
-    r = a[1:-1, :-2] + a[1:-1, 2:] + a[:-2, 1:-1] + a[2:, 1:-1] - 4.0 * a[1:-1, 1:-1]
-    assert abs(oracle_mod.residual(a) - np.sqrt(np.sum(r * r))) < 1e-13 * np.sqrt(np.sum(r * r))
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_residual_against_numpy_slices(oracle_mod, dtype):
+    # neighbour sums and the subtraction in fp64 on the same data: the fp32 oracle forms its terms in
+    # fp32 (a few roundings of 6e-8 on terms of size ~1), the sum of squares is fp64 / long double
+    tol = 1e-13 if dtype is np.float64 else 1e-6
+    a = random_padded((13, 17), dtype)
+    w = a.astype(np.float64)
+    r = w[1:-1, :-2] + w[1:-1, 2:] + w[:-2, 1:-1] + w[2:, 1:-1] - 4.0 * w[1:-1, 1:-1]
+    ref = np.sqrt(np.sum(r * r))
+    assert ref > 1.0 and abs(oracle_mod.residual(a) - ref) < tol * ref
+    a = random_padded((7, 9, 11), dtype)
+    w = a.astype(np.float64)
+    c = w[1:-1, 1:-1, 1:-1]
+    r = (w[1:-1, 1:-1, :-2] + w[1:-1, 1:-1, 2:] + w[1:-1, :-2, 1:-1] + w[1:-1, 2:, 1:-1]
+         + w[:-2, 1:-1, 1:-1] + w[2:, 1:-1, 1:-1] - 6.0 * c)
+    ref = np.sqrt(np.sum(r * r))
+    assert ref > 1.0 and abs(oracle_mod.residual(a) - ref) < tol * ref
 
 
 # ------------------------------------------- I6: C1 data ---------------------
@@ -211,7 +261,19 @@ def test_c1_light_cone_symmetry_and_first_row(oracle_mod):
 
 # ------------------------------------------- I7: residual --------------------
 @pytest.mark.parametrize("shape", [(16, 16), (6, 7, 8)])
-def test_residual_identity_and_monotone(oracle_mod, shape):
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_residual_identity_and_monotone(oracle_mod, shape, dtype):
+    if dtype is np.float32:
+        # R(u) = 2d * ||sweep(u) - u||, to fp32 rounding of the terms, while R is far above that floor
+        a = random_padded(tuple(n + 2 for n in shape), dtype)
+        u = a
+        for _ in range(6):
+            nxt = oracle_mod.sweep(u)
+            R = oracle_mod.residual(u)
+            diff = 2 * len(shape) * np.linalg.norm((interior(nxt).astype(np.float64) - interior(u)).reshape(-1))
+            assert R > 0.1 and abs(R - diff) <= 1e-5 * R
+            u = nxt
+        return
     d = len(shape)
     a = random_padded(tuple(n + 2 for n in shape))
     u = a
@@ -241,11 +303,12 @@ def test_run_residual_is_of_the_grid_the_iteration_produced(oracle_mod):
 
 # ------------------------------------------- I8: linearity -------------------
 @pytest.mark.parametrize("shape", [(10, 13), (5, 6, 7)])
-def test_scaling_by_two_is_exact(oracle_mod, shape):
-    a = random_padded(tuple(n + 2 for n in shape), lo=-1, hi=1)
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_scaling_by_two_is_exact(oracle_mod, shape, dtype):
+    a = random_padded(tuple(n + 2 for n in shape), dtype, lo=-1, hi=1)
     u, _ = oracle_mod.run(a, 5)
-    v, _ = oracle_mod.run(np.ascontiguousarray(2.0 * a), 5)
-    assert np.array_equal(2.0 * u, v)
+    v, _ = oracle_mod.run(np.ascontiguousarray(dtype(2.0) * a), 5)
+    assert v.dtype == a.dtype and np.array_equal(dtype(2.0) * u, v)
 
 
 # ------------------------------------------- I9: steady state ----------------
@@ -257,12 +320,16 @@ def test_top_edge_problem_centre_is_one_quarter(oracle_mod):
 
 
 # ------------------------------------------- fp32 follows fp64 ---------------
-def test_fp32_tracks_fp64(oracle_mod):
-    a = random_padded((34, 34))
-    u64, _ = oracle_mod.run(a, 50)
-    u32, _ = oracle_mod.run(a.astype(np.float32), 50)
+@pytest.mark.parametrize("shape", [(34, 34), (10, 12, 14)])
+def test_fp32_tracks_fp64(oracle_mod, shape):
+    a = random_padded(shape)
+    u64, r64 = oracle_mod.run(a, 50, 10)
+    u32, r32 = oracle_mod.run(a.astype(np.float32), 50, 10)
     assert u32.dtype == np.float32
     assert np.max(np.abs(u32 - u64)) < 1e-5
+    # residuals well above the fp32 rounding floor (~1e-6 * sqrt(points)) agree to that floor
+    floor = 1e-6 * np.sqrt(np.prod(shape))
+    assert len(r32) == 5 and all(abs(x - y) < floor + 1e-5 * y for x, y in zip(r32, r64))
 
 
 # ------------------------------------------- stored values --------------------
