@@ -21,7 +21,10 @@ of K timed steps, against the 8 TB/s HBM peak.  The K steps are timed twice: onc
 (`value`) and once with the events recorded (`roofline.value_with_events`; the launch durations
 come from this region).
 `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload on this
-machine's host cores (a baseline for context, not a target).
+machine's host cores (a baseline for context, not a target); the residual norms it returns are
+compared with the GPU's over the same steps (`residuals_match_oracle_1e-12`), so every line
+this program prints has checked its own output.  `other_workloads` carries the whole schedules of
+the remaining workload shapes (C1, C2, C4, C5), measured the same way in the same run.
 """
 from __future__ import annotations
 
@@ -42,6 +45,24 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # profiles/sweep3d_update_C4.md and profiles/sweep3d_update_P1.md.  Valid only for the library's default options on that
 # workload; otherwise reported as null.
 MEASURED_TRAFFIC_BYTES = {"C3": 4588478592, "C4": 2411674806, "P1": 14474894756}
+TRAFFIC_SOURCE = {"C3": "profiles/sweep2d_update_C3.md", "C4": "profiles/sweep3d_update_C4.md",
+                  "P1": "profiles/sweep3d_update_P1.md"}
+
+# The paper gives no absolute figure for its Jacobi proxy (Sec. VI-C); what it does state, as context only:
+PAPER_CONTEXT = ("paper Sec. VI-C, Jacobi3D on a 1024x1024x768 domain: up to 40 % (strong scaling) / up to 30 % (weak "
+                 "scaling) shorter run time than OpenMPI+CUDA on up to 16 nodes, each 2x Xeon Gold 6130 + 4x Tesla V100, "
+                 "attributed to overlapping messages, transfers and kernels; no absolute times, rates, precision or "
+                 "iteration counts are given, so there is no baseline figure for this metric")
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
@@ -63,6 +84,98 @@ def algorithmic_bytes_per_update(w, esize: int, fused: bool) -> int:
     return total
 
 
+class Schedule:
+    """The step loop of one workload on one plan: W warm-up steps, then K timed steps from the same field."""
+
+    def __init__(self, harness, torch, w, a, options=(), fuse_residual=True):
+        self.h, self.torch, self.w, self.a = harness, torch, w, a
+        self.every = w.residual_every
+        self.fuse_residual = fuse_residual
+        self.run = harness.JacobiRun(w.dims, w.tiles)
+        for kv in options:
+            k, v = kv.split("=")
+            self.run.set_option(k, int(v))
+        self.fused = bool(harness.B.jacobi_get_option(self.run.plan, "fused"))
+        self.run.load(a)
+        self.res_dev = None
+
+    def steps(self, n: int) -> None:
+        # Step i = `every` iterations, then the residual norm of the field they produced.  The
+        # norm of step i's result is computed inside the first update of step i+1 (same pass over
+        # memory); only the last step needs the stand-alone reduction.  n residuals in total.
+        run, every, res_dev = self.run, self.every, self.res_dev
+        for i in range(n):
+            if i == 0 or not self.fuse_residual:
+                run.sweep(every)
+            else:
+                run.sweep_residual(every, res_dev[i - 1:i])
+            if i == n - 1 or not self.fuse_residual:
+                run.residual_async(res_dev[i:i + 1])
+
+    def timed(self, K: int, W: int, events: bool, reps: int = 1):
+        """W warm-up steps, then `reps` times K timed steps, each time from the initial field (reloaded outside
+        the clock).  With `events` a HIP event pair is recorded around every update launch of the timed steps
+        (on the stream they run on).  Returns (seconds, residuals of the last repetition, summed launch ms, launches)."""
+        import time
+        torch, run, B = self.torch, self.run, self.h.B
+        if self.res_dev is None or self.res_dev.numel() < max(K, W, 1):
+            self.res_dev = torch.zeros(max(K, W, 1), dtype=torch.float64, device="cuda")
+        run.set_option("profile", 1 if events else 0)
+        self.steps(W)                              # also creates the events outside the timed region
+        if events:
+            B.jacobi_profile_read(run.plan)        # drop the warm-up launches from the record
+        total, ms, n = 0.0, 0.0, 0
+        for _ in range(reps):
+            run.load(self.a)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.steps(K)
+            torch.cuda.synchronize()
+            total += time.perf_counter() - t0
+            if events:
+                m, c = B.jacobi_profile_read(run.plan)
+                ms, n = ms + m, n + c
+        run.set_option("profile", 0)
+        return total, self.res_dev[:K].cpu().tolist(), ms, n
+
+    def close(self):
+        self.run.close()
+
+
+def other_workload(harness, torch, gen, name: str) -> dict:
+    """Whole schedule of one of the other workload shapes with the library's defaults: throughput (clean
+    run), and the update kernel's launch duration from HIP events (second run)."""
+    import math
+    w = gen.WORKLOADS[name]
+    a = gen.generate(w)
+    sch = Schedule(harness, torch, w, a)
+    try:
+        K = w.iters // w.residual_every
+        # launch-bound toy shapes: repeat the schedule so that the timed region is tens of milliseconds
+        reps = max(1, min(50, int(2e8 // (w.points * w.iters))))
+        dt, res, _, _ = sch.timed(K, 1, events=False, reps=reps)
+        _, _, ms, n = sch.timed(K, 1, events=True, reps=reps)
+        bytes_per_launch = algorithmic_bytes_per_update(w, 8, sch.fused)
+        avg_ms = ms / max(n, 1)
+        gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if n else 0.0
+        return {
+            "workload": f"{len(w.dims)}-D {'x'.join(map(str, w.dims))} fp64, {'x'.join(map(str, w.tiles))} tiles, "
+                        f"{w.iters} iterations, residual every {w.residual_every}",
+            "value": round(float(w.points) * w.iters * reps / dt / 1e9, 3),
+            "unit": "GLUP/s",
+            "ms_per_step": round(dt / (K * reps) * 1e3, 5),
+            "ms_per_iteration": round(dt / (w.iters * reps) * 1e3, 6),
+            "avg_launch_ms": round(avg_ms, 6),
+            "launches_timed": n,
+            "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "last_residual": res[-1] if res else None,
+            "passes_per_call": len(harness.B.jacobi_pass_schedule(sch.run.plan, w.residual_every)),
+        }
+    finally:
+        sch.close()
+        del a
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +187,8 @@ def main() -> int:
                     help="depth limit of the extra temporal-blocking measurement (3-D passes advance 2 iterations)")
     ap.add_argument("--no-temporal-blocking", action="store_true",
                     help="skip the extra measurement with several iterations per pass")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the compact block with the other workload shapes")
     ap.add_argument("--tasks", default="", help="G,S: also measure the schedule executed as tasks of G tiles over "
                     "S streams (jacobi_sweep_tasks), e.g. 1,16; off by default")
     ap.add_argument("--separate-residual", action="store_true",
@@ -103,50 +218,14 @@ def main() -> int:
     t0 = time.perf_counter()
     a = gen.generate(w)
     t_gen = time.perf_counter() - t0
-    run = harness.JacobiRun(w.dims, w.tiles)
-    for kv in args.option:
-        k, v = kv.split("=")
-        run.set_option(k, int(v))
-    fused = bool(harness.B.jacobi_get_option(run.plan, "fused"))
-    fuse_residual = not args.separate_residual
-    run.load(a)
-    res_dev = torch.zeros(max(K, W, 1), dtype=torch.float64, device="cuda")
-
-    def steps(n: int) -> None:
-        # Step i = `every` iterations, then the residual norm of the field they produced.  The
-        # norm of step i's result is computed inside the first update of step i+1 (same pass over
-        # memory); only the last step needs the stand-alone reduction.  n residuals in total.
-        for i in range(n):
-            if i == 0 or not fuse_residual:
-                run.sweep(every)
-            else:
-                run.sweep_residual(every, res_dev[i - 1:i])
-            if i == n - 1 or not fuse_residual:
-                run.residual_async(res_dev[i:i + 1])
-
-    def timed_steps(events: bool):
-        """W warm-up steps, then K timed steps from the same initial field.  With `events` a HIP event pair
-        is recorded around every update launch of the timed steps (on the stream they run on).
-        Returns (seconds, residuals, summed launch ms, launches)."""
-        run.set_option("profile", 1 if events else 0)
-        steps(W)                                   # also creates the events outside the timed region
-        if events:
-            harness.B.jacobi_profile_read(run.plan)    # drop the warm-up launches from the record
-        run.load(a)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        steps(K)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        ms, n = harness.B.jacobi_profile_read(run.plan) if events else (0.0, 0)
-        run.set_option("profile", 0)
-        return dt, res_dev[:K].cpu().tolist(), ms, n
+    sch = Schedule(harness, torch, w, a, args.option, fuse_residual=not args.separate_residual)
+    run, fused, fuse_residual = sch.run, sch.fused, sch.fuse_residual
 
     # Two timed regions over the same K steps: one clean (`value`), one carrying the event pairs the
     # roofline figure is computed from (its own throughput is reported beside it: the events cost about
     # 1 % on the 0.7 ms launches of the default workload, far more on launch-bound ones).
-    elapsed, residuals, _, _ = timed_steps(events=False)
-    elapsed_ev, _, upd_ms, upd_n = timed_steps(events=True)
+    elapsed, residuals, _, _ = sch.timed(K, W, events=False)
+    elapsed_ev, _, upd_ms, upd_n = sch.timed(K, W, events=True)
     lups = float(w.points) * every * K
     glups = lups / elapsed / 1e9
     esize = 8
@@ -158,8 +237,8 @@ def main() -> int:
     tb = None
     if not args.no_temporal_blocking:
         run.set_option("tblock", args.tblock)
-        tb_elapsed, tb_res, _, _ = timed_steps(events=False)
-        _, _, tb_ms, tb_n = timed_steps(events=True)
+        tb_elapsed, tb_res, _, _ = sch.timed(K, W, events=False)
+        _, _, tb_ms, tb_n = sch.timed(K, W, events=True)
         run.set_option("tblock", 1)
         tb = {
             "tblock": args.tblock,
@@ -179,6 +258,7 @@ def main() -> int:
     tasks = None
     if args.tasks and fused:
         grp, nstr = (int(x) for x in args.tasks.split(","))
+        res_dev = sch.res_dev
 
         def task_steps(n: int) -> None:
             for i in range(n):
@@ -216,7 +296,9 @@ def main() -> int:
         harness.B.jacobi_stream_copy(dst_g.data_ptr(), src_g.data_ptr(), run.nbytes, st)
     torch.cuda.synchronize()
     copy_gbs = 2.0 * run.nbytes * 20 / (time.perf_counter() - t0) / 1e9
+    sch.close()
 
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name) if not args.option else None
     out = {
         "metric": "Jacobi GLUP/s (lattice updates/sec) + % of HBM roofline, 1 MI355X",
         "value": round(glups, 3),
@@ -250,7 +332,9 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if not args.option else None,
+            "traffic": traffic,
+            "traffic_source": (f"{TRAFFIC_SOURCE[w.name]} (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this "
+                               "command, not measured in this run)") if traffic is not None else None,
             "bytes_per_launch": bytes_per_launch,
             "avg_launch_ms": round(avg_ms, 5),
             "launches_timed": upd_n,
@@ -258,6 +342,7 @@ def main() -> int:
             "value_with_events": round(lups / elapsed_ev / 1e9, 3),
             "stream_copy_gbs": round(copy_gbs, 1),
         },
+        "paper_context": PAPER_CONTEXT,
     }
 
     if tb is not None:
@@ -269,21 +354,45 @@ def main() -> int:
         import oracle
         oracle.build()
         n_steps_cpu = min(K, 16) if K > 0 else 1
+        threads = oracle.num_threads()
         t0 = time.perf_counter()
-        oracle.run(a, every * n_steps_cpu, every)
+        _, cpu_res = oracle.run(a, every * n_steps_cpu, every)
         t_cpu = time.perf_counter() - t0
+        # the same loops on ONE thread, over a shorter sample (one step)
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        oracle.run(a, every, every)
+        t_serial = time.perf_counter() - t0
+        oracle.set_threads(threads)
+        rate = float(w.points) * every * n_steps_cpu / t_cpu / 1e9
+        rate_serial = float(w.points) * every / t_serial / 1e9
+        match = len(cpu_res) == n_steps_cpu and all(abs(g - o) <= 1e-12 * abs(o) for g, o in zip(residuals, cpu_res))
         out["cpu_baseline"] = {
-            "value": round(float(w.points) * every * n_steps_cpu / t_cpu / 1e9, 4),
+            "value": round(rate, 4),
             "unit": "GLUP/s",
-            "cores": oracle.num_threads(),
+            "cores": threads,
             "kind": "oracle",
             "sample": f"first {n_steps_cpu} steps ({every * n_steps_cpu} iterations + {n_steps_cpu} residual norms) "
                       f"of the same {w.name} field, full grid; update loops on all threads, residual sums serial; "
                       f"{t_cpu:.1f} s",
+            "implied_host_gbs": round(16.0 * rate, 1),
+            "serial": {"value": round(rate_serial, 4), "unit": "GLUP/s", "cores": 1,
+                       "sample": f"first step ({every} iterations + 1 residual norm) of the same field; {t_serial:.1f} s"},
+            "nproc": os.cpu_count(),
+            "omp_num_threads": os.environ.get("OMP_NUM_THREADS"),
+            "cpu_model": cpu_model(),
+            "residuals_compared": n_steps_cpu,
         }
-    run.close()
+        out["residuals_match_oracle_1e-12"] = bool(match)
+        if not match:
+            print("bench.py: GPU residuals differ from the oracle's: " + repr(list(zip(residuals, cpu_res))), file=sys.stderr)
+    del a
+
+    if not args.no_other_workloads:
+        out["other_workloads"] = {name: other_workload(harness, torch, gen, name)
+                                  for name in ("C1", "C2", "C4", "C5") if name != w.name}
     print(json.dumps(out), flush=True)
-    return 0
+    return 0 if out.get("residuals_match_oracle_1e-12", True) else 1
 
 
 if __name__ == "__main__":

@@ -102,13 +102,33 @@ typedef struct jacobi_layout {
  *   dims   host array[ndim], interior points per dim, slowest->fastest, each > 0.
  *   tiles  host array[ndim], tile counts per dim, each > 0 and dividing dims[d].
  *   dtype  JACOBI_F64 or JACOBI_F32.
- * Touches no device; device scratch for the residual is allocated on first use.
+ * Touches no device (see jacobi_prepare).
  * Errors: EINVAL, ENOTDIV, ENOMEM.
  */
 int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64_t *tiles,
                   int dtype);
 
-/* Frees the plan and any device scratch it owns (synchronises the device if it owns any).
+/*
+ * jacobi_prepare: the plan's one-time device set-up, on the current device: reads the device's
+ * CU count and LDS size and allocates the plan-owned scratch of the residual reduction (one
+ * double per workgroup of the largest launch ANY option setting can ask for, so it never has
+ * to grow: 8 bytes per 4 one-row strips of about 100 cells at most, 5 MiB for 16384^2).
+ * This is the only device allocation the library ever makes for a plan (the paper's runtime
+ * keeps such buffers in a pre-allocated device memory pool for the same reason, Sec. VI-A).
+ * jacobi_scatter, jacobi_sweep, jacobi_sweep_residual, jacobi_sweep_tasks, residual_norm and
+ * residual_norm_host call it themselves if the caller has not; after it has run once, none of
+ * jacobi_sweep, jacobi_sweep_residual, halo_exchange and residual_norm allocates, frees or
+ * synchronises anything, whatever options are changed in between, so they can be recorded
+ * into a HIP graph (the call that runs the set-up cannot: do it before the capture starts).
+ * Idempotent.  Errors: EINVAL (NULL), ENOMEM, EHIP.
+ */
+int jacobi_prepare(jacobi_plan *plan);
+
+/* Bytes of device scratch jacobi_prepare allocates for this plan (host-only: no device call;
+ * independent of the current option values); 0 if plan is NULL. */
+size_t jacobi_scratch_bytes(const jacobi_plan *plan);
+
+/* Frees the plan and the device scratch it owns (synchronises the device first if it owns any).
  * NULL is accepted. */
 int jacobi_destroy(jacobi_plan *plan);
 
@@ -151,9 +171,9 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  * separate exchange; results are identical.
  * After return, the inter-tile halos of the result are unspecified (stale or fresh
  * depending on the option); call halo_exchange if they are needed.
- * Asynchronous on `stream`; allocates no memory (with option "profile" = 1 the first call creates
- * its HIP events); does not synchronise.  Large-grid launches request LDS they never touch, to limit
- * the workgroups per CU.
+ * Asynchronous on `stream`; allocates no memory once the plan is prepared (jacobi_prepare; with
+ * option "profile" = 1 the first call also creates its HIP events); does not synchronise.
+ * Large-grid launches request LDS they never touch, to limit the workgroups per CU.
  * Errors: EINVAL (null, in == out or overlapping, misaligned, iters < 0), EHIP.
  */
 int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream, void **final);
@@ -166,7 +186,7 @@ int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream
  * residual_norm reads the whole grid once more).  A caller that wants the residual after
  * every k-th iteration gets it from the NEXT call's first update.  Same value as
  * residual_norm(in) up to summation order; same fixed-order reduction; uses the plan's
- * device scratch (allocated, with a device synchronisation, on first use).
+ * device scratch (jacobi_prepare).
  * iters >= 1.  Errors: EINVAL, ENOMEM, EHIP.
  */
 int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, void *stream,
@@ -215,9 +235,9 @@ int halo_exchange(jacobi_plan *plan, void *grid, void *stream);
  *     sqrt( sum over all interior points of (sum of face neighbours - 2d*u)^2 )
  * to *result_dev (a DEVICE double).  The sum is accumulated in fp64 in a fixed
  * two-stage order (per-wavefront shuffle tree -> LDS -> per-workgroup partial -> one
- * final workgroup), so it is bit-reproducible from run to run.  Uses plan-owned
- * device scratch, allocated (with a device synchronisation) on the first call.
- * Asynchronous on `stream` otherwise.  Errors: EINVAL, ENOMEM, EHIP.
+ * final workgroup), so it is bit-reproducible from run to run.  Uses the plan-owned
+ * device scratch (jacobi_prepare); two calls on one plan that overlap in time (different
+ * streams) would share it and race.  Asynchronous on `stream`.  Errors: EINVAL, ENOMEM, EHIP.
  */
 int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *stream);
 

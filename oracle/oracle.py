@@ -64,6 +64,12 @@ def num_threads() -> int:
     return os.cpu_count() or 1
 
 
+def set_threads(n: int) -> None:
+    """Number of threads the OpenMP sweep loops use from now on (results do not depend on it)."""
+    load()
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 def _check(a: np.ndarray) -> Tuple[str, Tuple[int, ...]]:
     if a.dtype not in _SUF or not a.flags.c_contiguous or a.ndim not in (2, 3):
         raise ValueError("need a C-contiguous 2-D/3-D float32/float64 padded array")

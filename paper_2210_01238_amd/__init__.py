@@ -10,7 +10,7 @@ library raises ImportError.
 import importlib
 
 _API = (
-    "JacobiError", "JacobiLayout", "jacobi_create", "jacobi_destroy", "jacobi_grid_bytes",
+    "JacobiError", "JacobiLayout", "jacobi_create", "jacobi_prepare", "jacobi_scratch_bytes", "jacobi_destroy", "jacobi_grid_bytes",
     "jacobi_get_layout", "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_sweep_tasks",
     "jacobi_pass_schedule", "halo_exchange",
     "residual_norm", "residual_norm_host", "jacobi_set_option", "jacobi_get_option",

@@ -19,7 +19,7 @@ JACOBI_F64, JACOBI_F32 = 0, 1
 JACOBI_OK, JACOBI_EINVAL, JACOBI_ENOTDIV, JACOBI_ENOMEM, JACOBI_EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = (
-    "jacobi_create", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
+    "jacobi_create", "jacobi_prepare", "jacobi_scratch_bytes", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
     "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_sweep_tasks", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
     "residual_norm_host", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
     "jacobi_last_error", "jacobi_stream_copy",
@@ -52,6 +52,9 @@ def _load() -> ctypes.CDLL:
     P = ctypes.POINTER
     lib.jacobi_create.argtypes = [P(vp), ci, P(i64), P(i64), ci]
     lib.jacobi_destroy.argtypes = [vp]
+    lib.jacobi_prepare.argtypes = [vp]
+    lib.jacobi_scratch_bytes.argtypes = [vp]
+    lib.jacobi_scratch_bytes.restype = ctypes.c_size_t
     lib.jacobi_grid_bytes.argtypes = [vp]
     lib.jacobi_grid_bytes.restype = ctypes.c_size_t
     lib.jacobi_get_layout.argtypes = [vp, P(JacobiLayout)]
@@ -71,7 +74,7 @@ def _load() -> ctypes.CDLL:
     lib.jacobi_last_error.argtypes = []
     lib.jacobi_last_error.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("jacobi_grid_bytes", "jacobi_last_error"):
+        if name not in ("jacobi_grid_bytes", "jacobi_scratch_bytes", "jacobi_last_error"):
             getattr(lib, name).restype = ci
     return lib
 
@@ -98,6 +101,14 @@ def jacobi_create(dims: Sequence[int], tiles: Sequence[int], dtype: int = JACOBI
         raise JacobiError(JACOBI_EINVAL, "dims and tiles differ in length")
     _check(lib.jacobi_create(ctypes.byref(h), n, d, t, int(dtype)))
     return h.value
+
+
+def jacobi_prepare(plan: int) -> None:
+    _check(lib.jacobi_prepare(plan))
+
+
+def jacobi_scratch_bytes(plan: Optional[int]) -> int:
+    return int(lib.jacobi_scratch_bytes(plan))
 
 
 def jacobi_destroy(plan: Optional[int]) -> None:

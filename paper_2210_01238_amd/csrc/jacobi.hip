@@ -53,8 +53,12 @@ struct jacobi_plan {
     size_t esize;
     // options
     int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
-    int64_t cu_lds = -1;      // LDS bytes of a CU of the device (queried on first use; 0: unknown, no limits)
-    // residual scratch (device), sized for the residual launch
+    // device state, set up once by prepare_plan() (jacobi_prepare, or the first call that touches the device)
+    bool prepared = false;
+    int64_t cu_lds = 0;       // LDS bytes of a CU of the device (0: unknown, no workgroup limits)
+    int num_cu = jk::NUM_CU;  // compute units of the device
+    // residual scratch (device): one partial sum per workgroup of the largest launch any option setting can
+    // ask for, plus one slot for the value residual_norm_host copies back.  Never reallocated.
     double *partial = nullptr;
     int64_t partial_cap = 0;
     // profiling events around update launches
@@ -89,17 +93,8 @@ int xcd_chunk_of(const jacobi_plan *p, bool one_workgroup_per_cu = false)
 // Dynamic LDS to request with a launch so that at most `per_cu` workgroups share a CU.  Nobody touches
 // those bytes: the hardware offers no other way to cap the workgroups per CU at launch time (the compiler's
 // waves-per-SIMD hints only steer its register allocation).  0 if the device's LDS size is unknown.
-unsigned lds_to_limit_workgroups(jacobi_plan *p, int per_cu)
+unsigned lds_to_limit_workgroups(const jacobi_plan *p, int per_cu)
 {
-    if (p->cu_lds < 0) {
-        int dev = 0, bytes = 0;
-        p->cu_lds = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && bytes >= 65536)
-            p->cu_lds = bytes;                      // 160 KiB on gfx950: a workgroup may use all of a CU's LDS
-        else
-            (void)hipGetLastError();
-    }
     if (p->cu_lds == 0) return 0;
     // Measured with 256-thread workgroups that only wait: requests up to 20000 bytes let 8 share a CU, 26000: 6,
     // 30000-32000: 5, 36000-40000: 4, 44000-53589: 3, 54000-81000: 2, 100000 and more: 1 - slightly less than
@@ -381,7 +376,7 @@ StripParams tc3d_strips(const jacobi_plan *p, int depth, int *nyg_out)
             const int r = (int)ceil_div(g.td, nblk);
             if ((int)ceil_div(g.td, r) != nblk) continue;
             const int64_t units = (int64_t)g.Tz * nyg * sp.nseg * nblk;
-            const int64_t cost = ceil_div(units, jk::NUM_CU) * (r + 2 * depth);
+            const int64_t cost = ceil_div(units, p->num_cu) * (r + 2 * depth);
             if (best < 0 || cost < best) { best = cost; R = r; }
         }
     }
@@ -512,15 +507,48 @@ int launch_sg_t(jacobi_plan *p, const T *from, T *to, hipStream_t st)
     return JACOBI_OK;
 }
 
-int ensure_partials(jacobi_plan *p, int64_t need)
+// Partial sums (one per workgroup) the largest residual-producing launch can write, over every pass kind and
+// every value the options can take: the finest strips (one row or plane each, the fewest rows per wavefront)
+// give the most workgroups.  The plan's scratch is sized for this once, so no option change ever makes it grow.
+int64_t max_partials(jacobi_plan *p)
 {
-    if (p->partial_cap >= need) return JACOBI_OK;
-    if (p->partial) {
-        HIP_TRY(hipDeviceSynchronize());
-        HIP_TRY(hipFree(p->partial));
-        p->partial = nullptr;
-        p->partial_cap = 0;
+    const int64_t saved_rps = p->rows_per_strip, saved_rpw = p->rows_per_wave;
+    p->rows_per_strip = 1;
+    int64_t most = 0;
+    auto take = [&](int64_t strips) { most = std::max(most, ceil_div(strips, jk::WAVES_PER_WG)); };
+    for (int64_t rpw : {1, 2, 4}) {
+        p->rows_per_wave = rpw;
+        take(make_config(p, jk::MODE_RESIDUAL).sp.nstrips);
+        take(make_config(p, jk::MODE_BOTH).sp.nstrips);
+        if (p->geo.ndim == 3)
+            for (int d = jk::TP3D_MIN; d <= jk::TP3D_MAX; ++d) take(tp3d_strips(p, d, nullptr).nstrips);
     }
+    if (p->geo.ndim == 2) {
+        take(t2_strips(p).nstrips);
+        for (int d = jk::TP_MIN; d <= jk::TP_MAX; ++d) take(tp_strips(p, d).nstrips);
+    } else {
+        for (int d = jk::TC3D_MIN; d <= jk::TC3D_MAX; ++d) take(tc3d_strips(p, d, nullptr).nstrips);
+    }
+    p->rows_per_strip = saved_rps;
+    p->rows_per_wave = saved_rpw;
+    return most;
+}
+
+// One-time device set-up of a plan: reads the device's CU count and LDS size and allocates the residual
+// scratch.  The only place the library allocates device memory; called by jacobi_prepare and, if the caller
+// has not done so, by the first entry point that enqueues work (which therefore cannot be recorded into a
+// HIP graph; every later call can).
+int prepare_plan(jacobi_plan *p)
+{
+    if (p->prepared) return JACOBI_OK;
+    int dev = 0, v = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) p->num_cu = v;
+    else (void)hipGetLastError();
+    // 160 KiB on gfx950: a workgroup may use all of a CU's LDS
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v >= 65536) p->cu_lds = v;
+    else (void)hipGetLastError();
+    const int64_t need = max_partials(p) + 1;      // + the slot residual_norm_host reads back
     hipError_t e = hipMalloc((void **)&p->partial, (size_t)need * sizeof(double));
     if (e == hipErrorOutOfMemory) {
         (void)hipGetLastError();
@@ -528,24 +556,40 @@ int ensure_partials(jacobi_plan *p, int64_t need)
     }
     if (e != hipSuccess) return fail_hip(e, "hipMalloc(residual scratch)");
     p->partial_cap = need;
+    p->prepared = true;
+    return JACOBI_OK;
+}
+
+int check_partials(const jacobi_plan *p, int64_t nwg)
+{
+    // cannot happen (max_partials covers every launch); kept so that a planning mistake is an error, not a fault
+    if (nwg + 1 > p->partial_cap) return fail(JACOBI_EINVAL, "internal: residual scratch smaller than the launch");
+    return JACOBI_OK;
+}
+
+// Exchange + residual pass of `grid`, partial sums into `partial` (at least nwg entries), result to *out.
+int residual_launches(jacobi_plan *p, void *grid, double *partial, double *out, hipStream_t st)
+{
+    const StripParams sp = make_config(p, jk::MODE_RESIDUAL).sp;
+    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    int rc = launch_exchange(p, grid, st);
+    if (rc) return rc;
+    rc = launch_sweep(p, jk::MODE_RESIDUAL, grid, grid, partial, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, partial, (long long)nwg, out);
+    HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
 
 int residual_common(jacobi_plan *p, void *grid, double *result_dev, hipStream_t st)
 {
-    const StripParams sp = make_config(p, jk::MODE_RESIDUAL).sp;
-    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
-    // one extra slot holds the result for the host variant
-    int rc = ensure_partials(p, nwg + 1);
+    int rc = prepare_plan(p);
     if (rc) return rc;
-    rc = launch_exchange(p, grid, st);
+    const int64_t nwg = ceil_div(make_config(p, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
+    rc = check_partials(p, nwg);
     if (rc) return rc;
-    rc = launch_sweep(p, jk::MODE_RESIDUAL, grid, grid, p->partial, st);
-    if (rc) return rc;
-    double *out = result_dev ? result_dev : p->partial + nwg;
-    hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, p->partial, (long long)nwg, out);
-    HIP_TRY(hipGetLastError());
-    return JACOBI_OK;
+    // the last slot of the scratch holds the result for the host variant
+    return residual_launches(p, grid, p->partial, result_dev ? result_dev : p->partial + p->partial_cap - 1, st);
 }
 
 // Grid buffers must be 16-byte aligned (every lane moves 16 bytes at a time).
@@ -660,6 +704,17 @@ int jacobi_destroy(jacobi_plan *plan)
     return rc;
 }
 
+int jacobi_prepare(jacobi_plan *plan)
+{
+    if (!plan) return fail(JACOBI_EINVAL, "plan is NULL");
+    return prepare_plan(plan);
+}
+
+size_t jacobi_scratch_bytes(const jacobi_plan *plan)
+{
+    return plan ? (size_t)(max_partials(const_cast<jacobi_plan *>(plan)) + 1) * sizeof(double) : 0;
+}
+
 size_t jacobi_grid_bytes(const jacobi_plan *plan) { return plan ? (size_t)plan->lay.grid_bytes : 0; }
 
 int jacobi_get_layout(const jacobi_plan *plan, jacobi_layout *layout)
@@ -674,6 +729,7 @@ int jacobi_scatter(jacobi_plan *plan, const void *global_padded_dev, void *grid,
     if (!plan || !global_padded_dev || !grid) return fail(JACOBI_EINVAL, "NULL argument");
     if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
+    if (int rc = prepare_plan(plan)) return rc;
     return plan->lay.dtype == JACOBI_F64
                ? launch_sg_t<double, false>(plan, (const double *)global_padded_dev, (double *)grid, st)
                : launch_sg_t<float, false>(plan, (const float *)global_padded_dev, (float *)grid, st);
@@ -699,6 +755,8 @@ int halo_exchange(jacobi_plan *plan, void *grid, void *stream)
 static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipStream_t st, void **final,
                         double *residual_in_dev)
 {
+    int rc = prepare_plan(plan);
+    if (rc) return rc;
     if (plan->profile && plan->ev.empty()) {
         plan->ev.reserve(2 * MAX_PROFILE_EVENTS);
         for (int i = 0; i < 2 * MAX_PROFILE_EVENTS; ++i) {
@@ -716,11 +774,11 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
                                : first.kernel == 4 ? tc3d_strips(plan, first.depth, nullptr).nstrips
                                                    : tp3d_strips(plan, first.depth, nullptr).nstrips;
         nwg_res = ceil_div(strips, jk::WAVES_PER_WG);
-        int rc = ensure_partials(plan, nwg_res + 1);
+        rc = check_partials(plan, nwg_res);
         if (rc) return rc;
     }
 
-    int rc = launch_boundary_sync(plan, in, out, st);
+    rc = launch_boundary_sync(plan, in, out, st);
     if (rc) return rc;
     void *src = in, *dst = out;
     int k = 0;
@@ -811,6 +869,8 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
     if (iters == 0) return JACOBI_OK;
     const Geo &g = plan->geo;
     hipStream_t st = (hipStream_t)stream;
+    int rc = prepare_plan(plan);
+    if (rc) return rc;
     {
         // Recording this fork / join pattern into a HIP graph crashed inside the runtime when the capture
         // was ended (host-side segmentation fault, cause not found), and the same DAG built node by node
@@ -841,7 +901,7 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
     hipEvent_t *joined = plan->task_events.data() + 2 * (size_t)ntasks + 1;
 
     // on the caller's stream: the Dirichlet ring of `out`, and current halos of `in` for the first iteration
-    int rc = launch_boundary_sync(plan, in, out, st);
+    rc = launch_boundary_sync(plan, in, out, st);
     if (rc) return rc;
     rc = launch_exchange(plan, in, st);
     if (rc) return rc;
@@ -912,9 +972,7 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
     hipStream_t st = (hipStream_t)stream;
     int rc = residual_common(plan, grid, nullptr, st);
     if (rc) return rc;
-    const StripParams sp = make_config(plan, jk::MODE_RESIDUAL).sp;
-    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
-    HIP_TRY(hipMemcpyAsync(result_host, plan->partial + nwg, sizeof(double), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(result_host, plan->partial + plan->partial_cap - 1, sizeof(double), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     return JACOBI_OK;
 }

@@ -158,6 +158,34 @@ def test_pass_schedule_host_logic(J):
     J.jacobi_destroy(p)
 
 
+def test_scratch_size_covers_every_option_setting(J):
+    """jacobi_scratch_bytes (host only): one double per workgroup of the finest-grained residual launch
+    (strips of one row or plane, one row per wavefront), plus the host-result slot; independent of the
+    option values, so jacobi_prepare's allocation never has to grow."""
+    def nbytes(dims, tiles, dtype=0, **opts):
+        p = J.jacobi_create(dims, tiles, dtype)
+        for k, v in opts.items():
+            J.jacobi_set_option(p, k, v)
+        try:
+            return J.jacobi_scratch_bytes(p)
+        finally:
+            J.jacobi_destroy(p)
+    # 16384^2 as 8 x 8 tiles, 4 strips per workgroup.  Single steps: 64 tiles x 16 column segments x 2048
+    # one-row strips; the deepest blocked passes cut a whole row of tiles into segments of 104 owned columns
+    # (52 of 64 lanes): 8 rows of tiles x ceil(16384 / 104) = 158 segments x 2048 strips, which is more
+    assert nbytes((16384, 16384), (8, 8)) == 8 * (8 * 158 * 2048 // 4 + 1)
+    assert nbytes((16384, 16384), (8, 8), tblock=12, rows_per_strip=64) == nbytes((16384, 16384), (8, 8))
+    # 512^3 as 4 x 4 x 4 tiles of 128^3: 64 tiles x 128 rows x 128 planes x 1 segment
+    assert nbytes((512, 512, 512), (4, 4, 4)) == 8 * (64 * 128 * 128 // 4 + 1)
+    assert nbytes((512, 512, 512), (4, 4, 4), rows_per_wave=4, cooperative=0) == nbytes((512, 512, 512), (4, 4, 4))
+    # fp32 rows of 128 cells use 8-byte lanes only with 4 rows per wavefront; finest is still 1 row per strip
+    assert nbytes((512, 512, 512), (4, 4, 4), 1) == 8 * (64 * 128 * 128 // 4 + 1)
+    assert nbytes((1, 1), (1, 1)) == 16
+    assert J.jacobi_scratch_bytes(None) == 0
+    with pytest.raises(J.JacobiError):
+        J.jacobi_prepare(None)
+
+
 def test_task_execution_argument_errors_without_device(J):
     """Arguments of jacobi_sweep_tasks are checked before any device call."""
     p = J.jacobi_create((48, 48), (48, 48))

@@ -6,7 +6,8 @@ iterations in test time, so each workload is checked three ways:
       only on initial values within distance k, so the oracle recomputes windows around
       chosen points (tile junctions, tile edges, domain corners) exactly;
   (3) properties that hold at any size: discrete maximum principle, strictly decreasing
-      residuals, and agreement of the first residual with the oracle's.
+      residuals; and the schedule's first residual (after `residual_every` iterations, which
+      the oracle can still run on the whole grid) against the oracle's.
 The schedule is the benchmark's: blocks of `residual_every` iterations, each residual taken
 from the first update of the next block (jacobi_sweep_residual), the last one stand-alone.
 """
@@ -68,6 +69,8 @@ def full_size_check(H, oracle, name, few, fuse_residual=True, **options):
         res = r.run(w.iters, w.residual_every, fuse_residual=fuse_residual)
         assert len(res) == w.iters // w.residual_every
         assert all(res[i + 1] < res[i] for i in range(len(res) - 1)), f"{name}: residual not decreasing"
+        _, first = oracle.run(a, w.residual_every, w.residual_every)
+        assert abs(res[0] - first[0]) <= 1e-12 * first[0], f"{name}: first residual {res[0]} vs oracle {first[0]}"
         g = r.fetch_device()
         inner = g[tuple(slice(1, -1) for _ in w.dims)]
         tol = 0.0 if w.ndim == 2 else 4 * np.spacing(max(abs(amin), abs(amax)))

@@ -429,6 +429,62 @@ def test_sweep_can_be_captured_in_a_hip_graph(H, oracle_mod):
             r.close()
 
 
+def test_residual_calls_can_be_captured_after_prepare(H, oracle_mod):
+    """After jacobi_prepare nothing in jacobi_sweep_residual / residual_norm allocates or synchronises,
+    whatever options change in between: both are recorded into a HIP graph on a FRESH plan (no eager
+    call has run), replayed between eager calls that toggle `tblock` (other kernels, other numbers
+    of partial sums in the same scratch), and every replay must give the eager bits."""
+    import torch
+    a = random_padded((192, 256), seed=99)
+    n = 6
+    for dims, tiles, a in (((192, 256), (3, 2), a), ((24, 20, 36), (2, 2, 3), random_padded((24, 20, 36), seed=98))):
+        r = H.JacobiRun(dims, tiles)
+        ref = H.JacobiRun(dims, tiles)
+        try:
+            H.B.jacobi_prepare(r.plan)
+            assert H.B.jacobi_scratch_bytes(r.plan) >= 16
+            g_dev = torch.from_numpy(a).cuda()
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            out = torch.zeros(2, dtype=torch.float64, device="cuda")
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s):
+                st = int(torch.cuda.current_stream().cuda_stream)
+                H.B.jacobi_scatter(r.plan, g_dev.data_ptr(), r.a.data_ptr(), st)
+                fin = H.B.jacobi_sweep_residual(r.plan, r.a.data_ptr(), r.b.data_ptr(), n, out[0:1].data_ptr(), st)
+                H.B.residual_norm(r.plan, fin, out[1:2].data_ptr(), st)
+            assert fin == r.a.data_ptr()
+            # eager reference on a second plan
+            ref.load(a)
+            e0 = ref.residual()
+            ref.sweep(n)
+            e1 = ref.residual()
+            want = ref.fetch()
+            exp, exp_res = oracle_mod.run(a, n, n)
+            assert np.array_equal(want, exp) and abs(e1 - exp_res[0]) <= 1e-12 * exp_res[0]
+            for k, tb in enumerate((8, 1, 4)):
+                out.zero_()
+                graph.replay()
+                torch.cuda.synchronize()
+                r.cur = r.a
+                got = r.fetch()
+                vals = out.cpu().tolist()
+                assert np.array_equal(got, want), (dims, k)
+                assert abs(vals[0] - e0) <= 1e-12 * e0 and abs(vals[1] - e1) <= 1e-12 * e1, (dims, k, vals, e0, e1)
+                # eager work on the same plan with another blocking depth between the replays: the fused
+                # residual then comes from a blocked pass with a different number of workgroups
+                r.set_option("tblock", tb)
+                tmp = torch.zeros(1, dtype=torch.float64, device="cuda")
+                r.sweep_residual(5, tmp)
+                torch.cuda.synchronize()
+                assert abs(tmp.item() - e1) <= 1e-12 * e1
+                r.set_option("tblock", 1)
+        finally:
+            r.close()
+            ref.close()
+
+
 TASK_CASES = [
     # (interior dims, tiles, tiles per task, streams, iterations)
     ((96, 200), (3, 2), 1, 4, 7),            # one tile per task
