@@ -245,6 +245,28 @@ int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *strea
 int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void *stream);
 
 /*
+ * residual_norm_noalloc: residual_norm for callers that cannot allocate device memory at all -
+ * code under HIP graph capture that never ran jacobi_prepare, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same kernels, same summation order and therefore the same bits as
+ * residual_norm, but the per-workgroup partial sums go to a fixed array inside the library's
+ * own device image (JACOBI_NOALLOC_MAX_PARTIALS doubles = 1 MiB, resident on every GPU the
+ * library runs on until the process ends) instead of the plan's scratch.  The call allocates
+ * and frees nothing, on the device or through any allocating library routine, needs no
+ * jacobi_prepare, and does not synchronise.  `grid` and `result_dev` are the caller's device
+ * memory as for residual_norm.
+ * Limits and hazards: the residual launch of the plan must have at most
+ * JACOBI_NOALLOC_MAX_PARTIALS workgroups under the current options (16384^2 in 8 x 8 tiles:
+ * 32768; 1024 x 1024 x 768 in 128^3 tiles: 24576), otherwise EINVAL with a message that names
+ * both numbers and nothing is enqueued.  Every call on a GPU - of any plan - uses that GPU's
+ * one array: calls that overlap in time on one GPU (different streams or host threads) race;
+ * calls on one stream are safe.  Nothing in the array has to start at zero (every partial a
+ * call reads it has written itself), so it is never cleared and keeps the last call's values.
+ * Errors: EINVAL (NULL, misaligned, plan too large), EHIP.
+ */
+#define JACOBI_NOALLOC_MAX_PARTIALS 131072
+int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, void *stream);
+
+/*
  * Options (all int64).  Unknown key or out-of-range value -> EINVAL.
  *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches

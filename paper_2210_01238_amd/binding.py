@@ -21,7 +21,7 @@ JACOBI_OK, JACOBI_EINVAL, JACOBI_ENOTDIV, JACOBI_ENOMEM, JACOBI_EHIP = 0, 1, 2, 
 EXPORTS = (
     "jacobi_create", "jacobi_prepare", "jacobi_scratch_bytes", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
     "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_sweep_tasks", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
-    "residual_norm_host", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
+    "residual_norm_host", "residual_norm_noalloc", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
     "jacobi_last_error", "jacobi_stream_copy",
 )
 
@@ -66,6 +66,7 @@ def _load() -> ctypes.CDLL:
     lib.jacobi_pass_schedule.argtypes = [vp, ci, P(ci), ci, P(ci)]
     lib.halo_exchange.argtypes = [vp, vp, vp]
     lib.residual_norm.argtypes = [vp, vp, vp, vp]
+    lib.residual_norm_noalloc.argtypes = [vp, vp, vp, vp]
     lib.residual_norm_host.argtypes = [vp, vp, P(ctypes.c_double), vp]
     lib.jacobi_set_option.argtypes = [vp, ctypes.c_char_p, i64]
     lib.jacobi_get_option.argtypes = [vp, ctypes.c_char_p, P(i64)]
@@ -175,6 +176,14 @@ def halo_exchange(plan: int, grid: int, stream: int = 0) -> None:
 
 def residual_norm(plan: int, grid: int, result_dev: int, stream: int = 0) -> None:
     _check(lib.residual_norm(plan, grid, result_dev, stream))
+
+
+NOALLOC_MAX_PARTIALS = 131072   # JACOBI_NOALLOC_MAX_PARTIALS of include/jacobi.h
+
+
+def residual_norm_noalloc(plan: int, grid: int, result_dev: int, stream: int = 0) -> None:
+    """residual_norm whose scratch is a fixed array inside the library: allocates nothing."""
+    _check(lib.residual_norm_noalloc(plan, grid, result_dev, stream))
 
 
 def residual_norm_host(plan: int, grid: int, stream: int = 0) -> float:

@@ -9,6 +9,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <algorithm>
@@ -963,6 +964,50 @@ int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *strea
     if (!plan || !grid || !result_dev) return fail(JACOBI_EINVAL, "NULL argument");
     if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
     return residual_common(plan, grid, result_dev, (hipStream_t)stream);
+}
+
+// ---- residual_norm_noalloc: the partial sums live in an array of the library's own device image ----
+// Every GPU that loads the library holds its own copy of `scratch` at its own address.  In host code the
+// name is only a handle for hipGetSymbolAddress; the device address it yields (looked up once per device,
+// with that device current) is what the kernels are given.
+static __device__ __align__(256) double scratch[JACOBI_NOALLOC_MAX_PARTIALS];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_lock;
+double *g_scratch_ptr[MAX_DEVICES];     // device address of `scratch` on each device; nullptr: not looked up yet
+
+int static_scratch_of_current_device(double **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(JACOBI_EINVAL, "device ordinal beyond the 64 the library keeps scratch addresses for");
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(JACOBI_EHIP, "hipGetSymbolAddress returned no address for the static scratch");
+        g_scratch_ptr[dev] = (double *)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return JACOBI_OK;
+}
+}  // namespace
+
+int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, void *stream)
+{
+    if (!plan || !grid || !result_dev) return fail(JACOBI_EINVAL, "NULL argument");
+    if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
+    const int64_t nwg = ceil_div(make_config(plan, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
+    if (nwg > JACOBI_NOALLOC_MAX_PARTIALS) {
+        char msg[160];
+        snprintf(msg, sizeof(msg), "residual_norm_noalloc: the plan's residual launch has %lld workgroups, the static "
+                 "scratch holds %d partial sums", (long long)nwg, JACOBI_NOALLOC_MAX_PARTIALS);
+        return fail(JACOBI_EINVAL, msg);
+    }
+    double *partials = nullptr;
+    if (int rc = static_scratch_of_current_device(&partials)) return rc;
+    return residual_launches(plan, grid, partials, result_dev, (hipStream_t)stream);
 }
 
 int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void *stream)
