@@ -164,7 +164,8 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  *            jacobi_pass_schedule), so read *final.
  * First copies the Dirichlet boundary halos in -> out so both buffers carry them, then
  * for each iteration: halo exchange on the source buffer, update into the other buffer.
- * (Option "tblock" > 1 replaces this per-iteration sequence by multi-iteration passes.)
+ * (Option "tblock" > 1 replaces this per-iteration sequence by multi-iteration passes, and small
+ * 2-D grids run all iterations of the call inside one launch: option "resident".)
  * With option "fused" = 1 the update kernel itself writes each tile's fresh edge
  * cells into the neighbours' halos of the destination buffer (pack, transfer and
  * unpack fused into the update's epilogue), and only the first iteration needs a
@@ -303,6 +304,26 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    of rows and hand each other their border rows through LDS (depths 3 and 4,
  *                    and depth 2 where the other kernel cannot run); 0 = every wavefront carries
  *                    its own ghost rows (depths 2 and 3, needs a tile height >= depth) (default 1)
+ *   "resident"       0 | 1   small 2-D grids: run ALL iterations of a jacobi_sweep call inside ONE kernel
+ *                    launch (default 1).  Taken when the grid is 2-D, a row of the domain is at most
+ *                    2 KiB (256 fp64 / 512 fp32 columns), the tile width is a multiple of 16 bytes, and
+ *                    the rows fit one workgroup per CU (about 34 rows each by default: up to ~8000 rows).
+ *                    Such grids are updated in about a microsecond, so the launch-per-iteration sequence
+ *                    is bound by launch latency (3.5 us per iteration); here the grid stays in registers,
+ *                    the wavefronts of a workgroup pass each other their border rows through LDS, and
+ *                    the workgroups meet at a barrier in device memory only every "resident_depth"
+ *                    iterations (each holds that many ghost rows per side, which it recomputes), storing
+ *                    their own rows to the other grid and re-reading only the ghost rows.  These phases
+ *                    swap the two grids like passes do (jacobi_pass_schedule lists them; read *final).
+ *                    The barrier's wait is bounded: if the workgroups cannot all be resident (the device
+ *                    is busy with other work for seconds) the launch still ends and writes NaN.
+ *                    Ignores "tblock"; inter-tile halo cells of the result are left alone.
+ *   "resident_depth" 0 | 1..31  iterations between two barriers of that kernel (0 = choose: 16, evened
+ *                    out over the call)
+ *   "resident_rows"  0 | 1..4   rows each of its wavefronts keeps (0 = choose: 4, or just enough for a
+ *                    grid that fits one workgroup)
+ *   "resident_spin_limit"  0 | n  polls a workgroup waits at that barrier before giving up: n - 1
+ *                    beyond the first (0 = default, about 4 million: seconds)
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
  *                    made by jacobi_sweep (read with jacobi_profile_read)
  * None of the options changes any result bit.

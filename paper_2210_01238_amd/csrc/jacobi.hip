@@ -54,6 +54,7 @@ struct jacobi_plan {
     size_t esize;
     // options
     int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
+    int64_t resident = 1, resident_depth = 0, resident_rows = 0, resident_spin_limit = 0;
     // device state, set up once by prepare_plan() (jacobi_prepare, or the first call that touches the device)
     bool prepared = false;
     int64_t cu_lds = 0;       // LDS bytes of a CU of the device (0: unknown, no workgroup limits)
@@ -62,6 +63,7 @@ struct jacobi_plan {
     // ask for, plus one slot for the value residual_norm_host copies back.  Never reallocated.
     double *partial = nullptr;
     int64_t partial_cap = 0;
+    unsigned *sync_words = nullptr;   // behind the partial sums: arrival counter and failure flag of the resident kernel
     // profiling events around update launches
     std::vector<hipEvent_t> ev;   // pairs: 2*i start, 2*i+1 stop
     int64_t ev_used = 0;
@@ -405,6 +407,73 @@ int launch_tc3d(jacobi_plan *p, int depth, const void *src, void *dst, bool with
                           "3-D cooperative blocked-pass kernel launch");
 }
 
+// ---- all iterations of a call in one launch (resident_kernel.h) -----------------------------------------
+// Which small 2-D plans run that way, and how: column segments and rows per wavefront, rows a workgroup owns
+// (B) and ghost rows per side (d), workgroups, and the phases the iterations are cut into.
+struct ResidentChoice {
+    bool ok = false;
+    int nseg = 0, rw = 0, B = 0, d = 0, nwg = 0, nphase = 0, depth = 0, n_deep = 0;
+};
+
+constexpr int RESIDENT_DEFAULT_DEPTH = 20;
+constexpr unsigned RESIDENT_DEFAULT_SPIN = 1u << 22;    // polls of about a microsecond each: seconds
+
+ResidentChoice resident_choice(const jacobi_plan *p, int iters)
+{
+    ResidentChoice c;
+    const Geo &g = p->geo;
+    const int nv = 16 / (int)p->esize;
+    if (!p->resident || g.ndim != 2 || iters < 1 || g.tw % nv) return c;
+    const int64_t Nx = (int64_t)g.Tx * g.tw, Ny = (int64_t)g.Ty * g.th;
+    const int nseg = (int)ceil_div(Nx, (int64_t)jk::WAVE * nv);
+    if (nseg > jk::RES_MAX_SEG) return c;
+    // rows a wavefront can keep: two register sets of rows x vectors have to fit 128 registers
+    const int max_rw = nseg == 2 ? jk::RES_MAX_RW - 1 : jk::RES_MAX_RW;
+    int rw = (int)p->resident_rows;
+    if (rw > max_rw) rw = max_rw;
+    // one workgroup holds the whole grid and its two ring rows if they fit: no barrier, one phase
+    const int rw_single = (int)ceil_div(Ny + 2, jk::RES_WAVES);
+    if (rw_single <= max_rw && (rw == 0 || rw >= rw_single)) {
+        c.ok = true;
+        c.nseg = nseg; c.rw = rw ? rw : rw_single; c.B = (int)Ny; c.d = 1; c.nwg = 1;
+        c.nphase = 1; c.depth = iters; c.n_deep = 0;
+        return c;
+    }
+    if (rw == 0) rw = max_rw;
+    const int held = jk::RES_WAVES * rw;
+    int d0 = p->resident_depth > 0 ? (int)p->resident_depth : RESIDENT_DEFAULT_DEPTH;
+    if (d0 > (held - 1) / 2) d0 = (held - 1) / 2;        // at least one owned row
+    if (d0 > iters) d0 = iters;                           // no more ghost rows than a phase can use
+    // deep phases leave few owned rows per workgroup; the grid barrier needs every workgroup resident, so
+    // tall grids get shallower phases
+    for (; d0 >= 1; --d0) {
+        c.nphase = (int)ceil_div(iters, d0);
+        c.depth = iters / c.nphase;
+        c.n_deep = iters % c.nphase;
+        c.d = c.depth + (c.n_deep ? 1 : 0);              // the phases are equally deep: ghost rows for the deepest
+        c.B = held - 2 * c.d;
+        const int64_t nwg = ceil_div(Ny, c.B);
+        if (nwg > p->num_cu) continue;
+        c.ok = true;
+        c.nseg = nseg; c.rw = rw; c.nwg = (int)nwg;
+        return c;
+    }
+    return c;
+}
+
+int launch_resident(jacobi_plan *p, const ResidentChoice &c, void *in, void *out, hipStream_t st)
+{
+    jk::ResidentLaunch a;
+    a.nwg = (unsigned)c.nwg;
+    a.st = st;
+    a.g = p->geo;
+    a.rp.B = c.B; a.rp.d = c.d; a.rp.nphase = c.nphase; a.rp.depth = c.depth; a.rp.n_deep = c.n_deep;
+    a.rp.spin_limit = p->resident_spin_limit > 0 ? (unsigned)(p->resident_spin_limit - 1) : RESIDENT_DEFAULT_SPIN;
+    a.rp.sync = p->sync_words;
+    a.in = in; a.out = out;
+    return launch_checked(jk::launch_resident(p->lay.dtype == JACOBI_F64, c.nseg, c.rw, a), "resident kernel launch");
+}
+
 // What the next pass does with `left` iterations to go.  The iterations are spread evenly over
 // few passes of equal depth (10 iterations at depth 8 run as 5 + 5, not 8 + 2: up to depth 8 a
 // pass costs no more for being deeper).  kernel: 0 single step (needs current
@@ -550,13 +619,15 @@ int prepare_plan(jacobi_plan *p)
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v >= 65536) p->cu_lds = v;
     else (void)hipGetLastError();
     const int64_t need = max_partials(p) + 1;      // + the slot residual_norm_host reads back
-    hipError_t e = hipMalloc((void **)&p->partial, (size_t)need * sizeof(double));
+    // behind them: two doubles' worth of words for the resident kernel's grid barrier
+    hipError_t e = hipMalloc((void **)&p->partial, (size_t)(need + 2) * sizeof(double));
     if (e == hipErrorOutOfMemory) {
         (void)hipGetLastError();
         return fail(JACOBI_ENOMEM, "device allocation of residual scratch failed");
     }
     if (e != hipSuccess) return fail_hip(e, "hipMalloc(residual scratch)");
     p->partial_cap = need;
+    p->sync_words = (unsigned *)(p->partial + need);
     p->prepared = true;
     return JACOBI_OK;
 }
@@ -615,6 +686,10 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "rows_per_wave")) return &p->rows_per_wave;
     if (!strcmp(key, "tblock")) return &p->tblock;
     if (!strcmp(key, "cooperative")) return &p->cooperative;
+    if (!strcmp(key, "resident")) return &p->resident;
+    if (!strcmp(key, "resident_depth")) return &p->resident_depth;
+    if (!strcmp(key, "resident_rows")) return &p->resident_rows;
+    if (!strcmp(key, "resident_spin_limit")) return &p->resident_spin_limit;
     return nullptr;
 }
 
@@ -713,7 +788,7 @@ int jacobi_prepare(jacobi_plan *plan)
 
 size_t jacobi_scratch_bytes(const jacobi_plan *plan)
 {
-    return plan ? (size_t)(max_partials(const_cast<jacobi_plan *>(plan)) + 1) * sizeof(double) : 0;
+    return plan ? (size_t)(max_partials(const_cast<jacobi_plan *>(plan)) + 1 + 2) * sizeof(double) : 0;
 }
 
 size_t jacobi_grid_bytes(const jacobi_plan *plan) { return plan ? (size_t)plan->lay.grid_bytes : 0; }
@@ -765,6 +840,30 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
             HIP_TRY(hipEventCreate(&e));
             plan->ev.push_back(e);
         }
+    }
+    const ResidentChoice rc_res = resident_choice(plan, iters);
+    if (rc_res.ok) {
+        // small 2-D grid: every iteration inside one launch; the residual of `in`, if asked for, from the
+        // stand-alone reduction first (it refreshes in's halo cells, which the resident kernel does not read)
+        if (residual_in_dev) {
+            const int64_t nwg = ceil_div(make_config(plan, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
+            rc = check_partials(plan, nwg);
+            if (rc) return rc;
+            rc = residual_launches(plan, in, plan->partial, residual_in_dev, st);
+            if (rc) return rc;
+        }
+        rc = launch_boundary_sync(plan, in, out, st);
+        if (rc) return rc;
+        const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
+        if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
+        rc = launch_resident(plan, rc_res, in, out, st);
+        if (rc) return rc;
+        if (timed) {
+            HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));
+            ++plan->ev_used;
+        }
+        if (final) *final = (rc_res.nphase & 1) ? out : in;
+        return JACOBI_OK;
     }
     const PassChoice first = choose_pass(plan, iters);
     int64_t nwg_res = 0;
@@ -937,6 +1036,14 @@ int jacobi_pass_schedule(const jacobi_plan *plan, int iters, int *depths, int ca
     if (!plan || !npasses || (capacity > 0 && !depths)) return fail(JACOBI_EINVAL, "NULL argument");
     if (iters < 0 || capacity < 0) return fail(JACOBI_EINVAL, "iters and capacity must be >= 0");
     int n = 0;
+    const ResidentChoice rc = resident_choice(plan, iters);
+    if (rc.ok) {
+        // one launch; its phases swap the grids like passes do
+        for (int ph = 0; ph < rc.nphase; ++ph, ++n)
+            if (n < capacity) depths[n] = rc.depth + (ph < rc.n_deep ? 1 : 0);
+        *npasses = n;
+        return JACOBI_OK;
+    }
     for (int k = 0; k < iters;) {
         const PassChoice pc = choose_pass(plan, iters - k);
         if (n < capacity) depths[n] = pc.depth;
@@ -1027,7 +1134,7 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : slot == &plan->resident_depth ? 31 : slot == &plan->resident_rows ? jk::RES_MAX_RW : slot == &plan->resident_spin_limit ? (1LL << 31) : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
     if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");

@@ -47,4 +47,27 @@ constexpr int tc3d_rows_per_wave(int depth) { return depth == 2 ? 8 : depth == 3
 hipError_t launch_tc3d_f64(int depth, int mode, const LaunchArgs &a);
 hipError_t launch_tc3d_f32(int depth, int mode, const LaunchArgs &a);
 
+// All iterations of a call in one launch (small 2-D grids; resident_kernel.h).  nseg 1 or 2 column segments per
+// wavefront, 1..4 rows per wavefront.  With more than one workgroup a one-wavefront kernel that zeroes the
+// barrier words is launched first.
+constexpr int RES_WAVES = 16;                // wavefronts per workgroup (1024 threads: one workgroup per CU)
+constexpr int RES_MAX_SEG = 2;               // column segments a wavefront holds (rows of at most 2 KiB)
+constexpr int RES_MAX_RW = 4;                // rows per wavefront
+struct ResidentParams {
+    int B;                 // rows a workgroup owns
+    int d;                 // ghost rows per side
+    int nphase;            // phases; the first n_deep of them run depth + 1 iterations, the others depth
+    int depth, n_deep;
+    unsigned spin_limit;   // polls a workgroup waits at a grid barrier before it gives up
+    unsigned *sync;        // [0]: arrivals, [1]: failure flag (both zeroed before the launch); unused with one workgroup
+};
+struct ResidentLaunch {
+    unsigned nwg;
+    hipStream_t st;
+    Geo g;
+    ResidentParams rp;
+    void *in, *out;
+};
+hipError_t launch_resident(bool f64, int nseg, int rows_per_wave, const ResidentLaunch &a);
+
 }  // namespace jk

@@ -15,6 +15,10 @@ _TORCH_DT = {np.dtype(np.float64): torch.float64, np.dtype(np.float32): torch.fl
 _J_DT = {np.dtype(np.float64): B.JACOBI_F64, np.dtype(np.float32): B.JACOBI_F32}
 
 
+# Options every JacobiRun starts with (explicit keyword options override them).  Empty: the library's defaults.
+DEFAULT_OPTIONS: dict = {}
+
+
 def _stream() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
@@ -29,7 +33,7 @@ class JacobiRun:
         self.tiles = tuple(int(t) for t in tiles)
         self.np_dtype = np.dtype(dtype)
         self.plan = B.jacobi_create(self.dims, self.tiles, _J_DT[self.np_dtype])
-        for k, v in options.items():
+        for k, v in {**DEFAULT_OPTIONS, **options}.items():
             B.jacobi_set_option(self.plan, k, v)
         self.nbytes = B.jacobi_grid_bytes(self.plan)
         # contents deliberately left uninitialised: padding and stale halos may hold anything

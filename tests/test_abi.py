@@ -111,6 +111,7 @@ def test_pass_schedule_host_logic(J):
     """The pass planner (host only): iterations spread evenly over the fewest passes the depth allows."""
     def sched(dims, tiles, dtype, iters, **opts):
         p = J.jacobi_create(dims, tiles, dtype)
+        opts.setdefault("resident", 0)          # the launch-per-pass planner; the one-launch path is checked below
         for k, v in opts.items():
             J.jacobi_set_option(p, k, v)
         try:
@@ -147,6 +148,28 @@ def test_pass_schedule_host_logic(J):
     assert sched((32, 32, 32), (2, 2, 2), 1, 10, tblock=8, cooperative=0) == [2] * 5
     assert sched((32, 32, 33), (2, 2, 1), 0, 5, tblock=8) == [1] * 5      # odd tile width: single steps
     assert sched((6, 32, 32), (3, 2, 2), 0, 9, tblock=4) == [2, 2, 2, 2, 1]   # tile depth 2 limits the pass depth
+    # small 2-D grids (rows of at most 2 KiB, tile width a multiple of 16 bytes): all iterations in one launch,
+    # cut into equally deep phases of at most 20 (option resident_depth) iterations - fewer if the rows would
+    # then need more workgroups than the device has CUs; a grid whose rows (plus the two ring rows) fit one
+    # workgroup's 16 wavefronts x 3 rows (4 for rows of at most 1 KiB) needs a single phase
+    assert sched((256, 256), (1, 1), 0, 100, resident=1) == [20] * 5
+    assert sched((256, 256), (4, 4), 0, 100, resident=1, tblock=8) == [20] * 5
+    assert sched((256, 256), (1, 1), 0, 100, resident=1, resident_depth=31) == [20] * 5     # 48 rows held: at most 23 deep
+    assert sched((256, 256), (1, 1), 0, 100, resident=1, resident_depth=6) == [6] * 15 + [5] * 2
+    assert sched((256, 256), (1, 1), 0, 10, resident=1) == [10]
+    assert sched((46, 256), (1, 1), 0, 1000, resident=1) == [1000]
+    assert sched((47, 256), (1, 1), 0, 100, resident=1) == [20] * 5
+    assert sched((62, 128), (1, 1), 0, 1000, resident=1) == [1000]
+    assert sched((63, 128), (1, 1), 0, 100, resident=1) == [20] * 5
+    assert sched((46, 256), (1, 1), 0, 100, resident=1, resident_rows=2) == [15, 15] + [14] * 5   # 32 rows held: two workgroups
+    assert sched((4096, 256), (1, 1), 0, 100, resident=1) == [15, 15] + [14] * 5     # 18 owned rows each: 228 workgroups
+    assert sched((8000, 256), (1, 1), 0, 100, resident=1) == [8] * 9 + [7] * 4
+    assert sched((12000, 256), (1, 1), 0, 5, resident=1) == [1] * 5          # more workgroups than CUs at any depth
+    assert sched((256, 258), (1, 1), 0, 5, resident=1) == [1] * 5           # three vectors per lane: not taken
+    assert sched((256, 512), (1, 1), 1, 5, resident=1) == [5]               # fp32: 512 columns are two vectors per lane
+    assert sched((256, 254), (1, 127), 0, 5, resident=1) == [5]             # tiles two columns wide
+    assert sched((64, 63), (1, 1), 0, 5, resident=1) == [1] * 5             # odd tile width
+    assert sched((16, 16, 16), (1, 1, 1), 0, 5, resident=1) == [1] * 5      # 3-D
     p = J.jacobi_create((8, 8), (1, 1))
     raw = J.binding.lib
     n = ctypes.c_int()
@@ -154,13 +177,15 @@ def test_pass_schedule_host_logic(J):
     assert raw.jacobi_pass_schedule(p, -1, None, 0, ctypes.byref(n)) == 1
     assert raw.jacobi_pass_schedule(p, 3, None, 2, ctypes.byref(n)) == 1
     buf = (ctypes.c_int * 2)(7, 7)
+    J.jacobi_set_option(p, "resident", 0)
     assert raw.jacobi_pass_schedule(p, 5, buf, 2, ctypes.byref(n)) == 0 and n.value == 5 and list(buf) == [1, 1]
     J.jacobi_destroy(p)
 
 
 def test_scratch_size_covers_every_option_setting(J):
     """jacobi_scratch_bytes (host only): one double per workgroup of the finest-grained residual launch
-    (strips of one row or plane, one row per wavefront), plus the host-result slot; independent of the
+    (strips of one row or plane, one row per wavefront), plus the host-result slot and 16 bytes of barrier
+    words; independent of the
     option values, so jacobi_prepare's allocation never has to grow."""
     def nbytes(dims, tiles, dtype=0, **opts):
         p = J.jacobi_create(dims, tiles, dtype)
@@ -173,14 +198,14 @@ def test_scratch_size_covers_every_option_setting(J):
     # 16384^2 as 8 x 8 tiles, 4 strips per workgroup.  Single steps: 64 tiles x 16 column segments x 2048
     # one-row strips; the deepest blocked passes cut a whole row of tiles into segments of 104 owned columns
     # (52 of 64 lanes): 8 rows of tiles x ceil(16384 / 104) = 158 segments x 2048 strips, which is more
-    assert nbytes((16384, 16384), (8, 8)) == 8 * (8 * 158 * 2048 // 4 + 1)
+    assert nbytes((16384, 16384), (8, 8)) == 8 * (8 * 158 * 2048 // 4 + 1) + 16
     assert nbytes((16384, 16384), (8, 8), tblock=12, rows_per_strip=64) == nbytes((16384, 16384), (8, 8))
     # 512^3 as 4 x 4 x 4 tiles of 128^3: 64 tiles x 128 rows x 128 planes x 1 segment
-    assert nbytes((512, 512, 512), (4, 4, 4)) == 8 * (64 * 128 * 128 // 4 + 1)
+    assert nbytes((512, 512, 512), (4, 4, 4)) == 8 * (64 * 128 * 128 // 4 + 1) + 16
     assert nbytes((512, 512, 512), (4, 4, 4), rows_per_wave=4, cooperative=0) == nbytes((512, 512, 512), (4, 4, 4))
     # fp32 rows of 128 cells use 8-byte lanes only with 4 rows per wavefront; finest is still 1 row per strip
-    assert nbytes((512, 512, 512), (4, 4, 4), 1) == 8 * (64 * 128 * 128 // 4 + 1)
-    assert nbytes((1, 1), (1, 1)) == 16
+    assert nbytes((512, 512, 512), (4, 4, 4), 1) == 8 * (64 * 128 * 128 // 4 + 1) + 16
+    assert nbytes((1, 1), (1, 1)) == 32
     assert J.jacobi_scratch_bytes(None) == 0
     with pytest.raises(J.JacobiError):
         J.jacobi_prepare(None)

@@ -20,14 +20,6 @@ from parity_util import oracle_window
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def H():
-    import torch
-    assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_2210_01238_amd import harness
-    return harness
-
-
 def windows_for(w, iters, extra=12):
     """Index boxes (padded coordinates) whose exact part covers: the junction of tiles
     nearest the domain centre, the low corner of the domain, and the high corner."""

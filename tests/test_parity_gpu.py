@@ -14,14 +14,6 @@ pytestmark = pytest.mark.gpu
 RES_RTOL = {np.dtype(np.float64): 1e-12, np.dtype(np.float32): 1e-5}
 
 
-@pytest.fixture(scope="module")
-def H():
-    import torch
-    assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_2210_01238_amd import harness
-    return harness
-
-
 def run_case(H, oracle, a, tiles, iters, res_every=0, **opts):
     r = H.JacobiRun([n - 2 for n in a.shape], tiles, a.dtype, **opts)
     try:

@@ -10,14 +10,6 @@ from test_parity_gpu import check, run_case
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def H():
-    import torch
-    assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_2210_01238_amd import harness
-    return harness
-
-
 def divisors(n):
     return [d for d in range(1, n + 1) if n % d == 0]
 

@@ -11,14 +11,6 @@ import pytest
 from parity_util import random_padded
 
 
-@pytest.fixture(scope="module")
-def H():
-    import torch
-    assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_2210_01238_amd import harness
-    return harness
-
-
 def both_norms(H, raw, a, tiles):
     """(residual_norm, residual_norm_noalloc) of the field `a`, through the raw C ABI."""
     import torch
