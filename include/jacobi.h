@@ -295,7 +295,11 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    2-D passes of depth 3..12 need a tile width that is a multiple of 16 bytes
  *                    and a tile height >= depth, depth 2 needs tiles >= 2 x 2; 3-D passes need
  *                    a tile width that is a multiple of 16 bytes and a tile depth >= the pass
- *                    depth; otherwise single steps are used.  Blocked passes read the cells they
+ *                    depth; and in every case a row of tiles (tiles along x times the tile size,
+ *                    jacobi_layout.tiles[2] * tile_stride elements) smaller than 2 GiB, because the
+ *                    lanes of these passes address it with 32-bit byte offsets; otherwise passes of
+ *                    depth 2 (2-D, 64-bit addressing) or single steps are used (jacobi_pass_schedule
+ *                    shows which).  Blocked passes read the cells they
  *                    need beyond a tile straight from the neighbouring tiles, so the exchange is
  *                    part of their loads and they leave the halo cells alone.  Results are
  *                    bit-identical for every depth
@@ -324,9 +328,20 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    grid that fits one workgroup)
  *   "resident_spin_limit"  0 | n  polls a workgroup waits at that barrier before giving up: n - 1
  *                    beyond the first (0 = default, about 4 million: seconds)
+ *   "cu_lds"         0 | 65536..2^20  LDS bytes of a CU that the workgroup limits of large-grid launches are
+ *                    computed from (0 = the device's figure, read by jacobi_prepare; default 0).  Those
+ *                    launches request (cu_lds / n - 4096) bytes of LDS they never touch so that at most
+ *                    n workgroups share a CU (n = 1: 3-D update of fp64 grids of 1 GiB and more; n = 2:
+ *                    2-D blocked passes on such grids).  Before a kernel variant uses the request for the
+ *                    first time the library asks the runtime's occupancy calculator whether it has that
+ *                    effect; if not, the launch runs without a limit (results are the same, it is only
+ *                    a few per cent slower) and the read-only figure "lds_limit_failed" becomes 1.
  *   "profile"        0 | 1   record a HIP event pair around every update-kernel launch
  *                    made by jacobi_sweep (read with jacobi_profile_read)
  * None of the options changes any result bit.
+ * jacobi_get_option also reads these figures (not settable): "lds_limit_failed" (see "cu_lds"),
+ * "lds_request_1" / "lds_request_2" (the LDS bytes requested to keep 1 / 2 workgroups per CU; 0 while
+ * the LDS size is unknown), "num_cu" (compute units; 256 until jacobi_prepare has asked the device).
  */
 int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value);
 int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);

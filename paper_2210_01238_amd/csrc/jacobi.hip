@@ -55,6 +55,8 @@ struct jacobi_plan {
     // options
     int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
     int64_t resident = 1, resident_depth = 0, resident_rows = 0, resident_spin_limit = 0;
+    int64_t cu_lds_option = 0;        // option "cu_lds": LDS bytes per CU to compute the workgroup limits from (0: the device's)
+    int64_t lds_limit_failed = 0;     // read-only: a launch dropped its workgroup limit (the occupancy query did not confirm it)
     // device state, set up once by prepare_plan() (jacobi_prepare, or the first call that touches the device)
     bool prepared = false;
     int64_t cu_lds = 0;       // LDS bytes of a CU of the device (0: unknown, no workgroup limits)
@@ -98,11 +100,13 @@ int xcd_chunk_of(const jacobi_plan *p, bool one_workgroup_per_cu = false)
 // waves-per-SIMD hints only steer its register allocation).  0 if the device's LDS size is unknown.
 unsigned lds_to_limit_workgroups(const jacobi_plan *p, int per_cu)
 {
-    if (p->cu_lds == 0) return 0;
+    const int64_t cu_lds = p->cu_lds_option > 0 ? p->cu_lds_option : p->cu_lds;
+    if (cu_lds < 65536) return 0;
     // Measured with 256-thread workgroups that only wait: requests up to 20000 bytes let 8 share a CU, 26000: 6,
     // 30000-32000: 5, 36000-40000: 4, 44000-53589: 3, 54000-81000: 2, 100000 and more: 1 - slightly less than
     // 160 KiB is there to hand out.  4 KiB below an n-th of the nominal size lies well inside the range for n.
-    return (unsigned)(p->cu_lds / per_cu - 4096);
+    // The launch checks the effect with the runtime's occupancy query before it uses the figure (lds_for_launch).
+    return (unsigned)(cu_lds / per_cu - 4096);
 }
 
 SweepConfig make_config(const jacobi_plan *p, int mode)
@@ -184,6 +188,8 @@ int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *p
     // the pipeline keeps each one's loads in flight), so the update asks for all of the CU's LDS, which it never
     // touches.  Small grids, and the read-only residual pass, measured faster without the limit.
     a.lds = c.whole_cu ? lds_to_limit_workgroups(p, 1) : 0;
+    a.per_cu = 1;
+    a.limit_failed = &p->lds_limit_failed;
     const bool f64 = p->lay.dtype == JACOBI_F64;
     const int nt = (int)p->nontemporal;
     hipError_t e;
@@ -287,6 +293,8 @@ int launch_tp(jacobi_plan *p, int depth, const void *src, void *dst, bool with_r
     // faster without the limit.  (Depth 9, at 167 registers, would otherwise run 3 per CU: 0.99 ms per pass
     // against 0.94 for depth 10.)
     a.lds = p->lay.grid_bytes >= LARGE_GRID_BYTES ? lds_to_limit_workgroups(p, 2) : 0;
+    a.per_cu = 2;
+    a.limit_failed = &p->lds_limit_failed;
     const int mode = with_residual ? jk::MODE_BOTH : jk::MODE_UPDATE;
     return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_tp_f64(depth, mode, a) : jk::launch_tp_f32(depth, mode, a),
                           "pipelined blocked-pass kernel launch");
@@ -690,6 +698,7 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "resident_depth")) return &p->resident_depth;
     if (!strcmp(key, "resident_rows")) return &p->resident_rows;
     if (!strcmp(key, "resident_spin_limit")) return &p->resident_spin_limit;
+    if (!strcmp(key, "cu_lds")) return &p->cu_lds_option;
     return nullptr;
 }
 
@@ -1134,7 +1143,7 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : slot == &plan->resident_depth ? 31 : slot == &plan->resident_rows ? jk::RES_MAX_RW : slot == &plan->resident_spin_limit ? (1LL << 31) : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : slot == &plan->resident_depth ? 31 : slot == &plan->resident_rows ? jk::RES_MAX_RW : slot == &plan->resident_spin_limit ? (1LL << 31) : slot == &plan->cu_lds_option ? (1LL << 20) : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
     if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
@@ -1149,6 +1158,11 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
 int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value)
 {
     if (!plan || !key || !value) return fail(JACOBI_EINVAL, "NULL argument");
+    // read-only figures
+    if (!strcmp(key, "lds_limit_failed")) { *value = plan->lds_limit_failed; return JACOBI_OK; }
+    if (!strcmp(key, "lds_request_1")) { *value = lds_to_limit_workgroups(plan, 1); return JACOBI_OK; }
+    if (!strcmp(key, "lds_request_2")) { *value = lds_to_limit_workgroups(plan, 2); return JACOBI_OK; }
+    if (!strcmp(key, "num_cu")) { *value = plan->num_cu; return JACOBI_OK; }
     int64_t *slot = option_slot(const_cast<jacobi_plan *>(plan), key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
     *value = *slot;

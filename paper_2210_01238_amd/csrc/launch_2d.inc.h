@@ -11,7 +11,7 @@ static hipError_t sweep2d_dispatch(int mode, int unroll, int nt, const LaunchArg
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
 #define JK_L(MODE_, U_, NT_) \
-    hipLaunchKernelGGL((sweep2d_kernel<T, MODE_, U_, NT_>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial)
+    hipLaunchKernelGGL((sweep2d_kernel<T, MODE_, U_, NT_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
 #define JK_NT(MODE_, U_)                      \
     do {                                      \
         if (nt & 2) JK_L(MODE_, U_, 2);       \

@@ -11,8 +11,14 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
     const dim3 grid(a.nwg), block(WG);
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
-#define JK_K(MODE_, RW_, U_, NT_, NVEC_) \
-    hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial)
+#define JK_K(MODE_, RW_, U_, NT_, NVEC_)                                                                            \
+    do {                                                                                                            \
+        unsigned lds_ = 0;                                                                                          \
+        const hipError_t e_ = lds_for_launch<sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>>(a, WG, &lds_);          \
+        if (e_ != hipSuccess) return e_;                                                                            \
+        hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>), grid, block, lds_, a.st, a.g, a.sp, src, \
+                           dst, a.partial);                                                                         \
+    } while (0)
     // a.aux = 1: fp32 rows of at most 128 elements, 2 elements per lane (4 rows per wavefront only)
 #define JK_L(MODE_, RW_, U_, NT_)                                                                                   \
     do {                                                                                                            \

@@ -10,9 +10,9 @@ static hipError_t t2_dispatch(int mode, const LaunchArgs &a)
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
     if (mode == MODE_UPDATE)
-        hipLaunchKernelGGL((sweep2d_t2_kernel<T, MODE_UPDATE, T2_ROWS, 2>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial);
+        hipLaunchKernelGGL((sweep2d_t2_kernel<T, MODE_UPDATE, T2_ROWS, 2>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial);
     else if (mode == MODE_BOTH)
-        hipLaunchKernelGGL((sweep2d_t2_kernel<T, MODE_BOTH, T2_ROWS, 2>), grid, block, a.lds, a.st, a.g, a.sp, src, dst, a.partial);
+        hipLaunchKernelGGL((sweep2d_t2_kernel<T, MODE_BOTH, T2_ROWS, 2>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

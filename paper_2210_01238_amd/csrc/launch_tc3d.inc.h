@@ -13,7 +13,7 @@ static hipError_t tc3d_dispatch(int depth, int mode, const LaunchArgs &a)
     // template arguments after the mode: depth, rows per wavefront (tc3d_rows_per_wave), wavefronts per
     // workgroup, and the occupancy the compiler must fit (wavefronts per SIMD)
 #define JK_L(MODE_, TB_) \
-    hipLaunchKernelGGL((sweep3d_tc_kernel<T, MODE_, TB_, tc3d_rows_per_wave(TB_), TC3D_WAVES, 2>), grid, block, a.lds, a.st, a.g, a.sp, a.aux, src, dst, a.partial)
+    hipLaunchKernelGGL((sweep3d_tc_kernel<T, MODE_, TB_, tc3d_rows_per_wave(TB_), TC3D_WAVES, 2>), grid, block, 0, a.st, a.g, a.sp, a.aux, src, dst, a.partial)
 #define JK_V(MODE_)                              \
     do {                                         \
         if (depth == 2) JK_L(MODE_, 2);          \

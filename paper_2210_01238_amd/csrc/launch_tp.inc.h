@@ -15,15 +15,13 @@ static hipError_t tp_dispatch(int depth, int mode, const LaunchArgs &a)
     // VGPRs at depth 8, about 18 more with the residual), 2 beyond (215 at depth 12).  On large grids the
     // launch lets only 2 per SIMD run (see the LDS request in launch_tp).
 #define JK_MINW(TB_) ((TB_) >= 9 ? 2 : 3)
-    // a.lds above 64 KiB (it only limits the workgroups per CU) has to be allowed for the kernel first
+    // a.lds (it only limits the workgroups per CU) is checked, and allowed for the kernel if above 64 KiB, by lds_for_launch
 #define JK_L(MODE_, TB_)                                                                                           \
     do {                                                                                                           \
-        if (a.lds > 65536) {                                                                                       \
-            const hipError_t e_ = hipFuncSetAttribute((const void *)sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>, \
-                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);     \
-            if (e_ != hipSuccess) return e_;                                                                       \
-        }                                                                                                          \
-        hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>), grid, block, a.lds, a.st, a.g,     \
+        unsigned lds_ = 0;                                                                                         \
+        const hipError_t e_ = lds_for_launch<sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>>(a, WG, &lds_);     \
+        if (e_ != hipSuccess) return e_;                                                                           \
+        hipLaunchKernelGGL((sweep2d_tp_kernel<T, MODE_, TB_, 4, JK_MINW(TB_)>), grid, block, lds_, a.st, a.g,      \
                            a.sp, src, dst, a.partial);                                                             \
     } while (0)
 #define JK_D(MODE_)                         \

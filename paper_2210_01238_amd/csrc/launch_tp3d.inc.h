@@ -13,7 +13,7 @@ static hipError_t tp3d_dispatch(int depth, int rows_per_wave, int mode, const La
     // template arguments after the mode: depth, rows per wavefront, planes loaded ahead, and the occupancy
     // the compiler must fit (wavefronts per SIMD; chosen so that nothing spills)
 #define JK_L(MODE_, TB_, RW_, PF_, MINW_) \
-    hipLaunchKernelGGL((sweep3d_tp_kernel<T, MODE_, TB_, RW_, PF_, MINW_>), grid, block, a.lds, a.st, a.g, a.sp, a.aux, src, dst, a.partial)
+    hipLaunchKernelGGL((sweep3d_tp_kernel<T, MODE_, TB_, RW_, PF_, MINW_>), grid, block, 0, a.st, a.g, a.sp, a.aux, src, dst, a.partial)
 #define JK_V(MODE_)                                                        \
     do {                                                                   \
         if (depth == 2 && rows_per_wave == 2) JK_L(MODE_, 2, 2, 1, 3);     \

@@ -5,6 +5,7 @@
 // variant is not compiled).
 #pragma once
 #include "jacobi_kernels.h"
+#include <mutex>
 
 namespace jk {
 
@@ -17,8 +18,53 @@ struct LaunchArgs {
     void *dst;
     double *partial;     // per-workgroup partial sums (residual modes), else unused
     int aux = 0;         // kernel-specific extra (3-D blocked pass: row groups per tile)
-    unsigned lds = 0;    // dynamic LDS bytes nobody uses: they only limit how many workgroups share a CU
+    // Workgroup limit: `lds` bytes of dynamic LDS that nobody touches are requested with the launch so that at
+    // most `per_cu` workgroups share a CU (0: no limit).  The request only goes out if the occupancy query
+    // confirms that it has this effect for the kernel at hand (lds_for_launch); if not, the launch runs
+    // without a limit and *limit_failed is set.
+    unsigned lds = 0;
+    int per_cu = 0;
+    int64_t *limit_failed = nullptr;
 };
+
+// Dynamic LDS to pass to the launch of KERNEL (a __global__ function; the template argument makes the cache
+// below one per compiled variant): a.lds if the runtime confirms that a workgroup of `block_threads` threads
+// asking for it leaves room for at most a.per_cu workgroups on a CU, else 0.  Requests above 64 KiB are
+// allowed for the kernel first (once per kernel and device).  Checked once per kernel, device and size.
+template <auto KERNEL>
+inline hipError_t lds_for_launch(const LaunchArgs &a, int block_threads, unsigned *lds)
+{
+    struct Cache { unsigned allowed = 65536, checked = 0; bool ok = false; };
+    constexpr int MAX_DEV = 64;
+    static Cache cache[MAX_DEV];
+    static std::mutex lock;
+    *lds = 0;
+    if (a.lds == 0 || a.per_cu <= 0) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    bool ok = false;
+    if (dev >= 0 && dev < MAX_DEV) {
+        std::lock_guard<std::mutex> hold(lock);
+        Cache &c = cache[dev];
+        if (c.checked != a.lds) {
+            if (a.lds > c.allowed) {
+                e = hipFuncSetAttribute((const void *)KERNEL, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+                if (e != hipSuccess) return e;
+                c.allowed = a.lds;
+            }
+            int nb = 0;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, KERNEL, block_threads, a.lds);
+            if (e != hipSuccess) (void)hipGetLastError();
+            c.ok = e == hipSuccess && nb >= 1 && nb <= a.per_cu;
+            c.checked = a.lds;
+        }
+        ok = c.ok;
+    }
+    if (ok) *lds = a.lds;
+    else if (a.limit_failed) *a.limit_failed = 1;
+    return hipSuccess;
+}
 
 // single-step update / residual (mode: Mode; unroll 1,2,4,8,16; nt: 0 or 2)
 hipError_t launch_sweep2d_f64(int mode, int unroll, int nt, const LaunchArgs &a);

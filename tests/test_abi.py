@@ -211,6 +211,31 @@ def test_scratch_size_covers_every_option_setting(J):
         J.jacobi_prepare(None)
 
 
+def test_workgroup_limit_request_arithmetic(J):
+    """The LDS request that caps the workgroups per CU (host arithmetic; the launch confirms its effect with the
+    occupancy query).  How many 256-thread workgroups share a 160 KiB CU for a given request was measured
+    (and is what the occupancy calculator reports): up to 20000 bytes 8, 26000 6, 32000 5, 40000 4,
+    49152-53589 3, 65536-81000 2, 100000 and more 1.  The requests must lie well inside the range for n."""
+    p = J.jacobi_create((16384, 16384), (8, 8))
+    try:
+        assert J.jacobi_get_option(p, "lds_request_1") == 0 and J.jacobi_get_option(p, "lds_request_2") == 0   # size unknown
+        assert J.jacobi_get_option(p, "num_cu") == 256 and J.jacobi_get_option(p, "lds_limit_failed") == 0
+        J.jacobi_set_option(p, "cu_lds", 163840)
+        one, two = J.jacobi_get_option(p, "lds_request_1"), J.jacobi_get_option(p, "lds_request_2")
+        assert one == 163840 - 4096 and 100000 <= one <= 163840
+        assert two == 81920 - 4096 and 65536 <= two <= 81000
+        J.jacobi_set_option(p, "cu_lds", 65536)            # a 64 KiB CU: one workgroup takes (nearly) all of it
+        assert J.jacobi_get_option(p, "lds_request_1") == 65536 - 4096
+        for bad in (lambda: J.jacobi_set_option(p, "lds_limit_failed", 0), lambda: J.jacobi_set_option(p, "num_cu", 8),
+                    lambda: J.jacobi_set_option(p, "cu_lds", -1), lambda: J.jacobi_set_option(p, "cu_lds", 1 << 21)):
+            with pytest.raises(J.JacobiError):
+                bad()
+        J.jacobi_set_option(p, "cu_lds", 1000)             # below 64 KiB: no limits
+        assert J.jacobi_get_option(p, "lds_request_1") == 0
+    finally:
+        J.jacobi_destroy(p)
+
+
 def test_task_execution_argument_errors_without_device(J):
     """Arguments of jacobi_sweep_tasks are checked before any device call."""
     p = J.jacobi_create((48, 48), (48, 48))

@@ -73,6 +73,8 @@ def full_size_check(H, oracle, name, few, fuse_residual=True, **options):
             got = g[sl].cpu().numpy()
             assert got.size > 0
             assert np.array_equal(got, u[valid]), f"{name}: window {lo}..{hi} differs"
+        # large grids cap the workgroups per CU through an LDS request: the occupancy query must have confirmed it
+        assert H.B.jacobi_get_option(r.plan, "lds_limit_failed") == 0 and H.B.jacobi_get_option(r.plan, "num_cu") > 0
     finally:
         r.close()
 
@@ -203,3 +205,47 @@ def test_large_ragged_3d(H, oracle_mod):
 
 def test_large_ragged_3d_blocked_passes(H, oracle_mod):
     full_size_check(H, oracle_mod, LARGE_RAGGED_3D, few=3, tblock=4)
+
+
+# ---- 32-bit limits: per-lane byte offsets inside a row of tiles are 32-bit in the blocked-pass kernels ----------
+def whole_grid_after(H, oracle, w, few, **options):
+    """Whole grid, bit for bit, after `few` iterations; returns the pass schedule that ran."""
+    a = gen.generate(w)
+    ref, _ = oracle.run(a, few)
+    r = H.JacobiRun(w.dims, w.tiles, **options)
+    try:
+        sched = H.B.jacobi_pass_schedule(r.plan, few)
+        r.load(a)
+        del a
+        r.sweep(few)
+        got = r.fetch()
+        assert np.array_equal(got, ref), f"{w.dims} {options}: grid differs after {few} iterations"
+        res, ref_res = r.residual(), oracle.residual(ref)
+        assert abs(res - ref_res) <= 1e-12 * ref_res
+        return sched
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("options,few", [({}, 2), (dict(tblock=8), 6)])
+def test_2d_grid_above_4_GiB(H, oracle_mod, options, few):
+    """24576^2 fp64 = 4.8 GB per grid: every element offset beyond 2^32 bytes is exercised (single steps and
+    blocked passes; a row of tiles is 1.2 GB, so the blocked kernels can address it)."""
+    w = gen.WORKLOADS["C3"].scaled((24576, 24576), (4, 4), iters=few, residual_every=few)
+    sched = whole_grid_after(H, oracle_mod, w, few, **options)
+    assert sched == ([few] if options else [1] * few)
+
+
+def test_row_of_tiles_of_2_GiB_falls_back_to_the_two_step_kernel(H, oracle_mod):
+    """8192 x 65536 in 2 x 2 tiles: a row of tiles is 2.15 GB, beyond the 32-bit per-lane offsets of the pipelined
+    blocked passes, so with tblock = 8 the planner must fall back to the two-step kernel (64-bit addressing) and
+    single steps (the schedule says so), and the result must still be exact."""
+    w = gen.WORKLOADS["C3"].scaled((8192, 65536), (2, 2), iters=5, residual_every=5)
+    sched = whole_grid_after(H, oracle_mod, w, 5, tblock=8)
+    assert sched == [2, 2, 1]
+    # the same domain cut into lower tiles fits again: one pass of 5
+    r = H.JacobiRun((8192, 65536), (4, 2), tblock=8)
+    try:
+        assert H.B.jacobi_pass_schedule(r.plan, 5) == [5]
+    finally:
+        r.close()
