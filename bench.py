@@ -100,16 +100,20 @@ class Schedule:
         self.res_dev = None
 
     def steps(self, n: int) -> None:
-        # Step i = `every` iterations, then the residual norm of the field they produced.  The
-        # norm of step i's result is computed inside the first update of step i+1 (same pass over
-        # memory); only the last step needs the stand-alone reduction.  n residuals in total.
+        # Step i = `every` iterations, then the residual norm of the field they produced: n steps are ONE
+        # jacobi_run call.  (The norm of step i's result is computed inside the first update of step i+1, in
+        # the same pass over memory; only the last step needs the stand-alone reduction.)  With
+        # --separate-residual: a jacobi_sweep and a residual_norm call per step.
         run, every, res_dev = self.run, self.every, self.res_dev
-        for i in range(n):
-            if i == 0 or not self.fuse_residual:
+        if n <= 0:
+            return
+        if self.fuse_residual:
+            fin = self.h.B.jacobi_run(run.plan, run.cur.data_ptr(), run.other().data_ptr(), n * every, every,
+                                      res_dev.data_ptr(), int(self.torch.cuda.current_stream().cuda_stream))
+            run.cur = run.a if fin == run.a.data_ptr() else run.b
+        else:
+            for i in range(n):
                 run.sweep(every)
-            else:
-                run.sweep_residual(every, res_dev[i - 1:i])
-            if i == n - 1 or not self.fuse_residual:
                 run.residual_async(res_dev[i:i + 1])
 
     def timed(self, K: int, W: int, events: bool, reps: int = 1):

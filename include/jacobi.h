@@ -75,6 +75,10 @@ enum jacobi_status {
  *     x+ halo of row (k, i) at xhalo_offset + xhalo_pitch + k*(th+2) + i;
  *     each array is followed by at least 3 unused elements (xhalo_pitch is rounded up
  *     to a multiple of 128 bytes after adding them).
+ *   - behind them two more dense arrays of the same shape, the x SEND arrays, at xsend_offset
+ *     and xsend_offset + xhalo_pitch: scratch in which an update with option "fused" = 0
+ *     packs the tile's own first and last column for the exchange kernel that follows it.
+ *     Their contents are unspecified between calls; scatter and gather ignore them.
  * A halo cell holds either a copy of the neighbouring tile's edge cell (refreshed
  * by halo_exchange) or, on the domain boundary, the Dirichlet value.
  */
@@ -92,6 +96,7 @@ typedef struct jacobi_layout {
     int64_t xhalo_pitch;   /* distance from the x- to the x+ halo array */
     int64_t tile_stride;   /* elements between consecutive tiles */
     int64_t grid_bytes;    /* ntiles * tile_stride * sizeof(element) */
+    int64_t xsend_offset;  /* start of the x send arrays inside a tile (xhalo_pitch apart) */
 } jacobi_layout;
 
 /*
@@ -169,7 +174,10 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  * With option "fused" = 1 the update kernel itself writes each tile's fresh edge
  * cells into the neighbours' halos of the destination buffer (pack, transfer and
  * unpack fused into the update's epilogue), and only the first iteration needs a
- * separate exchange; results are identical.
+ * separate exchange; results are identical.  With "fused" = 0 every iteration runs the
+ * exchange kernel; the update then packs each tile's first and last column into dense
+ * send arrays (the strided x faces: one cell per cache line otherwise), from which the
+ * exchange of the next iteration copies.
  * After return, the inter-tile halos of the result are unspecified (stale or fresh
  * depending on the option); call halo_exchange if they are needed.
  * Asynchronous on `stream`; allocates no memory once the plan is prepared (jacobi_prepare; with
@@ -192,6 +200,21 @@ int jacobi_sweep(jacobi_plan *plan, void *in, void *out, int iters, void *stream
  */
 int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, void *stream,
                           void **final, double *residual_in_dev);
+
+/*
+ * jacobi_run: a whole workload schedule in one call: `iters` iterations, and after every
+ * `residual_every`-th of them the residual norm of the grid THAT iteration produced, written to
+ * residuals_dev[k] for the (k+1)*residual_every-th iteration (a DEVICE array of
+ * iters / residual_every doubles; may be NULL if that is 0; residual_every = 0: no norms).
+ * Equivalent to blocks of jacobi_sweep(residual_every) each followed by residual_norm, but each norm
+ * except the last is taken from inside the first update of the NEXT block (jacobi_sweep_residual), so
+ * it costs no pass over memory of its own; values agree up to summation order.  in / out / final as
+ * for jacobi_sweep (the buffers swap roles once per pass of every block: read *final).
+ * Asynchronous on `stream`; allocates and synchronises nothing once the plan is prepared.
+ * Errors: EINVAL, ENOMEM, EHIP.
+ */
+int jacobi_run(jacobi_plan *plan, void *in, void *out, int iters, int residual_every,
+               double *residuals_dev, void *stream, void **final);
 
 /*
  * jacobi_pass_schedule: what jacobi_sweep(plan, ., ., iters) will launch with the current

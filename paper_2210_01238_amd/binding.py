@@ -20,7 +20,7 @@ JACOBI_OK, JACOBI_EINVAL, JACOBI_ENOTDIV, JACOBI_ENOMEM, JACOBI_EHIP = 0, 1, 2, 
 
 EXPORTS = (
     "jacobi_create", "jacobi_prepare", "jacobi_scratch_bytes", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
-    "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_sweep_tasks", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
+    "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_run", "jacobi_sweep_tasks", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
     "residual_norm_host", "residual_norm_noalloc", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
     "jacobi_last_error", "jacobi_stream_copy",
 )
@@ -32,7 +32,7 @@ class JacobiLayout(ctypes.Structure):
         ("dims", ctypes.c_int64 * 3), ("tiles", ctypes.c_int64 * 3), ("tile", ctypes.c_int64 * 3),
         ("ntiles", ctypes.c_int64), ("nplanes", ctypes.c_int64), ("pitch", ctypes.c_int64),
         ("plane", ctypes.c_int64), ("xhalo_offset", ctypes.c_int64), ("xhalo_pitch", ctypes.c_int64),
-        ("tile_stride", ctypes.c_int64), ("grid_bytes", ctypes.c_int64),
+        ("tile_stride", ctypes.c_int64), ("grid_bytes", ctypes.c_int64), ("xsend_offset", ctypes.c_int64),
     ]
 
 
@@ -62,6 +62,7 @@ def _load() -> ctypes.CDLL:
     lib.jacobi_gather.argtypes = [vp, vp, vp, vp]
     lib.jacobi_sweep.argtypes = [vp, vp, vp, ci, vp, P(vp)]
     lib.jacobi_sweep_residual.argtypes = [vp, vp, vp, ci, vp, P(vp), vp]
+    lib.jacobi_run.argtypes = [vp, vp, vp, ci, ci, vp, vp, P(vp)]
     lib.jacobi_sweep_tasks.argtypes = [vp, vp, vp, ci, ci, ci, vp, P(vp)]
     lib.jacobi_pass_schedule.argtypes = [vp, ci, P(ci), ci, P(ci)]
     lib.halo_exchange.argtypes = [vp, vp, vp]
@@ -167,6 +168,16 @@ def jacobi_sweep_residual(plan: int, grid_in: int, grid_out: int, iters: int, re
     fin = ctypes.c_void_p()
     _check(lib.jacobi_sweep_residual(plan, grid_in, grid_out, int(iters), stream, ctypes.byref(fin),
                                      residual_in_dev))
+    return fin.value
+
+
+def jacobi_run(plan: int, grid_in: int, grid_out: int, iters: int, residual_every: int, residuals_dev: Optional[int],
+               stream: int = 0) -> int:
+    """iters iterations with the residual norm after every residual_every-th one written to the device
+    array residuals_dev.  Returns the pointer that holds the result grid."""
+    fin = ctypes.c_void_p()
+    _check(lib.jacobi_run(plan, grid_in, grid_out, int(iters), int(residual_every), residuals_dev, stream,
+                          ctypes.byref(fin)))
     return fin.value
 
 

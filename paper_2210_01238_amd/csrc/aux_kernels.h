@@ -18,19 +18,17 @@ __global__ __launch_bounds__(1024) void residual_final_kernel(const double *__re
 }
 
 // ------------------------------------------------------------------------------------
-// Face copies.  A face of a tile is one of its 2*ndim halo faces (0: x-, 1: x+, 2: y-,
-// 3: y+, 4: z-, 5: z+), interior extent only (edges/corners are never read by the
-// stencils).  EXCHANGE: for faces with a neighbouring tile, halo <- neighbour's edge cells
-// (pack + transfer + unpack in one gather-scatter copy), within one grid.  BOUNDARY: for
-// faces on the domain boundary, copy the Dirichlet halo cells from `src` grid to `dst` grid.
-// Work item = (tile, face, chunk of 4*WG cells); workgroups stride over the item list.
+// Boundary copy.  A face of a tile is one of its 2*ndim halo faces (0: x-, 1: x+, 2: y-, 3: y+, 4: z-,
+// 5: z+).  For every face that lies on the domain boundary, the Dirichlet halo cells are copied from the
+// `src` grid to the `dst` grid - the full padded extent of the face, with its edges and corners, so that
+// the destination carries the complete ring.  Work item = (tile, face, chunk of 4*WG cells); workgroups
+// stride over the item list.
 // ------------------------------------------------------------------------------------
-enum FaceMode { FACE_EXCHANGE = 0, FACE_BOUNDARY = 1 };
 constexpr int FACE_CHUNK = 4 * WG;
 
-template <typename T, int FMODE>
-__global__ __launch_bounds__(WG) void face_copy_kernel(Geo g, const T *__restrict__ src, T *__restrict__ dst,
-                                                       int chunks_per_face, long long nitems)
+template <typename T>
+__global__ __launch_bounds__(WG) void boundary_copy_kernel(Geo g, const T *__restrict__ src, T *__restrict__ dst,
+                                                           int chunks_per_face, long long nitems)
 {
     const int nfaces = 2 * g.ndim;
     for (long long item = blockIdx.x; item < nitems; item += gridDim.x) {
@@ -41,41 +39,108 @@ __global__ __launch_bounds__(WG) void face_copy_kernel(Geo g, const T *__restric
         const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
         const int tc = axis == 0 ? tx : axis == 1 ? ty : tz;
         const int Tn = axis == 0 ? g.Tx : axis == 1 ? g.Ty : g.Tz;
-        const bool has_nbr = hi ? tc < Tn - 1 : tc > 0;
-        if ((FMODE == FACE_EXCHANGE) != has_nbr) continue;
-
-        const long long tstep = axis == 0 ? 1 : axis == 1 ? g.Tx : (long long)g.Ty * g.Tx;
-        const T *stile = src + ((long long)t + (FMODE == FACE_EXCHANGE ? (hi ? tstep : -tstep) : 0)) * g.tile_stride;
-        T *dtile = dst + (long long)t * g.tile_stride;
-
-        // face cells are indexed (a, b) with b fastest.  EXCHANGE copies the interior extent of
-        // the face; BOUNDARY the full padded extent (face plus its edges and corners), so the
-        // destination grid carries the complete Dirichlet ring.
-        constexpr int X = FMODE == FACE_BOUNDARY ? 1 : 0;   // extend by the halo cells
-        const int nb = axis == 0 ? g.th + 2 * X : g.tw;
-        const int na = axis == 2 ? g.th + 2 * X : (X ? g.nplanes : g.td);
-        const int k_first = X ? 0 : g.z0, i_first = X ? 0 : 1;
+        if (hi ? tc < Tn - 1 : tc > 0) continue;     // a neighbouring tile, not the boundary
+        const long long tile = (long long)t * g.tile_stride;
+        // face cells are indexed (a, b) with b fastest, over the padded extent
+        const int nb = axis == 0 ? g.rows : g.tw;
+        const int na = axis == 2 ? g.rows : g.nplanes;
         const long long n = (long long)na * nb;
         const long long base = (long long)chunk * FACE_CHUNK;
         for (int q = 0; q < 4; ++q) {
             const long long e = base + q * WG + threadIdx.x;
             if (e >= n) break;
             const int a = (int)(e / nb), b = (int)(e - (long long)a * nb);
-            long long so, dofs;
-            if (axis == 0) {          // (a, b) = (plane, row)
-                const int k = k_first + a, i = i_first + b;
-                dofs = hi ? xp_off(g, k, i) : xm_off(g, k, i);
-                so = FMODE == FACE_BOUNDARY ? dofs : main_off(g, k, i, hi ? 0 : g.tw - 1);
-            } else if (axis == 1) {   // (a, b) = (plane, column)
-                const int k = k_first + a;
-                dofs = main_off(g, k, hi ? g.th + 1 : 0, b);
-                so = FMODE == FACE_BOUNDARY ? dofs : main_off(g, k, hi ? 1 : g.th, b);
-            } else {                  // (a, b) = (row, column)
-                const int i = i_first + a;
-                dofs = main_off(g, hi ? g.td + 1 : 0, i, b);
-                so = FMODE == FACE_BOUNDARY ? dofs : main_off(g, hi ? 1 : g.td, i, b);
+            const long long off = axis == 0   ? (hi ? xp_off(g, a, b) : xm_off(g, a, b))      // (plane, row)
+                                  : axis == 1 ? main_off(g, a, hi ? g.th + 1 : 0, b)          // (plane, column)
+                                              : main_off(g, hi ? g.td + 1 : 0, a, b);         // (row, column)
+            dst[tile + off] = src[tile + off];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Stand-alone halo exchange (paper Sec. VI-C: pack, transfer, unpack - one copy on one device): for every
+// face of every tile that has a neighbour, halo cells <- the neighbour's edge cells, in place in one grid.
+// y and z faces are rows of the neighbour (contiguous, cache-line aligned): copied as 16-byte vectors, whole
+// vectors (the padding columns behind a row may hold anything and are overwritten with the source's).
+// x faces, XSRC = 0: gathered from the neighbour's first / last column, one cell per row (one cell per cache
+// line: 16 times the payload is read; always valid).  XSRC = 1: copied from the neighbour's dense x send
+// arrays, which a FUSED_PACK update of that grid has just filled (dense to dense).
+// Work item = (tile, face, chunk of 4*64 vectors or cells), one per WAVEFRONT (faces of small tiles are a few
+// hundred bytes: a whole workgroup per face would idle most of its lanes); a lane issues its (up to) four
+// loads before its stores.  Workgroups stride over the item list.
+// ------------------------------------------------------------------------------------
+constexpr int HALO_CHUNK = 4 * WAVE;
+
+template <typename T, int XSRC>
+__global__ __launch_bounds__(WG) void halo_exchange_kernel(Geo g, T *grid, int chunks_per_face, long long nitems)
+{
+    using V = typename Vec<T>::type;
+    constexpr int NV = Vec<T>::N;
+    const int nfaces = 2 * g.ndim;
+    const int vrow = (g.tw + NV - 1) / NV;           // vectors per row (pitch is a multiple of NV)
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    for (long long item = (long long)blockIdx.x * WAVES_PER_WG + wave; item < nitems; item += (long long)gridDim.x * WAVES_PER_WG) {
+        const int chunk = (int)(item % chunks_per_face);
+        const long long tf = item / chunks_per_face;
+        const int face = (int)(tf % nfaces), t = (int)(tf / nfaces);
+        const int axis = face >> 1, hi = face & 1;   // axis 0: x, 1: y, 2: z
+        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+        const int tc = axis == 0 ? tx : axis == 1 ? ty : tz;
+        const int Tn = axis == 0 ? g.Tx : axis == 1 ? g.Ty : g.Tz;
+        if (!(hi ? tc < Tn - 1 : tc > 0)) continue;   // no neighbour on this side
+        const long long tstep = axis == 0 ? 1 : axis == 1 ? g.Tx : (long long)g.Ty * g.Tx;
+        const T *stile = grid + ((long long)t + (hi ? tstep : -tstep)) * g.tile_stride;
+        T *dtile = grid + (long long)t * g.tile_stride;
+        // offsets inside a tile fit 32 bits (a tile has fewer than 2^31 elements): keeps the index arithmetic cheap
+        const unsigned base = (unsigned)chunk * HALO_CHUNK;
+        unsigned dofs[4];
+        constexpr unsigned NONE = 0xffffffffu;
+        if (axis == 0) {
+            // cells (plane a, row b), b fastest: consecutive lanes write consecutive halo entries
+            const unsigned n = (unsigned)g.td * (unsigned)g.th;
+            const unsigned s0 = XSRC ? (unsigned)(g.xsend + (hi ? 0 : g.hpitch)) : (hi ? 0u : (unsigned)(g.tw - 1));
+            const unsigned d0 = (unsigned)(g.xoff + (hi ? g.hpitch : 0));
+            T v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned e = base + q * WAVE + lane;
+                dofs[q] = NONE;
+                if (e >= n) continue;
+                const unsigned a = e / (unsigned)g.th, b = e - a * (unsigned)g.th;
+                const unsigned k = g.z0 + a, i = 1 + b;
+                const unsigned entry = k * (unsigned)g.rows + i;
+                // my x+ halo <- the right neighbour's first column; my x- halo <- the left neighbour's last column
+                v[q] = stile[XSRC ? s0 + entry : entry * (unsigned)g.pitch + s0];
+                dofs[q] = d0 + entry;
             }
-            dtile[dofs] = stile[so];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (dofs[q] != NONE) dtile[dofs[q]] = v[q];
+        } else {
+            // vectors (row a of the face, vector b of the row): y faces have one row per plane, z faces th rows
+            const unsigned na = axis == 1 ? g.td : g.th;
+            const unsigned n = na * (unsigned)vrow;
+            // element offset of face row a: y faces step by a plane, z faces by a row
+            const unsigned step = axis == 1 ? (unsigned)g.plane : (unsigned)g.pitch;
+            const unsigned first = axis == 1 ? (unsigned)g.z0 * (unsigned)g.plane : (unsigned)g.pitch;
+            const unsigned d0 = first + (axis == 1 ? (hi ? (unsigned)(g.th + 1) * g.pitch : 0u)
+                                                   : (hi ? (unsigned)(g.td + 1) * (unsigned)g.plane : 0u));
+            const unsigned s0 = first + (axis == 1 ? (hi ? 1u : (unsigned)g.th) * g.pitch
+                                                   : (hi ? 1u : (unsigned)g.td) * (unsigned)g.plane);
+            V v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned e = base + q * WAVE + lane;
+                dofs[q] = NONE;
+                if (e >= n) continue;
+                const unsigned a = e / (unsigned)vrow, c = (e - a * (unsigned)vrow) * NV;
+                v[q] = *(const V *)(stile + (s0 + a * step + c));
+                dofs[q] = d0 + a * step + c;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (dofs[q] != NONE) *(V *)(dtile + dofs[q]) = v[q];
         }
     }
 }

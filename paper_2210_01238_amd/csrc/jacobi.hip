@@ -145,7 +145,8 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     sp.R = R;
     sp.nblk = (int)ceil_div(extent, R);
     sp.nstrips = lanes_of_work * sp.nblk;
-    sp.fused = (int)p->fused;
+    // option fused = 0: the exchange is a kernel of its own, and the updates pack their x edge cells for it
+    sp.fused = p->fused ? jk::FUSED_PUSH : jk::FUSED_PACK;
     int u = (int)p->unroll;
     // one workgroup per CU for the 3-D update of a large grid (see launch_sweep)
     // (fp64 rows that fill a wavefront's 64 x 16 bytes only: fp32, and tiles narrower than 128 cells, lose with it)
@@ -538,11 +539,11 @@ PassChoice choose_pass(const jacobi_plan *p, int left)
     return {1, 0};
 }
 
-template <typename T, int FMODE>
-int launch_faces_t(jacobi_plan *p, const T *src, T *dst, hipStream_t st)
+template <typename T>
+int launch_boundary_t(jacobi_plan *p, const T *src, T *dst, hipStream_t st)
 {
     const Geo &g = p->geo;
-    // largest face, in cells, including its edge cells (the boundary copy covers those too)
+    // largest face, in cells, including its edge cells
     const int64_t pd = g.nplanes, ph = g.rows;
     int64_t max_face = pd * ph;                                    // x faces
     if (pd * g.tw > max_face) max_face = pd * g.tw;                // y faces
@@ -550,25 +551,46 @@ int launch_faces_t(jacobi_plan *p, const T *src, T *dst, hipStream_t st)
     const int chunks = (int)ceil_div(max_face, jk::FACE_CHUNK);
     const int64_t nitems = (int64_t)g.ntiles * 2 * g.ndim * chunks;
     const int64_t nblk = nitems < MAX_COPY_BLOCKS ? nitems : MAX_COPY_BLOCKS;
-    hipLaunchKernelGGL((jk::face_copy_kernel<T, FMODE>), dim3((unsigned)nblk), dim3(jk::WG), 0, st, g, src, dst,
+    hipLaunchKernelGGL((jk::boundary_copy_kernel<T>), dim3((unsigned)nblk), dim3(jk::WG), 0, st, g, src, dst,
                        chunks, (long long)nitems);
     HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
 
-int launch_exchange(jacobi_plan *p, void *grid, hipStream_t st)
+template <typename T, int XSRC>
+int launch_exchange_t(jacobi_plan *p, T *grid, hipStream_t st)
+{
+    const Geo &g = p->geo;
+    const int nv = 16 / (int)sizeof(T);
+    const int64_t vrow = ceil_div(g.tw, nv);
+    // largest face in its copy units: cells of an x face, 16-byte vectors of a y or z face
+    int64_t units = (int64_t)g.td * g.th;
+    if ((int64_t)g.td * vrow > units) units = (int64_t)g.td * vrow;
+    if (g.ndim == 3 && (int64_t)g.th * vrow > units) units = (int64_t)g.th * vrow;
+    const int chunks = (int)ceil_div(units, jk::HALO_CHUNK);
+    const int64_t nitems = (int64_t)g.ntiles * 2 * g.ndim * chunks;            // one per wavefront
+    const int64_t nwg = ceil_div(nitems, jk::WAVES_PER_WG);
+    const int64_t nblk = nwg < MAX_COPY_BLOCKS ? nwg : MAX_COPY_BLOCKS;
+    hipLaunchKernelGGL((jk::halo_exchange_kernel<T, XSRC>), dim3((unsigned)nblk), dim3(jk::WG), 0, st, g, grid, chunks,
+                       (long long)nitems);
+    HIP_TRY(hipGetLastError());
+    return JACOBI_OK;
+}
+
+// Halo exchange of `grid`.  from_send_arrays: the x faces are copied from the tiles' dense x send arrays (only
+// valid if the grid was just produced by an update in FUSED_PACK mode) instead of gathered from their columns.
+int launch_exchange(jacobi_plan *p, void *grid, hipStream_t st, bool from_send_arrays = false)
 {
     if (p->geo.ntiles == 1) return JACOBI_OK;   // no neighbours, nothing to copy
-    return p->lay.dtype == JACOBI_F64
-               ? launch_faces_t<double, jk::FACE_EXCHANGE>(p, (const double *)grid, (double *)grid, st)
-               : launch_faces_t<float, jk::FACE_EXCHANGE>(p, (const float *)grid, (float *)grid, st);
+    if (p->lay.dtype == JACOBI_F64)
+        return from_send_arrays ? launch_exchange_t<double, 1>(p, (double *)grid, st) : launch_exchange_t<double, 0>(p, (double *)grid, st);
+    return from_send_arrays ? launch_exchange_t<float, 1>(p, (float *)grid, st) : launch_exchange_t<float, 0>(p, (float *)grid, st);
 }
 
 int launch_boundary_sync(jacobi_plan *p, const void *in, void *out, hipStream_t st)
 {
-    return p->lay.dtype == JACOBI_F64
-               ? launch_faces_t<double, jk::FACE_BOUNDARY>(p, (const double *)in, (double *)out, st)
-               : launch_faces_t<float, jk::FACE_BOUNDARY>(p, (const float *)in, (float *)out, st);
+    return p->lay.dtype == JACOBI_F64 ? launch_boundary_t<double>(p, (const double *)in, (double *)out, st)
+                                      : launch_boundary_t<float>(p, (const float *)in, (float *)out, st);
 }
 
 template <typename T, bool GATHER>
@@ -744,7 +766,8 @@ int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64
     L.xhalo_offset = L.nplanes * L.plane;
     // at least 3 spare elements after each array: a vector read that starts at the last entry stays inside the tile
     L.xhalo_pitch = round_up(L.nplanes * (L.tile[1] + 2) + 3, line);
-    L.tile_stride = L.xhalo_offset + 2 * L.xhalo_pitch;
+    L.xsend_offset = L.xhalo_offset + 2 * L.xhalo_pitch;
+    L.tile_stride = L.xsend_offset + 2 * L.xhalo_pitch;
     L.grid_bytes = L.ntiles * L.tile_stride * (int64_t)p->esize;
 
     const int64_t lim = 0x7fffffffLL;
@@ -768,6 +791,7 @@ int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64
     g.plane = L.plane;
     g.xoff = L.xhalo_offset;
     g.hpitch = L.xhalo_pitch;
+    g.xsend = L.xsend_offset;
     g.tile_stride = L.tile_stride;
     *plan = p;
     return JACOBI_OK;
@@ -892,12 +916,13 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     void *src = in, *dst = out;
     int k = 0;
     bool halos_current = false;     // inter-tile halos of src hold src's own edge cells
+    bool x_packed = false;          // src's x send arrays hold its first / last columns (the last pass packed them)
     while (k < iters) {
         const PassChoice pc = choose_pass(plan, iters - k);
         const bool with_res = k == 0 && residual_in_dev;
         if (pc.depth == 1 && !halos_current) {
             // the single-step update reads halos; blocked passes neither need nor refresh them
-            rc = launch_exchange(plan, src, st);
+            rc = launch_exchange(plan, src, st, x_packed);
             if (rc) return rc;
         }
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
@@ -917,8 +942,9 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
                                (long long)nwg_res, residual_in_dev);
             HIP_TRY(hipGetLastError());
         }
-        // a single-step update with the fused push leaves dst's halos current
+        // a single-step update with the fused push leaves dst's halos current; without it, dst's x send arrays
         halos_current = pc.depth == 1 && plan->fused;
+        x_packed = pc.depth == 1 && !plan->fused;
         void *t = src; src = dst; dst = t;
         k += pc.depth;
     }
@@ -1073,6 +1099,38 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
     if (iters < 1) return fail(JACOBI_EINVAL, "iters must be >= 1");
     if (final) *final = in;
     return sweep_common(plan, in, out, iters, (hipStream_t)stream, final, residual_in_dev);
+}
+
+int jacobi_run(jacobi_plan *plan, void *in, void *out, int iters, int residual_every, double *residuals_dev,
+               void *stream, void **final)
+{
+    if (!plan || !in || !out) return fail(JACOBI_EINVAL, "NULL argument");
+    if (in == out) return fail(JACOBI_EINVAL, "in and out must be different grids");
+    if (misaligned(in) || misaligned(out)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
+    if (grids_overlap(plan, in, out)) return fail(JACOBI_EINVAL, "in and out overlap");
+    if (iters < 0 || residual_every < 0) return fail(JACOBI_EINVAL, "iters and residual_every must be >= 0");
+    const int nres = residual_every > 0 ? iters / residual_every : 0;
+    if (nres > 0 && !residuals_dev) return fail(JACOBI_EINVAL, "residuals_dev is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    void *cur = in, *other = out;
+    int done = 0, pending = -1;      // pending: index of a residual still owed for the grid in `cur`
+    while (done < iters) {
+        const int n = std::min(residual_every > 0 ? residual_every : iters, iters - done);
+        void *fin = cur;
+        // the norm of the grid a block of iterations produced is taken from the first update of the next block
+        int rc = sweep_common(plan, cur, other, n, st, &fin, pending >= 0 ? residuals_dev + pending : nullptr);
+        if (rc) return rc;
+        pending = -1;
+        if (fin != cur) std::swap(cur, other);
+        done += n;
+        if (residual_every > 0 && done % residual_every == 0) {
+            const int k = done / residual_every - 1;
+            if (done < iters) pending = k;
+            else if ((rc = residual_common(plan, cur, residuals_dev + k, st))) return rc;   // the last one: stand-alone
+        }
+    }
+    if (final) *final = cur;
+    return JACOBI_OK;
 }
 
 int residual_norm(jacobi_plan *plan, void *grid, double *result_dev, void *stream)

@@ -42,6 +42,7 @@ struct Geo {
     long long plane;        // rows * pitch
     long long xoff;         // x- halo array offset inside a tile
     long long hpitch;       // x- -> x+ halo array distance
+    long long xsend;        // x send arrays (packed copies of the tile's own first / last column), hpitch apart
     long long tile_stride;  // elements per tile
 };
 
@@ -248,12 +249,20 @@ __device__ __forceinline__ double wg_sum(double v, double *lds /* WAVES_PER_WG (
 // exactly the values the update already holds in registers).
 enum Mode { MODE_UPDATE = 0, MODE_RESIDUAL = 1, MODE_BOTH = 2 };
 
+// What an update does with a tile's fresh edge cells besides storing them in place.  PUSH: writes them into the
+// face neighbours' halo cells of the destination grid (pack, transfer and unpack in the update's epilogue).
+// PACK: writes the first / last column into the tile's own dense x send arrays (the paper's "pack into a
+// contiguous message buffer", Sec. VI-C; rows and planes are contiguous already), from which the stand-alone
+// exchange kernel then copies instead of gathering one cell per cache line.
+enum Fused { FUSED_NONE = 0, FUSED_PUSH = 1, FUSED_PACK = 2 };
+
 struct StripParams {
     int R;               // rows (2-D) / planes (3-D) per strip
     int nseg;            // column segments per row = ceil(pitch / (64*NV))
     int nblk;            // strips along the marching direction = ceil(extent / R)
     long long nstrips;   // total
-    int fused;           // update mode: push edge cells into neighbour halos of dst
+    int fused;           // update mode: 1 = push edge cells into the neighbours' halo cells of dst (FUSED_PUSH),
+                         // 2 = pack the x edge cells into the tile's own send arrays of dst (FUSED_PACK)
     int xcd_chunk;       // G of xcd_logical_wg(): consecutive workgroups one XCD takes
     int rows_fastest = 0; // 3-D blocked passes: consecutive strips are neighbours in y (else in x)
     int tile0 = 0;        // single-step kernels: first tile this launch covers (a task = a range of tiles)
@@ -299,12 +308,16 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
         const bool e_in_row = e_col < g.pitch;
         const T *tsrc = src + (long long)t * g.tile_stride;
         T *tdst = dst + (long long)t * g.tile_stride;
-        // neighbour tiles of dst that receive this strip's edge cells (fused mode)
-        const bool push = MODE != MODE_RESIDUAL && sp.fused;
+        // where this strip's edge cells go besides their own place: the neighbour tiles' halo cells of dst
+        // (push), or for the x edges the tile's own send arrays (pack); x targets are indexed by the row
+        const bool push = MODE != MODE_RESIDUAL && sp.fused == FUSED_PUSH;
+        const bool xcopy = MODE != MODE_RESIDUAL && sp.fused != FUSED_NONE;
         T *dst_ym = (push && ty > 0) ? tdst - (long long)g.Tx * g.tile_stride : nullptr;
         T *dst_yp = (push && ty < g.Ty - 1) ? tdst + (long long)g.Tx * g.tile_stride : nullptr;
-        T *dst_xm = (push && tx > 0 && col0 == 0 && active) ? tdst - g.tile_stride : nullptr;
-        T *dst_xp = (push && tx < g.Tx - 1 && has_last) ? tdst + g.tile_stride : nullptr;
+        T *dst_xm = (xcopy && tx > 0 && col0 == 0 && active)
+                        ? (push ? tdst - g.tile_stride + g.xoff + g.hpitch : tdst + g.xsend) : nullptr;
+        T *dst_xp = (xcopy && tx < g.Tx - 1 && has_last)
+                        ? (push ? tdst + g.tile_stride + g.xoff : tdst + g.xsend + g.hpitch) : nullptr;
 
         V prev = V(0), cur = V(0);
         if (active) {
@@ -358,11 +371,11 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
                     if constexpr (MODE != MODE_RESIDUAL) {
                         if (active) {
                             stv<(NT & 2) != 0>((V *)(tdst + main_off(g, 0, rr, col0)), out);
-                            if (push) {
+                            if (xcopy) {
                                 if (rr == 1 && dst_ym) *(V *)(dst_ym + main_off(g, 0, g.th + 1, col0)) = out;
                                 if (rr == g.th && dst_yp) *(V *)(dst_yp + main_off(g, 0, 0, col0)) = out;
-                                if (dst_xm) dst_xm[xp_off(g, 0, rr)] = out[0];
-                                if (dst_xp) dst_xp[xm_off(g, 0, rr)] = out[jlast];
+                                if (dst_xm) dst_xm[rr] = out[0];
+                                if (dst_xp) dst_xp[rr] = out[jlast];
                             }
                         }
                     }
@@ -863,14 +876,19 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
 
         const T *tsrc = src + (long long)t * g.tile_stride;
         T *tdst = dst + (long long)t * g.tile_stride;
-        const bool push = MODE != MODE_RESIDUAL && sp.fused;
+        // push: edge cells into the neighbour tiles' halo cells of dst; pack: x edge cells into the tile's own
+        // send arrays (see Fused); x targets are indexed by (plane, row)
+        const bool push = MODE != MODE_RESIDUAL && sp.fused == FUSED_PUSH;
+        const bool xcopy = MODE != MODE_RESIDUAL && sp.fused != FUSED_NONE;
         const long long zs = (long long)g.Ty * g.Tx * g.tile_stride, ys = (long long)g.Tx * g.tile_stride;
         T *dst_zm = (push && tz > 0) ? tdst - zs : nullptr;
         T *dst_zp = (push && tz < g.Tz - 1) ? tdst + zs : nullptr;
         T *dst_ym = (push && ty > 0) ? tdst - ys : nullptr;
         T *dst_yp = (push && ty < g.Ty - 1) ? tdst + ys : nullptr;
-        T *dst_xm = (push && tx > 0 && col0 == 0 && active) ? tdst - g.tile_stride : nullptr;
-        T *dst_xp = (push && tx < g.Tx - 1 && has_last) ? tdst + g.tile_stride : nullptr;
+        T *dst_xm = (xcopy && tx > 0 && col0 == 0 && active)
+                        ? (push ? tdst - g.tile_stride + g.xoff + g.hpitch : tdst + g.xsend) : nullptr;
+        T *dst_xp = (xcopy && tx < g.Tx - 1 && has_last)
+                        ? (push ? tdst + g.tile_stride + g.xoff : tdst + g.xsend + g.hpitch) : nullptr;
 
         // rows below the tile (ragged last row group) are clamped to the y+ halo row th+1, so the
         // register row after the last real row IS that row's y+ neighbour; clamped rows never store
@@ -957,13 +975,13 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                     }
                     if constexpr (STORES) {
                         buffer_store<(NT & 2) != 0>(out, out_plane, wanted ? col_bytes : BUF_SKIP, row_start(min(i, g.th + 1)));
-                        if (push && wanted && active) {
+                        if (xcopy && wanted && active) {
                             if (kk == 1 && dst_zm) *(V *)(dst_zm + main_off(g, g.td + 1, i, col0)) = out;
                             if (kk == g.td && dst_zp) *(V *)(dst_zp + main_off(g, 0, i, col0)) = out;
                             if (i == 1 && dst_ym) *(V *)(dst_ym + main_off(g, kk, g.th + 1, col0)) = out;
                             if (i == g.th && dst_yp) *(V *)(dst_yp + main_off(g, kk, 0, col0)) = out;
-                            if (dst_xm) dst_xm[xp_off(g, kk, i)] = out[0];
-                            if (dst_xp) dst_xp[xm_off(g, kk, i)] = out[jlast];
+                            if (dst_xm) dst_xm[(long long)kk * g.rows + i] = out[0];
+                            if (dst_xp) dst_xp[(long long)kk * g.rows + i] = out[jlast];
                         }
                     }
                 }

@@ -42,7 +42,7 @@ def test_layout_2d(J):
     assert list(L.tile) == [1, 2048, 2048] and list(L.tiles) == [1, 8, 8]
     assert L.pitch == 2048 and L.plane == 2050 * 2048 and L.xhalo_offset == L.plane
     assert L.xhalo_pitch % 16 == 0 and L.xhalo_pitch >= 2050
-    assert L.tile_stride == L.xhalo_offset + 2 * L.xhalo_pitch
+    assert L.xsend_offset == L.xhalo_offset + 2 * L.xhalo_pitch and L.tile_stride == L.xsend_offset + 2 * L.xhalo_pitch
     assert L.grid_bytes == 64 * L.tile_stride * 8 == J.jacobi_grid_bytes(p)
     assert (L.pitch * 8) % 128 == 0 and (L.tile_stride * 8) % 128 == 0
     J.jacobi_destroy(p)
@@ -87,6 +87,9 @@ def test_null_and_argument_errors_without_device(J):
                  lambda: J.jacobi_sweep(p, 4096, 4096 + nb - 16, 1),       # overlapping
                  lambda: J.halo_exchange(p, 264), lambda: J.residual_norm(p, 264, 256),
                  lambda: J.jacobi_sweep(p, 256, 256 + nb, -1), lambda: J.halo_exchange(p, 0),
+                 lambda: J.jacobi_run(p, 256, 256 + nb, 4, 2, None), lambda: J.jacobi_run(p, 256, 256 + nb, -1, 2, 768),
+                 lambda: J.jacobi_run(p, 256, 256 + nb, 4, -1, 768), lambda: J.jacobi_run(p, 256, 256, 4, 2, 768),
+                 lambda: J.jacobi_run(p, 0, 256, 4, 2, 768),
                  lambda: J.jacobi_sweep_residual(p, 256, 256 + nb, 0, 768), lambda: J.jacobi_sweep_residual(p, 256, 256 + nb, 1, 0),
                  lambda: J.residual_norm(p, 0, 256), lambda: J.residual_norm(p, 256, 0),
                  lambda: J.jacobi_scatter(p, 0, 256), lambda: J.jacobi_gather(p, 256, 0),
@@ -100,6 +103,7 @@ def test_null_and_argument_errors_without_device(J):
             call()
         assert e.value.code == 1
     assert J.jacobi_sweep(p, 256, 256 + nb, 0) == 256     # zero iterations: no-op, result in `in`
+    assert J.jacobi_run(p, 256, 256 + nb, 0, 2, None) == 256
     J.jacobi_set_option(p, "fused", 0)
     assert J.jacobi_get_option(p, "fused") == 0
     assert J.jacobi_grid_bytes(None) == 0
