@@ -169,6 +169,9 @@ int jacobi_gather(jacobi_plan *plan, const void *grid, void *global_padded_dev, 
  *            jacobi_pass_schedule), so read *final.
  * First copies the Dirichlet boundary halos in -> out so both buffers carry them, then
  * for each iteration: halo exchange on the source buffer, update into the other buffer.
+ * (How the exchange is carried out depends on option "fused", below; the first update of a
+ * call reads the neighbouring tiles' edge cells directly, which is why `in`'s inter-tile
+ * halos need not be valid and are not refreshed.)
  * (Option "tblock" > 1 replaces this per-iteration sequence by multi-iteration passes, and small
  * 2-D grids run all iterations of the call inside one launch: option "resident".)
  * With option "fused" = 1 the update kernel itself writes each tile's fresh edge
@@ -255,9 +258,11 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
 int halo_exchange(jacobi_plan *plan, void *grid, void *stream);
 
 /*
- * residual_norm: exchanges halos of `grid`, then writes
+ * residual_norm: writes
  *     sqrt( sum over all interior points of (sum of face neighbours - 2d*u)^2 )
- * to *result_dev (a DEVICE double).  The sum is accumulated in fp64 in a fixed
+ * to *result_dev (a DEVICE double).  The inter-tile halo cells of `grid` need not be
+ * current and are left alone: the pass reads the neighbouring tiles' edge cells itself
+ * (the exchange is part of its loads); only the Dirichlet boundary halos are read as halos.  The sum is accumulated in fp64 in a fixed
  * two-stage order (per-wavefront shuffle tree -> LDS -> per-workgroup partial -> one
  * final workgroup), so it is bit-reproducible from run to run.  Uses the plan-owned
  * device scratch (jacobi_prepare); two calls on one plan that overlap in time (different

@@ -173,9 +173,10 @@ int launch_checked(hipError_t e, const char *what)
 // Single-step pass over `src` in the given mode (jk::Mode); with tile_count > 0 only over the tiles
 // [tile0, tile0 + tile_count).
 int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *partial, hipStream_t st,
-                 int tile0 = 0, int tile_count = 0)
+                 int tile0 = 0, int tile_count = 0, bool pull = false)
 {
     SweepConfig c = make_config(p, mode);
+    c.sp.pull = pull ? 1 : 0;
     if (tile_count > 0) {
         c.sp.nstrips = c.sp.nstrips / p->geo.ntiles * tile_count;   // strips are laid out tile by tile
         c.sp.tile0 = tile0;
@@ -202,16 +203,17 @@ int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *p
     return launch_checked(e, "update kernel launch");
 }
 
-int launch_update(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
+// pull: src's inter-tile halo cells are not current; read the neighbouring tiles' edge cells instead
+int launch_update(jacobi_plan *p, const void *src, void *dst, hipStream_t st, bool pull)
 {
-    return launch_sweep(p, jk::MODE_UPDATE, src, dst, nullptr, st);
+    return launch_sweep(p, jk::MODE_UPDATE, src, dst, nullptr, st, 0, 0, pull);
 }
 
 // Update src -> dst and, in the same pass, per-workgroup partial sums of the squared residual
 // terms of src.
-int launch_update_with_residual(jacobi_plan *p, const void *src, void *dst, hipStream_t st)
+int launch_update_with_residual(jacobi_plan *p, const void *src, void *dst, hipStream_t st, bool pull)
 {
-    return launch_sweep(p, jk::MODE_BOTH, src, dst, p->partial, st);
+    return launch_sweep(p, jk::MODE_BOTH, src, dst, p->partial, st, 0, 0, pull);
 }
 
 // Two time steps per pass (2-D only; needs tiles of at least 2 x 2 cells).
@@ -669,14 +671,13 @@ int check_partials(const jacobi_plan *p, int64_t nwg)
     return JACOBI_OK;
 }
 
-// Exchange + residual pass of `grid`, partial sums into `partial` (at least nwg entries), result to *out.
+// Residual pass of `grid` (it reads the neighbouring tiles' edge cells itself: the grid's halo cells need not be
+// current and are left alone), partial sums into `partial` (at least nwg entries), result to *out.
 int residual_launches(jacobi_plan *p, void *grid, double *partial, double *out, hipStream_t st)
 {
     const StripParams sp = make_config(p, jk::MODE_RESIDUAL).sp;
     const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
-    int rc = launch_exchange(p, grid, st);
-    if (rc) return rc;
-    rc = launch_sweep(p, jk::MODE_RESIDUAL, grid, grid, partial, st);
+    int rc = launch_sweep(p, jk::MODE_RESIDUAL, grid, grid, partial, st, 0, 0, /*pull=*/true);
     if (rc) return rc;
     hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, partial, (long long)nwg, out);
     HIP_TRY(hipGetLastError());
@@ -877,7 +878,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     const ResidentChoice rc_res = resident_choice(plan, iters);
     if (rc_res.ok) {
         // small 2-D grid: every iteration inside one launch; the residual of `in`, if asked for, from the
-        // stand-alone reduction first (it refreshes in's halo cells, which the resident kernel does not read)
+        // stand-alone reduction first
         if (residual_in_dev) {
             const int64_t nwg = ceil_div(make_config(plan, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
             rc = check_partials(plan, nwg);
@@ -920,14 +921,18 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     while (k < iters) {
         const PassChoice pc = choose_pass(plan, iters - k);
         const bool with_res = k == 0 && residual_in_dev;
-        if (pc.depth == 1 && !halos_current) {
-            // the single-step update reads halos; blocked passes neither need nor refresh them
+        // A single-step update needs the cells beyond each tile (blocked passes fetch theirs themselves).  With the
+        // fused push they are in src's halo cells from the second update of a run on; the first one PULLS them
+        // from the neighbouring tiles' edges instead of waiting for an exchange kernel.  With fused = 0 the exchange
+        // is a kernel of its own before every update (paper Sec. VI-C: pack, transfer, unpack, then update).
+        const bool pull = pc.depth == 1 && !halos_current && plan->fused;
+        if (pc.depth == 1 && !halos_current && !plan->fused) {
             rc = launch_exchange(plan, src, st, x_packed);
             if (rc) return rc;
         }
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
-        if (pc.kernel == 0)      rc = with_res ? launch_update_with_residual(plan, src, dst, st) : launch_update(plan, src, dst, st);
+        if (pc.kernel == 0)      rc = with_res ? launch_update_with_residual(plan, src, dst, st, pull) : launch_update(plan, src, dst, st, pull);
         else if (pc.kernel == 1) rc = launch_t2(plan, src, dst, with_res, st);
         else if (pc.kernel == 2) rc = launch_tp(plan, pc.depth, src, dst, with_res, st);
         else if (pc.kernel == 3) rc = launch_tp3d(plan, pc.depth, src, dst, with_res, st);

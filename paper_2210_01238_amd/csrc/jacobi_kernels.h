@@ -266,12 +266,17 @@ struct StripParams {
     int xcd_chunk;       // G of xcd_logical_wg(): consecutive workgroups one XCD takes
     int rows_fastest = 0; // 3-D blocked passes: consecutive strips are neighbours in y (else in x)
     int tile0 = 0;        // single-step kernels: first tile this launch covers (a task = a range of tiles)
+    int pull = 0;         // single-step kernels: run the variant that reads the cells beyond a tile from the neighbouring
+                          // tiles' edge cells instead of the tile's halo cells (which may then be stale: no exchange
+                          // needed); the stand-alone residual pass always does
 };
 
 // ------------------------------------------------------------------------------------
 // 2-D: 5-point update (or residual) of every tile.  new = 0.25*((W+E)+(S+N)).
 // ------------------------------------------------------------------------------------
-template <typename T, int MODE, int U, int NT>
+// PULL: cells beyond a tile are read from the neighbouring tiles' edge cells instead of the tile's halo cells (a
+// compile-time switch: as a run-time one its address selects cost the steady-state update 5-7 %).
+template <typename T, int MODE, int U, int NT, bool PULL>
 __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
                                                      double *__restrict__ partial)
@@ -308,6 +313,18 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
         const bool e_in_row = e_col < g.pitch;
         const T *tsrc = src + (long long)t * g.tile_stride;
         T *tdst = dst + (long long)t * g.tile_stride;
+        // Pull mode: a cell beyond the tile is read from the neighbouring tile's edge (row th of the tile above
+        // for halo row 0, row 1 of the tile below for halo row th+1, the last / first column of the tile to the
+        // left / right for the x halos); on the domain boundary the halo cell holds the Dirichlet value as ever.
+        const long long ystep = (long long)g.Tx * g.tile_stride;
+        const bool pull_ym = PULL && ty > 0, pull_yp = PULL && ty < g.Ty - 1;
+        const bool pull_xm = PULL && tx > 0, pull_xp = PULL && tx < g.Tx - 1;
+        // first cell of row `row` (0 .. th+1) as this strip has to read it
+        auto row_ptr = [&](int row) -> const T * {
+            if (row == 0 && pull_ym) return tsrc - ystep + main_off(g, 0, g.th, 0);
+            if (row == g.th + 1 && pull_yp) return tsrc + ystep + main_off(g, 0, 1, 0);
+            return tsrc + main_off(g, 0, row, 0);
+        };
         // where this strip's edge cells go besides their own place: the neighbour tiles' halo cells of dst
         // (push), or for the x edges the tile's own send arrays (pack); x targets are indexed by the row
         const bool push = MODE != MODE_RESIDUAL && sp.fused == FUSED_PUSH;
@@ -321,15 +338,15 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 
         V prev = V(0), cur = V(0);
         if (active) {
-            prev = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, r0 - 1, col0)));
-            cur = ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, r0, col0)));
+            prev = ldv<(NT & 1) != 0>((const V *)(row_ptr(r0 - 1) + col0));
+            cur = ldv<(NT & 1) != 0>((const V *)(row_ptr(r0) + col0));
         }
         for (int r = r0; r <= r1; r += U) {
             V nx[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int rn = min(r + u + 1, g.th + 1);   // clamped: stays inside the tile
-                nx[u] = active ? ldv<(NT & 1) != 0>((const V *)(tsrc + main_off(g, 0, rn, col0))) : V(0);
+                nx[u] = active ? ldv<(NT & 1) != 0>((const V *)(row_ptr(rn) + col0)) : V(0);
             }
             // One gather load fetches every x-edge cell of this group of rows.  It is issued LAST on
             // purpose: the first row then cannot be finished before all row loads have landed, so a
@@ -341,8 +358,11 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
                 const int el = lane & 31;
                 if (el < U) {
                     const int rc = min(r + el, g.th + 1);
-                    if (lane < 32) edge = w_halo ? tsrc[xm_off(g, 0, rc)] : tsrc[main_off(g, 0, rc, seg_c0 - 1)];
-                    else if (seg_has_last) edge = tsrc[xp_off(g, 0, rc)];
+                    if (lane < 32)
+                        edge = !w_halo ? tsrc[main_off(g, 0, rc, seg_c0 - 1)]
+                               : pull_xm ? tsrc[main_off(g, 0, rc, g.tw - 1) - g.tile_stride] : tsrc[xm_off(g, 0, rc)];
+                    else if (seg_has_last)
+                        edge = pull_xp ? tsrc[main_off(g, 0, rc, 0) + g.tile_stride] : tsrc[xp_off(g, 0, rc)];
                     else if (e_in_row) edge = tsrc[main_off(g, 0, rc, e_col)];
                 }
             }
@@ -829,7 +849,7 @@ __global__ __launch_bounds__(WG, MINW) void sweep2d_tp_kernel(Geo g, StripParams
 // so that the compiler can count what is outstanding: a trip waits for its own data only, while
 // its stores and the next trip's loads stay in flight.  (With loads and stores under branches every
 // trip began by waiting for all of them.)  Needs planes smaller than 2 GiB.
-template <typename T, int MODE, int RW, int U, int NT, int NVEC = Vec<T>::N>
+template <typename T, int MODE, int RW, int U, int NT, bool PULL, int NVEC = Vec<T>::N>
 __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
                                                      const T *__restrict__ src, T *__restrict__ dst,
                                                      double *__restrict__ partial)
@@ -899,19 +919,51 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
         const unsigned row_bytes = (unsigned)g.pitch * (unsigned)sizeof(T);
         const unsigned plane_bytes = (unsigned)(g.plane * (long long)sizeof(T));       // below 2 GiB
         const unsigned col_bytes = active ? (unsigned)col0 * (unsigned)sizeof(T) : BUF_SKIP;
-        auto src_plane = [&](int k) { return buffer_of(const_cast<T *>(tsrc) + (long long)k * g.plane, plane_bytes); };
+        // Pull mode (see sweep2d_kernel): cells beyond the tile come from the neighbouring tiles' edge planes,
+        // rows and columns instead of the halo cells.  Everything here is wave-uniform.
+        const bool pull_zm = PULL && tz > 0, pull_zp = PULL && tz < g.Tz - 1;
+        const bool pull_xm = PULL && tx > 0, pull_xp = PULL && tx < g.Tx - 1;
+        // where plane k (0 .. td+1) of the tile has to be read: the halo planes from the tiles below / above
+        auto plane_off = [&](int k) -> long long {
+            return (k == 0 && pull_zm) ? -zs + (long long)g.td * g.plane : (k == g.td + 1 && pull_zp) ? zs + g.plane : (long long)k * g.plane;
+        };
+        // this wavefront's row rw in such a plane.  In the ragged last row group the rows beyond the tile are
+        // clamped onto halo row th+1, which is then a register row's y+ neighbour: pulled from row 1 of the tile behind
+        long long row_tile[RW];
+        unsigned row_begin[RW];
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) {
+            const int row = min(i0 + rw, g.th + 1);
+            const bool from_next_tile = PULL && ty < g.Ty - 1 && row == g.th + 1;
+            row_tile[rw] = from_next_tile ? ys : 0;
+            row_begin[rw] = (unsigned)(from_next_tile ? 1 : row) * row_bytes;
+        }
+        auto load_row = [&](int k, int rw) {
+            return buffer_load<V>(buffer_of(const_cast<T *>(tsrc) + (plane_off(k) + row_tile[rw]), plane_bytes), col_bytes, row_begin[rw]);
+        };
         auto dst_plane = [&](int k) { return buffer_of(tdst + (long long)k * g.plane, plane_bytes); };
         auto row_start = [&](int row) { return (unsigned)row * row_bytes; };
+        // the rows just above / below this wavefront's rows, in plane k (1 .. td; other k: values unused): halo rows
+        // from the tiles before / behind in y
+        const int ym_row_own = i0 - 1, yp_row_own = min(i0 + RW, g.th + 1);
+        const bool pull_ym = PULL && ty > 0 && ym_row_own == 0, pull_yp = PULL && ty < g.Ty - 1 && yp_row_own == g.th + 1;
+        const long long ym_tile = pull_ym ? -ys : 0, yp_tile = pull_yp ? ys : 0;
+        const unsigned ym_start = row_start(pull_ym ? g.th : ym_row_own), yp_start = row_start(pull_yp ? 1 : yp_row_own);
+        auto ym_plane = [&](int k) { return buffer_of(const_cast<T *>(tsrc) + (ym_tile + (long long)k * g.plane), plane_bytes); };
+        auto yp_plane = [&](int k) { return buffer_of(const_cast<T *>(tsrc) + (yp_tile + (long long)k * g.plane), plane_bytes); };
 
         // x-edge gather: lane l < RW fetches the W edge of row l, lane 32+l the E edge - from the x-halo
         // arrays, or from the neighbouring segment's cells; the other lanes re-read the tile's first cell.
         // (selects, not branches: a branch on the lane would drag wave-uniform values into vector registers)
         const int el = lane & 31, ir = row_of(el);
         const bool fetches = el < RW, w_side = lane < 32;
-        const long long w_off = w_halo ? xm_off(g, 0, ir) : main_off(g, 0, ir, seg_c0 - 1);
-        const long long e_off = seg_has_last ? xp_off(g, 0, ir) : e_in_row ? main_off(g, 0, ir, e_col) : 0;
-        const long long w_step = w_halo ? (long long)g.rows : g.plane;
-        const long long e_step = seg_has_last ? (long long)g.rows : e_in_row ? g.plane : 0;
+        const bool w_dense = w_halo && !pull_xm, e_dense = seg_has_last && !pull_xp;    // read from the x-halo arrays
+        const long long w_off = w_dense ? xm_off(g, 0, ir) : w_halo ? main_off(g, 0, ir, g.tw - 1) - g.tile_stride
+                                                                    : main_off(g, 0, ir, seg_c0 - 1);
+        const long long e_off = e_dense ? xp_off(g, 0, ir) : seg_has_last ? main_off(g, 0, ir, 0) + g.tile_stride
+                                : e_in_row ? main_off(g, 0, ir, e_col) : 0;
+        const long long w_step = w_dense ? (long long)g.rows : g.plane;
+        const long long e_step = e_dense ? (long long)g.rows : (seg_has_last || e_in_row) ? g.plane : 0;
         const long long edge_off = fetches ? (w_side ? w_off : e_off) : 0;      // element offset in plane 0
         const long long edge_step = fetches ? (w_side ? w_step : e_step) : 0;   // and per plane
 
@@ -922,22 +974,20 @@ __global__ __launch_bounds__(WG) void sweep3d_kernel(Geo g, StripParams sp,
             for (int u = 0; u < U; ++u) {
                 const int kc = min(k + u, g.td + 1);          // clamped: stays inside the tile
                 const int kn = min(k + u + 1, g.td + 1);
-                const __amdgpu_buffer_rsrc_t above = src_plane(kn), here = src_plane(kc);
 #pragma unroll
-                for (int rw = 0; rw < RW; ++rw) P[u].up[rw] = buffer_load<V>(above, col_bytes, row_start(row_of(rw)));
-                P[u].ym = buffer_load<V>(here, col_bytes, row_start(i0 - 1));
-                P[u].yp = buffer_load<V>(here, col_bytes, row_start(row_of(RW)));
+                for (int rw = 0; rw < RW; ++rw) P[u].up[rw] = load_row(kn, rw);
+                P[u].ym = buffer_load<V>(ym_plane(kc), col_bytes, ym_start);
+                P[u].yp = buffer_load<V>(yp_plane(kc), col_bytes, yp_start);
                 P[u].edge = tsrc[edge_off + (long long)kc * edge_step];
             }
         };
 
         V below[RW], cur[RW];
         {
-            const __amdgpu_buffer_rsrc_t b0 = src_plane(k0 - 1), b1 = src_plane(k0);
 #pragma unroll
             for (int rw = 0; rw < RW; ++rw) {
-                below[rw] = buffer_load<V>(b0, col_bytes, row_start(row_of(rw)));
-                cur[rw] = buffer_load<V>(b1, col_bytes, row_start(row_of(rw)));
+                below[rw] = load_row(k0 - 1, rw);
+                cur[rw] = load_row(k0, rw);
             }
         }
 

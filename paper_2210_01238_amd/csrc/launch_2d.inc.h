@@ -10,8 +10,14 @@ static hipError_t sweep2d_dispatch(int mode, int unroll, int nt, const LaunchArg
     const dim3 grid(a.nwg), block(WG);
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
-#define JK_L(MODE_, U_, NT_) \
-    hipLaunchKernelGGL((sweep2d_kernel<T, MODE_, U_, NT_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+    // the read-only residual pass always pulls (no variant of it reads halo cells); updates in either way
+#define JK_K(MODE_, U_, NT_, PULL_) \
+    hipLaunchKernelGGL((sweep2d_kernel<T, MODE_, U_, NT_, PULL_>), grid, block, 0, a.st, a.g, a.sp, src, dst, a.partial)
+#define JK_L(MODE_, U_, NT_)                                          \
+    do {                                                              \
+        if (MODE_ == MODE_RESIDUAL || a.sp.pull) JK_K(MODE_, U_, NT_, true); \
+        else if constexpr (MODE_ != MODE_RESIDUAL) JK_K(MODE_, U_, NT_, false); \
+    } while (0)
 #define JK_NT(MODE_, U_)                      \
     do {                                      \
         if (nt & 2) JK_L(MODE_, U_, 2);       \
@@ -35,6 +41,7 @@ static hipError_t sweep2d_dispatch(int mode, int unroll, int nt, const LaunchArg
 #undef JK_U
 #undef JK_NT
 #undef JK_L
+#undef JK_K
     return hipGetLastError();
 }
 

@@ -11,13 +11,19 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
     const dim3 grid(a.nwg), block(WG);
     const T *src = (const T *)a.src;
     T *dst = (T *)a.dst;
-#define JK_K(MODE_, RW_, U_, NT_, NVEC_)                                                                            \
+#define JK_P(MODE_, RW_, U_, NT_, PULL_, NVEC_)                                                                     \
     do {                                                                                                            \
         unsigned lds_ = 0;                                                                                          \
-        const hipError_t e_ = lds_for_launch<sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>>(a, WG, &lds_);          \
+        const hipError_t e_ = lds_for_launch<sweep3d_kernel<T, MODE_, RW_, U_, NT_, PULL_, NVEC_>>(a, WG, &lds_);   \
         if (e_ != hipSuccess) return e_;                                                                            \
-        hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, NVEC_>), grid, block, lds_, a.st, a.g, a.sp, src, \
-                           dst, a.partial);                                                                         \
+        hipLaunchKernelGGL((sweep3d_kernel<T, MODE_, RW_, U_, NT_, PULL_, NVEC_>), grid, block, lds_, a.st, a.g,    \
+                           a.sp, src, dst, a.partial);                                                              \
+    } while (0)
+    // the read-only residual pass always pulls (no variant of it reads halo cells); updates in either way
+#define JK_K(MODE_, RW_, U_, NT_, NVEC_)                                                                            \
+    do {                                                                                                            \
+        if (MODE_ == MODE_RESIDUAL || a.sp.pull) JK_P(MODE_, RW_, U_, NT_, true, NVEC_);                            \
+        else if constexpr (MODE_ != MODE_RESIDUAL) JK_P(MODE_, RW_, U_, NT_, false, NVEC_);                         \
     } while (0)
     // a.aux = 1: fp32 rows of at most 128 elements, 2 elements per lane (4 rows per wavefront only)
 #define JK_L(MODE_, RW_, U_, NT_)                                                                                   \
@@ -60,6 +66,7 @@ static hipError_t sweep3d_dispatch(int mode, int rows_per_wave, int unroll, int 
 #undef JK_NT
 #undef JK_L
 #undef JK_K
+#undef JK_P
     return hipGetLastError();
 }
 
