@@ -356,6 +356,11 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    grid that fits one workgroup)
  *   "resident_spin_limit"  0 | n  polls a workgroup waits at that barrier before giving up: n - 1
  *                    beyond the first (0 = default, about 4 million: seconds)
+ *   "stack"          0 | 1 | 4 | 8  2-D stand-alone residual pass: wavefronts of a workgroup stacked over
+ *                    the same columns, 8 rows each, passing each other their border rows through LDS
+ *                    instead of loading them again (0 = choose: 8 on tiles of 1024 rows and more, else
+ *                    4; 1 = off: every wavefront loads its own border rows; default 0).  Only with
+ *                    "rows_per_strip" = 0 and "unroll" = 0, and tiles at least one band high.
  *   "cu_lds"         0 | 65536..2^20  LDS bytes of a CU that the workgroup limits of large-grid launches are
  *                    computed from (0 = the device's figure, read by jacobi_prepare; default 0).  Those
  *                    launches request (cu_lds / n - 4096) bytes of LDS they never touch so that at most

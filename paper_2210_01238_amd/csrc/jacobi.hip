@@ -55,6 +55,7 @@ struct jacobi_plan {
     // options
     int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
     int64_t resident = 1, resident_depth = 0, resident_rows = 0, resident_spin_limit = 0;
+    int64_t stack = 0;                // 2-D residual pass: wavefronts per workgroup stacked over one column segment (0: choose, 1: off, 4, 8)
     int64_t cu_lds_option = 0;        // option "cu_lds": LDS bytes per CU to compute the workgroup limits from (0: the device's)
     int64_t lds_limit_failed = 0;     // read-only: a launch dropped its workgroup limit (the occupancy query did not confirm it)
     // device state, set up once by prepare_plan() (jacobi_prepare, or the first call that touches the device)
@@ -163,6 +164,46 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     return c;
 }
 
+// The 2-D stand-alone residual pass with stacked wavefronts (residual2d_stack_kernel): wavefronts per workgroup
+// and rows per wavefront, or waves = 0 if the plan and options take the one-strip-per-wavefront kernel:
+// explicit strip options, tiles lower than one band, or a problem so small that it gets shorter strips.
+struct StackChoice { int waves = 0, rows = 0; };
+StackChoice stack_choice(const jacobi_plan *p, int mode)
+{
+    const Geo &g = p->geo;
+    StackChoice c;
+    if (mode != jk::MODE_RESIDUAL || g.ndim != 2 || p->stack == 1 || p->rows_per_strip != 0 || p->unroll != 0) return c;
+    // 8 rows per wavefront; 8 wavefronts on tall tiles, 4 otherwise (16384^2 in 2048^2 tiles: 343 us with 8, 356 with 4,
+    // 370 unstacked; 8192^2 in 128^2 tiles: 97 / 94 / 106; 4096^2: 26.9 / 26.6 / 30.2)
+    const int rows = 8;
+    const int waves = p->stack ? (int)p->stack : g.th >= 1024 ? 8 : 4;
+    if (g.th < waves * rows) return c;
+    if (p->stack == 0 && make_config(p, mode).sp.R != 16) return c;     // small problem: shorter strips, more workgroups
+    c.waves = waves; c.rows = rows;
+    return c;
+}
+
+StripParams stack_strips(const jacobi_plan *p, StackChoice c)
+{
+    const Geo &g = p->geo;
+    StripParams sp;
+    sp.R = c.rows;
+    sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * (16 / (int)p->esize));
+    sp.nblk = (int)ceil_div(g.th, c.waves * c.rows);                          // bands per tile
+    sp.nstrips = (int64_t)g.ntiles * sp.nseg * sp.nblk * jk::WAVES_PER_WG;   // partial sums: one per unit
+    sp.fused = jk::FUSED_NONE;
+    sp.xcd_chunk = p->xcd_chunk > 0 ? (int)p->xcd_chunk : 32;
+    sp.pull = 1;
+    return sp;
+}
+
+// Workgroups (= partial sums in the residual modes) of the single-step launch launch_sweep makes for `mode`.
+int64_t single_step_workgroups(const jacobi_plan *p, int mode)
+{
+    if (const StackChoice sc = stack_choice(p, mode); sc.waves) return stack_strips(p, sc).nstrips / jk::WAVES_PER_WG;
+    return ceil_div(make_config(p, mode).sp.nstrips, jk::WAVES_PER_WG);
+}
+
 int launch_checked(hipError_t e, const char *what)
 {
     if (e == hipErrorInvalidValue) return fail(JACOBI_EINVAL, "kernel variant not compiled for these options");
@@ -175,6 +216,17 @@ int launch_checked(hipError_t e, const char *what)
 int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *partial, hipStream_t st,
                  int tile0 = 0, int tile_count = 0, bool pull = false)
 {
+    if (tile_count == 0) {
+        if (const StackChoice sc = stack_choice(p, mode); sc.waves) {
+            const StripParams sp = stack_strips(p, sc);
+            const int64_t nwg = sp.nstrips / jk::WAVES_PER_WG;
+            if (nwg <= 0 || nwg > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many workgroups for one launch");
+            const jk::LaunchArgs a{(unsigned)nwg, st, p->geo, sp, src, dst, partial};
+            return launch_checked(p->lay.dtype == JACOBI_F64 ? jk::launch_stack_f64(sc.rows, sc.waves, a)
+                                                             : jk::launch_stack_f32(sc.rows, sc.waves, a),
+                                  "stacked residual kernel launch");
+        }
+    }
     SweepConfig c = make_config(p, mode);
     c.sp.pull = pull ? 1 : 0;
     if (tile_count > 0) {
@@ -622,6 +674,7 @@ int64_t max_partials(jacobi_plan *p)
         p->rows_per_wave = rpw;
         take(make_config(p, jk::MODE_RESIDUAL).sp.nstrips);
         take(make_config(p, jk::MODE_BOTH).sp.nstrips);
+        if (p->geo.ndim == 2) take(stack_strips(p, StackChoice{4, 8}).nstrips);      // the stacked kernel: never more than the others
         if (p->geo.ndim == 3)
             for (int d = jk::TP3D_MIN; d <= jk::TP3D_MAX; ++d) take(tp3d_strips(p, d, nullptr).nstrips);
     }
@@ -675,8 +728,7 @@ int check_partials(const jacobi_plan *p, int64_t nwg)
 // current and are left alone), partial sums into `partial` (at least nwg entries), result to *out.
 int residual_launches(jacobi_plan *p, void *grid, double *partial, double *out, hipStream_t st)
 {
-    const StripParams sp = make_config(p, jk::MODE_RESIDUAL).sp;
-    const int64_t nwg = ceil_div(sp.nstrips, jk::WAVES_PER_WG);
+    const int64_t nwg = single_step_workgroups(p, jk::MODE_RESIDUAL);
     int rc = launch_sweep(p, jk::MODE_RESIDUAL, grid, grid, partial, st, 0, 0, /*pull=*/true);
     if (rc) return rc;
     hipLaunchKernelGGL(jk::residual_final_kernel, dim3(1), dim3(1024), 0, st, partial, (long long)nwg, out);
@@ -688,7 +740,7 @@ int residual_common(jacobi_plan *p, void *grid, double *result_dev, hipStream_t 
 {
     int rc = prepare_plan(p);
     if (rc) return rc;
-    const int64_t nwg = ceil_div(make_config(p, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
+    const int64_t nwg = single_step_workgroups(p, jk::MODE_RESIDUAL);
     rc = check_partials(p, nwg);
     if (rc) return rc;
     // the last slot of the scratch holds the result for the host variant
@@ -722,6 +774,7 @@ int64_t *option_slot(jacobi_plan *p, const char *key)
     if (!strcmp(key, "resident_rows")) return &p->resident_rows;
     if (!strcmp(key, "resident_spin_limit")) return &p->resident_spin_limit;
     if (!strcmp(key, "cu_lds")) return &p->cu_lds_option;
+    if (!strcmp(key, "stack")) return &p->stack;
     return nullptr;
 }
 
@@ -880,7 +933,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         // small 2-D grid: every iteration inside one launch; the residual of `in`, if asked for, from the
         // stand-alone reduction first
         if (residual_in_dev) {
-            const int64_t nwg = ceil_div(make_config(plan, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
+            const int64_t nwg = single_step_workgroups(plan, jk::MODE_RESIDUAL);
             rc = check_partials(plan, nwg);
             if (rc) return rc;
             rc = residual_launches(plan, in, plan->partial, residual_in_dev, st);
@@ -902,7 +955,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     const PassChoice first = choose_pass(plan, iters);
     int64_t nwg_res = 0;
     if (residual_in_dev) {
-        const int64_t strips = first.kernel == 0   ? make_config(plan, jk::MODE_BOTH).sp.nstrips
+        const int64_t strips = first.kernel == 0   ? single_step_workgroups(plan, jk::MODE_BOTH) * jk::WAVES_PER_WG
                                : first.kernel == 1 ? t2_strips(plan).nstrips
                                : first.kernel == 2 ? tp_strips(plan, first.depth).nstrips
                                : first.kernel == 4 ? tc3d_strips(plan, first.depth, nullptr).nstrips
@@ -1177,7 +1230,7 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
 {
     if (!plan || !grid || !result_dev) return fail(JACOBI_EINVAL, "NULL argument");
     if (misaligned(grid)) return fail(JACOBI_EINVAL, "grids must be 16-byte aligned");
-    const int64_t nwg = ceil_div(make_config(plan, jk::MODE_RESIDUAL).sp.nstrips, jk::WAVES_PER_WG);
+    const int64_t nwg = single_step_workgroups(plan, jk::MODE_RESIDUAL);
     if (nwg > JACOBI_NOALLOC_MAX_PARTIALS) {
         char msg[160];
         snprintf(msg, sizeof(msg), "residual_norm_noalloc: the plan's residual launch has %lld workgroups, the static "
@@ -1206,10 +1259,12 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
     int64_t *slot = option_slot(plan, key);
     if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : slot == &plan->resident_depth ? 31 : slot == &plan->resident_rows ? jk::RES_MAX_RW : slot == &plan->resident_spin_limit ? (1LL << 31) : slot == &plan->cu_lds_option ? (1LL << 20) : 1;
+    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : slot == &plan->resident_depth ? 31 : slot == &plan->resident_rows ? jk::RES_MAX_RW : slot == &plan->resident_spin_limit ? (1LL << 31) : slot == &plan->cu_lds_option ? (1LL << 20) : slot == &plan->stack ? 8 : 1;
     if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
     if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
+    if (slot == &plan->stack && value != 0 && value != 1 && value != 4 && value != 8)
+        return fail(JACOBI_EINVAL, "stack must be 0, 1, 4 or 8");
     if (slot == &plan->nontemporal && value == 1) return fail(JACOBI_EINVAL, "nontemporal must be 0 or 2");
     if (slot == &plan->tblock && value < 1) return fail(JACOBI_EINVAL, "tblock must be 1..12");
     if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)

@@ -412,6 +412,114 @@ __global__ __launch_bounds__(WG) void sweep2d_kernel(Geo g, StripParams sp,
 }
 
 // ------------------------------------------------------------------------------------
+// 2-D stand-alone residual pass, wavefronts of a workgroup STACKED: the NW wavefronts of a workgroup take NW
+// consecutive R-row strips of the same 64*NV columns, and the row just above / below a wavefront's strip - the
+// last / first row of its neighbour in the workgroup - comes through LDS instead of being loaded again.  A
+// workgroup then reads R*NW + 2 rows for R*NW rows (sweep2d_kernel: R + 2 for R; the two extra rows are the
+// neighbouring strips' and only come from cache if those run on the same XCD at the same time).  For the
+// read-only pass this is worth 6-12 % (16384^2: 369 -> 346 us, 128^2 tiles: 107 -> 94 us); the UPDATE was built
+// the same way and ran 4 % slower than with independent wavefronts (the barrier makes four wavefronts read, then
+// four write), so it keeps sweep2d_kernel.  Always pulls: cells beyond a tile are read from the neighbouring
+// tiles' edge cells (see sweep2d_kernel).  Work unit = (tile, band of R*NW rows, column segment), one workgroup
+// each: every wavefront reaches the barrier; a wavefront whose rows lie beyond the tile (ragged last band)
+// loads clamped rows and adds nothing.  Same terms as everywhere; one partial sum per workgroup.
+// ------------------------------------------------------------------------------------
+template <typename T, int R, int NW>
+__global__ __launch_bounds__(NW * WAVE) void residual2d_stack_kernel(Geo g, StripParams sp, const T *__restrict__ src,
+                                                                     double *__restrict__ partial)
+{
+    using V = typename Vec<T>::type;
+    constexpr int NV = Vec<T>::N;
+    static_assert(R >= 1 && R <= 32, "the edge gather gives each side 32 lanes");
+    __shared__ V xrow[NW][2][WAVE];           // [wavefront][its first / last row][lane]
+    __shared__ double red[NW];
+
+    const int lane = threadIdx.x % WAVE;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const long long lwg = xcd_logical_wg(sp.xcd_chunk);        // the work unit: the grid has exactly one workgroup each
+    double acc = 0.0;
+
+    const int per_tile = sp.nblk * sp.nseg;                    // sp.nblk: bands per tile
+    const int t = (int)(lwg / per_tile);
+    const int rem = (int)(lwg - (long long)t * per_tile);
+    const int band = rem / sp.nseg, seg = rem - band * sp.nseg;
+    const int ty = t / g.Tx, tx = t - ty * g.Tx;
+    const int r0 = 1 + (band * NW + wave) * R;                 // may lie beyond the tile (ragged last band)
+    const int r1 = min(g.th, r0 + R - 1);
+    const int col0 = (seg * WAVE + lane) * NV;
+    const bool active = col0 < g.pitch;
+    const int last = g.tw - 1;
+    const bool has_last = active && col0 <= last && last < col0 + NV;
+    const int jlast = last - col0;
+    const int seg_c0 = seg * WAVE * NV;
+    const bool seg_has_last = seg_c0 <= last && last < seg_c0 + WAVE * NV;
+    const bool w_halo = seg_c0 == 0;
+    const int e_col = seg_c0 + WAVE * NV;
+    const bool e_in_row = e_col < g.pitch;
+    const T *tsrc = src + (long long)t * g.tile_stride;
+    const long long ystep = (long long)g.Tx * g.tile_stride;
+    const bool pull_ym = ty > 0, pull_yp = ty < g.Ty - 1, pull_xm = tx > 0, pull_xp = tx < g.Tx - 1;
+    // first cell of row `row` (clamped to 0 .. th+1) as it has to be read: halo rows from the tiles above / below
+    auto row_ptr = [&](int row) -> const T * {
+        row = min(row, g.th + 1);
+        if (row == 0 && pull_ym) return tsrc - ystep + main_off(g, 0, g.th, 0);
+        if (row == g.th + 1 && pull_yp) return tsrc + ystep + main_off(g, 0, 1, 0);
+        return tsrc + main_off(g, 0, row, 0);
+    };
+
+    // rows r0-1 .. r0+R: index 0 and R+1 are the neighbours' (LDS, or memory at the ends of the band)
+    V row[R + 2];
+#pragma unroll
+    for (int q = 1; q <= R; ++q) row[q] = active ? *(const V *)(row_ptr(r0 + q - 1) + col0) : V(0);
+    row[0] = V(0);
+    row[R + 1] = V(0);
+    if (wave == 0 && active) row[0] = *(const V *)(row_ptr(r0 - 1) + col0);
+    if (wave == NW - 1 && active) row[R + 1] = *(const V *)(row_ptr(r0 + R) + col0);
+    // the x-edge cells of the strip: lane l < R -> W edge of row r0+l, lane 32+l -> E edge
+    T edge = T(0);
+    {
+        const int el = lane & 31;
+        if (el < R) {
+            const int rc = min(r0 + el, g.th + 1);
+            if (lane < 32)
+                edge = !w_halo ? tsrc[main_off(g, 0, rc, seg_c0 - 1)]
+                       : pull_xm ? tsrc[main_off(g, 0, rc, g.tw - 1) - g.tile_stride] : tsrc[xm_off(g, 0, rc)];
+            else if (seg_has_last)
+                edge = pull_xp ? tsrc[main_off(g, 0, rc, 0) + g.tile_stride] : tsrc[xp_off(g, 0, rc)];
+            else if (e_in_row) edge = tsrc[main_off(g, 0, rc, e_col)];
+        }
+    }
+    xrow[wave][0][lane] = row[1];
+    xrow[wave][1][lane] = row[R];
+    __syncthreads();
+    if (wave > 0) row[0] = xrow[wave > 0 ? wave - 1 : 0][1][lane];
+    if (wave < NW - 1) row[R + 1] = xrow[wave < NW - 1 ? wave + 1 : wave][0][lane];
+
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const V prev = row[u], cur = row[u + 1], nxt = row[u + 2];
+        const T ew = lane_value(edge, u), ee = lane_value(edge, 32 + u);
+        const T left = from_prev_lane(cur[NV - 1], ew);    // lane 0 keeps the W edge
+        const T right = from_next_lane(cur[0], ee);        // lane 63 keeps the E edge
+        if (r0 + u <= r1) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const T w = j == 0 ? left : cur[j - 1];
+                T e = j == NV - 1 ? right : cur[j + 1];
+                if (has_last && j == jlast) e = ee;
+                const T we = w + e;
+                const T sn = prev[j] + nxt[j];
+                const T res = (we + sn) - Coef<T>::four * cur[j];
+                const double rd = (double)res;
+                if (col0 + j <= last) acc += rd * rd;
+            }
+        }
+    }
+    const double tot = wg_sum(acc, red);
+    if (threadIdx.x == 0) partial[lwg] = tot;
+}
+
+// ------------------------------------------------------------------------------------
 // 2-D, two time steps per pass over memory (temporal blocking, T = 2).
 //
 // A strip produces RT rows x 64*NV columns of u(t+2).  It needs u(t) on RT+4 rows and 2 more

@@ -72,6 +72,10 @@ hipError_t launch_sweep2d_f32(int mode, int unroll, int nt, const LaunchArgs &a)
 // rows_per_wave 1,2,4; unroll 1,2,4
 hipError_t launch_sweep3d_f64(int mode, int rows_per_wave, int unroll, int nt, const LaunchArgs &a);
 hipError_t launch_sweep3d_f32(int mode, int rows_per_wave, int unroll, int nt, const LaunchArgs &a);
+// 2-D residual pass with the wavefronts of a workgroup stacked (rows 8 per wavefront, waves 4 or 8 per
+// workgroup); a.nwg = work units (tile x band x column segment), a.sp.nblk = bands per tile
+hipError_t launch_stack_f64(int rows, int waves, const LaunchArgs &a);
+hipError_t launch_stack_f32(int rows, int waves, const LaunchArgs &a);
 // two iterations per pass (8-row strips); mode MODE_UPDATE or MODE_BOTH
 constexpr int T2_ROWS = 8;
 hipError_t launch_t2(bool f64, int mode, const LaunchArgs &a);

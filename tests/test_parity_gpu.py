@@ -93,12 +93,41 @@ def test_fp32_within_tolerance(H, oracle_mod, dims, tiles, iters, every, fused):
     dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=0, fused=0, rows_per_strip=5), dict(unroll=16, rows_per_strip=16),
     dict(xcd_chunk=1), dict(xcd_chunk=3, unroll=1), dict(xcd_chunk=1000),
     dict(rows_per_wave=1), dict(rows_per_wave=2, unroll=4), dict(rows_per_wave=4, unroll=1, rows_per_strip=3),
+    dict(stack=1), dict(stack=4), dict(stack=8, xcd_chunk=5),
 ])
 def test_options_do_not_change_results(H, oracle_mod, opts):
     a = random_padded((150, 260), seed=3)
     check(*run_case(H, oracle_mod, a, (3, 2), 10, 5, **opts))
     b = random_padded((20, 18, 40), seed=4)
     check(*run_case(H, oracle_mod, b, (2, 3, 2), 6, 3, **opts))
+
+
+@pytest.mark.parametrize("dims,tiles", [
+    ((150, 260), (3, 2)),      # tiles 50 x 130: second band ragged (18 rows), two column segments, ragged width
+    ((66, 128), (2, 1)),       # tiles 33 rows: one row in the second band
+    ((64, 64), (1, 1)),        # exactly one band of 4 wavefronts (two of 8), half-empty lanes
+    ((256, 100), (2, 2)),      # 128-row tiles: 4 bands of 32 / 2 of 64, tile seam in x and y
+    ((520, 384), (1, 3)),      # 520 rows: 16 full bands of 32 + 8 rows
+])
+@pytest.mark.parametrize("stack", [4, 8])
+def test_stacked_residual_pass(H, oracle_mod, dims, tiles, stack):
+    """The 2-D residual pass with the wavefronts of a workgroup stacked (border rows through LDS), forced on small
+    shapes: against the oracle and bit for bit against the unstacked pass on the same grid."""
+    for dtype in (np.float64, np.float32):
+        a = random_padded(dims, dtype=dtype, seed=sum(dims) + stack)
+        ref, _ = oracle_mod.run(a, 3)
+        want = oracle_mod.residual(ref)
+        r = H.JacobiRun(dims, tiles, dtype, stack=stack)
+        try:
+            r.load(a)
+            r.sweep(3)                       # leaves the inter-tile halo cells of the result to the pushes
+            got = r.residual()
+            r.set_option("stack", 1)
+            plain = r.residual()
+        finally:
+            r.close()
+        assert abs(got - want) <= RES_RTOL[np.dtype(dtype)] * want, (dims, tiles, stack, got, want)
+        assert abs(got - plain) <= 1e-14 * plain           # other summation tree, same terms
 
 
 def test_c1_workload_and_stored_values(H, oracle_mod):
