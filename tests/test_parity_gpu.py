@@ -130,6 +130,70 @@ def test_stacked_residual_pass(H, oracle_mod, dims, tiles, stack):
         assert abs(got - plain) <= 1e-14 * plain           # other summation tree, same terms
 
 
+def poison_inter_tile_halos(H, r):
+    """NaN into every halo cell that has a neighbouring tile behind it (faces with their edges; Dirichlet
+    halos untouched), and into the x send arrays: what a caller may leave there."""
+    import torch
+    lay = H.B.jacobi_get_layout(r.plan)
+    Tz, Ty, Tx = lay.tiles
+    td, th, tw = lay.tile
+    tdt = torch.float64 if r.np_dtype == np.float64 else torch.float32
+    raw = r.cur.view(tdt)
+    host = raw.cpu().numpy().copy()
+    rows, npl = th + 2, lay.nplanes
+    for t in range(lay.ntiles):
+        tz, ty, tx = t // (Ty * Tx), (t // Tx) % Ty, t % Tx
+        base = t * lay.tile_stride
+        main = host[base: base + npl * rows * lay.pitch].reshape(npl, rows, lay.pitch)
+        xm = host[base + lay.xhalo_offset: base + lay.xhalo_offset + npl * rows].reshape(npl, rows)
+        xp = host[base + lay.xhalo_offset + lay.xhalo_pitch: base + lay.xhalo_offset + lay.xhalo_pitch + npl * rows].reshape(npl, rows)
+        ks = slice(1, td + 1) if lay.ndim == 3 else slice(0, 1)
+        if ty > 0: main[ks, 0, :tw] = np.nan
+        if ty < Ty - 1: main[ks, th + 1, :tw] = np.nan
+        if tx > 0: xm[ks, 1:th + 1] = np.nan
+        if tx < Tx - 1: xp[ks, 1:th + 1] = np.nan
+        if lay.ndim == 3:
+            if tz > 0: main[0, 1:th + 1, :tw] = np.nan
+            if tz < Tz - 1: main[td + 1, 1:th + 1, :tw] = np.nan
+        host[base + lay.xsend_offset: base + lay.xsend_offset + 2 * lay.xhalo_pitch] = np.nan
+    raw.copy_(torch.from_numpy(host))
+
+
+@pytest.mark.parametrize("dims,tiles", [
+    ((96, 200), (3, 2)), ((150, 260), (3, 2)), ((48, 48), (48, 48)), ((64, 1030), (2, 2)),
+    ((24, 20, 36), (2, 2, 3)), ((12, 26, 260), (2, 2, 2)),      # 13-row tiles: ragged last row group of 4
+    ((9, 15, 40), (3, 5, 2)), ((8, 8, 8), (8, 8, 8)),
+])
+@pytest.mark.parametrize("opts", [dict(), dict(fused=0), dict(tblock=4)])
+def test_stale_halo_cells_are_never_read_as_data(H, oracle_mod, dims, tiles, opts):
+    """jacobi_sweep, jacobi_sweep_residual and residual_norm must not depend on what the inter-tile halo cells
+    (or the x send arrays) hold when they are called: the first update of a call and the residual pass read
+    the neighbouring tiles' edge cells themselves (with fused = 0 an exchange kernel runs first)."""
+    import torch
+    for dtype in (np.float64, np.float32):
+        a = random_padded(dims, dtype=dtype, seed=sum(dims))
+        r = H.JacobiRun(dims, tiles, dtype, **opts)
+        try:
+            r.load(a)
+            poison_inter_tile_halos(H, r)
+            res0 = r.residual()                                   # residual pass on poisoned halos
+            poison_inter_tile_halos(H, r)
+            dev = torch.zeros(1, dtype=torch.float64, device="cuda")
+            r.sweep_residual(5, dev)                              # first update (with the fused residual) on poisoned halos
+            poison_inter_tile_halos(H, r)
+            r.sweep(4)
+            poison_inter_tile_halos(H, r)
+            res9 = r.residual()
+            out = r.fetch()
+        finally:
+            r.close()
+        ref, ref_res = oracle_mod.run(a, 9, 9)
+        check(out, [res9], ref, ref_res)
+        want0 = oracle_mod.residual(a)
+        tol = RES_RTOL[np.dtype(dtype)]
+        assert abs(res0 - want0) <= tol * want0 and abs(dev.item() - want0) <= tol * want0
+
+
 def test_c1_workload_and_stored_values(H, oracle_mod):
     from test_oracle_pins import read_golden_c1
     w = gen.WORKLOADS["C1"]
