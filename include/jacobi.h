@@ -301,9 +301,12 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
  *                    through; 0 = choose from the shape: 8 rows / 16 planes for single steps,
  *                    up to 128 rows / the tile depth for blocked passes (default 0)
- *   "nontemporal"    0 | 2   2 = results are written with streaming (non-temporal) stores
- *                    (default 2).  Streaming loads were measured slower (border rows are
- *                    re-read from cache) and are not offered.  Blocked passes always stream.
+ *   "nontemporal"    0 | 1 | 2   how single-step updates store their results: 2 = streaming
+ *                    (non-temporal) stores, 0 = plain stores, 1 = choose (default): plain when both
+ *                    grids fit the Infinity Cache (grids of at most 64 MiB: the next iteration then
+ *                    loads them from the cache), streaming beyond.  Streaming loads were measured
+ *                    slower (border rows are re-read from cache) and are not offered.  Blocked passes
+ *                    always stream.
  *   "unroll"         0 | 1 | 2 | 4 | 8  rows (planes) whose loads a wavefront issues back to
  *                    back before computing (3-D: planes per trip of the load pipeline); 0 = choose:
  *                    2-D the whole strip, up to 8; 3-D 2, or 1 on fp64 grids of 1 GiB and more

@@ -42,6 +42,7 @@ constexpr int MAX_TASK_STREAMS = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 constexpr int64_t LARGE_GRID_BYTES = 1LL << 30;   // grids from this size on get the workgroup-per-CU limits
+constexpr int64_t CACHED_GRID_BYTES = 64LL << 20; // two grids of at most this size each stay in the 256 MB Infinity Cache
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -53,7 +54,7 @@ struct jacobi_plan {
     Geo geo;
     size_t esize;
     // options
-    int64_t fused = 1, rows_per_strip = 0, nontemporal = 2, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
+    int64_t fused = 1, rows_per_strip = 0, nontemporal = 1, profile = 0, unroll = 0, xcd_chunk = 0, rows_per_wave = 0, tblock = 1, cooperative = 1;
     int64_t resident = 1, resident_depth = 0, resident_rows = 0, resident_spin_limit = 0;
     int64_t stack = 0;                // 2-D residual pass: wavefronts per workgroup stacked over one column segment (0: choose, 1: off, 4, 8)
     int64_t cu_lds_option = 0;        // option "cu_lds": LDS bytes per CU to compute the workgroup limits from (0: the device's)
@@ -88,6 +89,16 @@ struct SweepConfig {
     int lane_elems;      // elements per lane: 16 bytes' worth, or 2 for narrow fp32 rows in 3-D
     bool whole_cu;       // 3-D update of a large grid: one workgroup per CU
 };
+
+// Store flavour of the single-step updates (bit 2 of the kernels' NT argument: streaming stores): the option, or,
+// left to the library (1), streaming unless both grids fit the Infinity Cache - there a plain store keeps the
+// result on-chip for the next iteration's loads (2048^2: 15.5 -> 11.3 us per iteration), while on grids beyond
+// it plain stores lose (6144^2: 102 -> 110 us) because the written lines push out what is still to be read.
+int store_flavour(const jacobi_plan *p)
+{
+    if (p->nontemporal != 1) return (int)p->nontemporal;
+    return p->lay.grid_bytes <= CACHED_GRID_BYTES ? 0 : 2;
+}
 
 // Consecutive workgroups one XCD takes (jk::xcd_logical_wg): the option, or 8 - 16 for launches that run one
 // workgroup per CU (measured: 512^3 0.401 -> 0.396 ms, 1024 x 1024 x 768 2.40 -> 2.36; 24 and more: as 8).
@@ -140,7 +151,8 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
         // mid-sized 2-D grids: at 8 rows a 4096^2 grid gives each CU only ~3 rounds of workgroups
         // and the last round runs half empty; 4-row strips measure 8 % faster there
         if (!d3 && mode != jk::MODE_RESIDUAL && (int64_t)ceil_div(extent, R) * lanes_of_work < 24576) R = 4;
-        while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < 4096) R /= 2;
+        // (3-D: 16-plane strips until fewer than 2048 would be left: 256^3 in 128^3 tiles 57.4 -> 53.9 us with 16 instead of 8)
+        while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < (d3 ? 2048 : 4096)) R /= 2;
     }
     if (R > extent) R = extent;
     sp.R = R;
@@ -245,7 +257,7 @@ int launch_sweep(jacobi_plan *p, int mode, const void *src, void *dst, double *p
     a.per_cu = 1;
     a.limit_failed = &p->lds_limit_failed;
     const bool f64 = p->lay.dtype == JACOBI_F64;
-    const int nt = (int)p->nontemporal;
+    const int nt = store_flavour(p);
     hipError_t e;
     if (p->geo.ndim == 2)
         e = f64 ? jk::launch_sweep2d_f64(mode, c.unroll, nt, a) : jk::launch_sweep2d_f32(mode, c.unroll, nt, a);
@@ -1265,7 +1277,6 @@ int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
         return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
     if (slot == &plan->stack && value != 0 && value != 1 && value != 4 && value != 8)
         return fail(JACOBI_EINVAL, "stack must be 0, 1, 4 or 8");
-    if (slot == &plan->nontemporal && value == 1) return fail(JACOBI_EINVAL, "nontemporal must be 0 or 2");
     if (slot == &plan->tblock && value < 1) return fail(JACOBI_EINVAL, "tblock must be 1..12");
     if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)
         return fail(JACOBI_EINVAL, "rows_per_wave must be 0, 1, 2 or 4");

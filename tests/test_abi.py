@@ -94,7 +94,7 @@ def test_null_and_argument_errors_without_device(J):
                  lambda: J.residual_norm(p, 0, 256), lambda: J.residual_norm(p, 256, 0),
                  lambda: J.jacobi_scatter(p, 0, 256), lambda: J.jacobi_gather(p, 256, 0),
                  lambda: J.jacobi_set_option(p, "no_such_option", 1),
-                 lambda: J.jacobi_set_option(p, "fused", 2), lambda: J.jacobi_set_option(p, "nontemporal", 1),
+                 lambda: J.jacobi_set_option(p, "fused", 2), lambda: J.jacobi_set_option(p, "nontemporal", 3),
                  lambda: J.jacobi_set_option(p, "tblock", 0), lambda: J.jacobi_set_option(p, "tblock", 13),
                  lambda: J.jacobi_set_option(p, "unroll", 3),
                  lambda: J.jacobi_set_option(p, "rows_per_strip", 5000),

@@ -90,7 +90,7 @@ def test_fp32_within_tolerance(H, oracle_mod, dims, tiles, iters, every, fused):
 
 @pytest.mark.parametrize("opts", [
     dict(rows_per_strip=1), dict(rows_per_strip=3, unroll=2), dict(rows_per_strip=7, fused=0, unroll=4),
-    dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=0, fused=0, rows_per_strip=5), dict(unroll=16, rows_per_strip=16),
+    dict(rows_per_strip=4096, unroll=8), dict(nontemporal=0), dict(nontemporal=2), dict(nontemporal=0, fused=0, rows_per_strip=5), dict(unroll=16, rows_per_strip=16),
     dict(xcd_chunk=1), dict(xcd_chunk=3, unroll=1), dict(xcd_chunk=1000),
     dict(rows_per_wave=1), dict(rows_per_wave=2, unroll=4), dict(rows_per_wave=4, unroll=1, rows_per_strip=3),
     dict(stack=1), dict(stack=4), dict(stack=8, xcd_chunk=5),

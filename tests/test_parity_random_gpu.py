@@ -29,7 +29,7 @@ def make_cases(ndim, count, seed, blocked_3d=False):
                     rows_per_strip=int(rng.choice([0, 0, 1, 2, 3, 5, 8, 16, 33, 128])),
                     unroll=int(rng.choice([0, 0, 1, 2, 4, 8] + ([16] if ndim == 2 else []))),
                     xcd_chunk=int(rng.choice([0, 1, 2, 8, 8, 64])),
-                    nontemporal=int(rng.choice([0, 2, 2])))
+                    nontemporal=int(rng.choice([0, 1, 2])))
         if ndim == 2:
             opts["tblock"] = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8, 10, 12]))
         else:
