@@ -133,3 +133,80 @@ def make_medium_cases(count, seed):
 @pytest.mark.parametrize("n,case", list(enumerate(make_medium_cases(40, 20221005))))
 def test_random_medium_sizes(H, oracle_mod, n, case):
     run_random(H, oracle_mod, case, 5000 + n)
+
+
+def make_resident_cases(count, seed):
+    """Shapes the all-iterations-in-one-launch path takes (rows of at most 2 KiB, tile widths a multiple of
+    16 bytes), with random phase depths and rows per wavefront."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for n in range(count):
+        f32 = n % 4 == 3
+        nv = 4 if f32 else 2
+        width = nv * int(rng.integers(1, 128 + 1))
+        dims = (int(rng.integers(1, 1500)), width)
+        ty = int(rng.choice(divisors(dims[0])))
+        tx = int(rng.choice([d for d in divisors(width) if (width // d) % nv == 0]))
+        iters = int(rng.integers(1, 70))
+        every = int(rng.integers(1, iters + 1))
+        opts = dict(resident=1, resident_depth=int(rng.choice([0, 0, 1, 2, 5, 9, 14, 20, 31])),
+                    resident_rows=int(rng.choice([0, 0, 1, 2, 3, 4])))
+        cases.append((dims, (ty, tx), iters, every, opts, bool(rng.integers(0, 2)), np.float32 if f32 else np.float64))
+    return cases
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_resident_cases(48, 20221006))))
+def test_random_resident(H, oracle_mod, n, case):
+    """jacobi_sweep calls that run as one launch: random small 2-D shapes, tilings, cadences, phase geometry."""
+    dims, tiles, iters, every, opts, fuse_res, dtype = case
+    r = H.JacobiRun(dims, tiles, dtype, **opts)
+    try:
+        assert len(H.B.jacobi_pass_schedule(r.plan, iters)) < iters or iters == 1 or opts["resident_depth"] == 1
+    finally:
+        r.close()
+    a = random_padded(dims, dtype=dtype, seed=6000 + n)
+    if not fuse_res:
+        return check(*run_case(H, oracle_mod, a, tiles, iters, every, **opts))
+    r = H.JacobiRun(dims, tiles, dtype, **opts)
+    try:
+        r.load(a)
+        res = r.run(iters, every, fuse_residual=True)
+        out = r.fetch()
+    finally:
+        r.close()
+    ref, ref_res = oracle_mod.run(a, iters, every)
+    check(out, res, ref, ref_res)
+
+
+def make_stack_cases(count, seed):
+    """2-D shapes for the stand-alone residual pass with stacked wavefronts (tiles at least a band of 8 rows high)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for n in range(count):
+        ty, tx = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        th, tw = int(rng.integers(8, 300)), int(rng.integers(1, 500))
+        cases.append(((ty * th, tx * tw), (ty, tx), int(rng.integers(1, 6)), int(rng.choice([4, 8])),
+                      np.float32 if n % 3 == 2 else np.float64))
+    return cases
+
+
+@pytest.mark.parametrize("n,case", list(enumerate(make_stack_cases(36, 20221007))))
+def test_random_stacked_residual(H, oracle_mod, n, case):
+    """residual_norm through the stacked kernel after a few updates, against the oracle and against the
+    unstacked kernel (same terms in another order: tolerance, not bits)."""
+    dims, tiles, iters, stack, dtype = case
+    a = random_padded(dims, dtype=dtype, seed=7000 + n)
+    ref, ref_res = oracle_mod.run(a, iters, iters)
+    r = H.JacobiRun(dims, tiles, dtype, stack=stack)
+    try:
+        r.load(a)
+        r.sweep(iters)
+        res = r.residual()
+        assert r.residual() == res                      # reproducible to the bit
+        out = r.fetch()
+        r.set_option("stack", 1)
+        plain = r.residual()
+    finally:
+        r.close()
+    check(out, [res], ref, ref_res)
+    assert abs(plain - res) <= (1e-12 if dtype == np.float64 else 1e-5) * max(abs(res), 1e-300)
