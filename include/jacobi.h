@@ -211,8 +211,11 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
  * iters / residual_every doubles; may be NULL if that is 0; residual_every = 0: no norms).
  * Equivalent to blocks of jacobi_sweep(residual_every) each followed by residual_norm, but each norm
  * except the last is taken from inside the first update of the NEXT block (jacobi_sweep_residual), so
- * it costs no pass over memory of its own; values agree up to summation order.  in / out / final as
- * for jacobi_sweep (the buffers swap roles once per pass of every block: read *final).
+ * it costs no pass over memory of its own; values agree up to summation order.  The blocks after the
+ * first also start from what the block before left in the two grids (the Dirichlet ring in both, the
+ * halo cells its last update pushed), where separate calls would copy the ring and fetch the
+ * neighbours' edge cells again.  in / out / final as for jacobi_sweep (the buffers swap roles once per
+ * pass of every block: read *final).
  * Asynchronous on `stream`; allocates and synchronises nothing once the plan is prepared.
  * Errors: EINVAL, ENOMEM, EHIP.
  */

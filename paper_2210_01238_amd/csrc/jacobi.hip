@@ -927,8 +927,15 @@ int halo_exchange(jacobi_plan *plan, void *grid, void *stream)
     return launch_exchange(plan, grid, (hipStream_t)stream);
 }
 
+// What a block of iterations leaves behind for the block that jacobi_run enqueues next on the same two grids.
+struct RunCarry {
+    bool ring_done = false;         // both grids carry the Dirichlet ring
+    bool halos_current = false;     // the inter-tile halo cells of the block's result hold its own edge cells
+    bool x_packed = false;          // its x send arrays hold its first / last columns
+};
+
 static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipStream_t st, void **final,
-                        double *residual_in_dev)
+                        double *residual_in_dev, RunCarry *carry = nullptr)
 {
     int rc = prepare_plan(plan);
     if (rc) return rc;
@@ -951,8 +958,11 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
             rc = residual_launches(plan, in, plan->partial, residual_in_dev, st);
             if (rc) return rc;
         }
-        rc = launch_boundary_sync(plan, in, out, st);
-        if (rc) return rc;
+        if (!(carry && carry->ring_done)) {
+            rc = launch_boundary_sync(plan, in, out, st);
+            if (rc) return rc;
+        }
+        if (carry) *carry = RunCarry{true, false, false};      // the kernel stores rows only
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
         rc = launch_resident(plan, rc_res, in, out, st);
@@ -977,12 +987,14 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         if (rc) return rc;
     }
 
-    rc = launch_boundary_sync(plan, in, out, st);
-    if (rc) return rc;
+    if (!(carry && carry->ring_done)) {
+        rc = launch_boundary_sync(plan, in, out, st);
+        if (rc) return rc;
+    }
     void *src = in, *dst = out;
     int k = 0;
-    bool halos_current = false;     // inter-tile halos of src hold src's own edge cells
-    bool x_packed = false;          // src's x send arrays hold its first / last columns (the last pass packed them)
+    bool halos_current = carry && carry->halos_current;     // inter-tile halos of src hold src's own edge cells
+    bool x_packed = carry && carry->x_packed;   // src's x send arrays hold its first / last columns (the last pass packed them)
     while (k < iters) {
         const PassChoice pc = choose_pass(plan, iters - k);
         const bool with_res = k == 0 && residual_in_dev;
@@ -1018,6 +1030,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
         void *t = src; src = dst; dst = t;
         k += pc.depth;
     }
+    if (carry) *carry = RunCarry{true, halos_current, x_packed};
     if (final) *final = src;
     return JACOBI_OK;
 }
@@ -1184,11 +1197,12 @@ int jacobi_run(jacobi_plan *plan, void *in, void *out, int iters, int residual_e
     hipStream_t st = (hipStream_t)stream;
     void *cur = in, *other = out;
     int done = 0, pending = -1;      // pending: index of a residual still owed for the grid in `cur`
+    RunCarry carry;                  // blocks after the first start from what the one before left in the grids
     while (done < iters) {
         const int n = std::min(residual_every > 0 ? residual_every : iters, iters - done);
         void *fin = cur;
         // the norm of the grid a block of iterations produced is taken from the first update of the next block
-        int rc = sweep_common(plan, cur, other, n, st, &fin, pending >= 0 ? residuals_dev + pending : nullptr);
+        int rc = sweep_common(plan, cur, other, n, st, &fin, pending >= 0 ? residuals_dev + pending : nullptr, &carry);
         if (rc) return rc;
         pending = -1;
         if (fin != cur) std::swap(cur, other);
