@@ -355,8 +355,12 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    swap the two grids like passes do (jacobi_pass_schedule lists them; read *final).
  *                    The barrier's wait is bounded: if the workgroups cannot all be resident (the device
  *                    is busy with other work for seconds) the launch still ends and writes NaN.
+ *                    The launch is the whole call: it carries the Dirichlet ring over itself, and in
+ *                    jacobi_run it also delivers the residual norm of the grid it produced (NaN if the
+ *                    barrier gave up).  Two launches of one plan must not overlap in time: they share
+ *                    the barrier words in the plan's scratch.
  *                    Ignores "tblock"; inter-tile halo cells of the result are left alone.
- *   "resident_depth" 0 | 1..31  iterations between two barriers of that kernel (0 = choose: 16, evened
+ *   "resident_depth" 0 | 1..31  iterations between two barriers of that kernel (0 = choose: 20, evened
  *                    out over the call)
  *   "resident_rows"  0 | 1..4   rows each of its wavefronts keeps (0 = choose: 4, or just enough for a
  *                    grid that fits one workgroup)

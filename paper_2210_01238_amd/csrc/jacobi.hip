@@ -491,9 +491,12 @@ struct ResidentChoice {
 };
 
 constexpr int RESIDENT_DEFAULT_DEPTH = 20;
+constexpr int RESIDENT_MAX_WORKGROUPS = 1024;           // the plan's scratch holds a partial sum for each
 constexpr unsigned RESIDENT_DEFAULT_SPIN = 1u << 22;    // polls of about a microsecond each: seconds
 
-ResidentChoice resident_choice(const jacobi_plan *p, int iters)
+// with_residual: the kernel is also to deliver the residual norm of its result, for which the rows next to a
+// workgroup's own must still be exact after the deepest phase: one more ghost row per side.
+ResidentChoice resident_choice(const jacobi_plan *p, int iters, bool with_residual = false)
 {
     ResidentChoice c;
     const Geo &g = p->geo;
@@ -516,8 +519,9 @@ ResidentChoice resident_choice(const jacobi_plan *p, int iters)
     }
     if (rw == 0) rw = max_rw;
     const int held = jk::RES_WAVES * rw;
+    const int spare = with_residual ? 1 : 0;
     int d0 = p->resident_depth > 0 ? (int)p->resident_depth : RESIDENT_DEFAULT_DEPTH;
-    if (d0 > (held - 1) / 2) d0 = (held - 1) / 2;        // at least one owned row
+    if (d0 > (held - 1) / 2 - spare) d0 = (held - 1) / 2 - spare;     // at least one owned row
     if (d0 > iters) d0 = iters;                           // no more ghost rows than a phase can use
     // deep phases leave few owned rows per workgroup; the grid barrier needs every workgroup resident, so
     // tall grids get shallower phases
@@ -525,10 +529,10 @@ ResidentChoice resident_choice(const jacobi_plan *p, int iters)
         c.nphase = (int)ceil_div(iters, d0);
         c.depth = iters / c.nphase;
         c.n_deep = iters % c.nphase;
-        c.d = c.depth + (c.n_deep ? 1 : 0);              // the phases are equally deep: ghost rows for the deepest
+        c.d = c.depth + (c.n_deep ? 1 : 0) + spare;      // the phases are equally deep: ghost rows for the deepest
         c.B = held - 2 * c.d;
         const int64_t nwg = ceil_div(Ny, c.B);
-        if (nwg > p->num_cu) continue;
+        if (nwg > p->num_cu || nwg > RESIDENT_MAX_WORKGROUPS) continue;
         c.ok = true;
         c.nseg = nseg; c.rw = rw; c.nwg = (int)nwg;
         return c;
@@ -536,7 +540,10 @@ ResidentChoice resident_choice(const jacobi_plan *p, int iters)
     return c;
 }
 
-int launch_resident(jacobi_plan *p, const ResidentChoice &c, void *in, void *out, hipStream_t st)
+// copy_ring: `out` does not carry the Dirichlet ring yet; residual_out_dev: if not null, the residual norm of
+// the grid the launch produces (the choice must have been made with_residual).
+int launch_resident(jacobi_plan *p, const ResidentChoice &c, void *in, void *out, hipStream_t st, bool copy_ring,
+                    double *residual_out_dev)
 {
     jk::ResidentLaunch a;
     a.nwg = (unsigned)c.nwg;
@@ -545,6 +552,9 @@ int launch_resident(jacobi_plan *p, const ResidentChoice &c, void *in, void *out
     a.rp.B = c.B; a.rp.d = c.d; a.rp.nphase = c.nphase; a.rp.depth = c.depth; a.rp.n_deep = c.n_deep;
     a.rp.spin_limit = p->resident_spin_limit > 0 ? (unsigned)(p->resident_spin_limit - 1) : RESIDENT_DEFAULT_SPIN;
     a.rp.sync = p->sync_words;
+    a.rp.copy_ring = copy_ring ? 1 : 0;
+    a.rp.partial = p->partial;
+    a.rp.residual = residual_out_dev;
     a.in = in; a.out = out;
     return launch_checked(jk::launch_resident(p->lay.dtype == JACOBI_F64, c.nseg, c.rw, a), "resident kernel launch");
 }
@@ -698,6 +708,7 @@ int64_t max_partials(jacobi_plan *p)
     }
     p->rows_per_strip = saved_rps;
     p->rows_per_wave = saved_rpw;
+    if (p->geo.ndim == 2) most = std::max<int64_t>(most, RESIDENT_MAX_WORKGROUPS);      // the one-launch kernel's
     return most;
 }
 
@@ -725,6 +736,13 @@ int prepare_plan(jacobi_plan *p)
     if (e != hipSuccess) return fail_hip(e, "hipMalloc(residual scratch)");
     p->partial_cap = need;
     p->sync_words = (unsigned *)(p->partial + need);
+    // the resident kernel's barrier words are zero between launches: it clears them itself when it finishes
+    e = hipMemset(p->sync_words, 0, 2 * sizeof(double));
+    if (e != hipSuccess) {
+        (void)hipFree(p->partial);
+        p->partial = nullptr;
+        return fail_hip(e, "hipMemset(barrier words)");
+    }
     p->prepared = true;
     return JACOBI_OK;
 }
@@ -934,8 +952,10 @@ struct RunCarry {
     bool x_packed = false;          // its x send arrays hold its first / last columns
 };
 
+// residual_in_dev: if not null, also the residual norm of `in`; residual_out_dev: if not null, also that of the
+// grid the iterations produce.
 static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipStream_t st, void **final,
-                        double *residual_in_dev, RunCarry *carry = nullptr)
+                        double *residual_in_dev, RunCarry *carry = nullptr, double *residual_out_dev = nullptr)
 {
     int rc = prepare_plan(plan);
     if (rc) return rc;
@@ -947,10 +967,12 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
             plan->ev.push_back(e);
         }
     }
-    const ResidentChoice rc_res = resident_choice(plan, iters);
+    ResidentChoice rc_res = resident_choice(plan, iters, residual_out_dev != nullptr);
+    const bool norm_in_launch = rc_res.ok && residual_out_dev;
+    if (!rc_res.ok && residual_out_dev) rc_res = resident_choice(plan, iters);
     if (rc_res.ok) {
-        // small 2-D grid: every iteration inside one launch; the residual of `in`, if asked for, from the
-        // stand-alone reduction first
+        // small 2-D grid: every iteration inside one launch, which also carries the ring over and delivers the
+        // residual of its result; the residual of `in`, if asked for, from the stand-alone reduction first
         if (residual_in_dev) {
             const int64_t nwg = single_step_workgroups(plan, jk::MODE_RESIDUAL);
             rc = check_partials(plan, nwg);
@@ -958,20 +980,21 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
             rc = residual_launches(plan, in, plan->partial, residual_in_dev, st);
             if (rc) return rc;
         }
-        if (!(carry && carry->ring_done)) {
-            rc = launch_boundary_sync(plan, in, out, st);
-            if (rc) return rc;
-        }
+        rc = check_partials(plan, rc_res.nwg);
+        if (rc) return rc;
+        const bool copy_ring = !(carry && carry->ring_done);
         if (carry) *carry = RunCarry{true, false, false};      // the kernel stores rows only
         const bool timed = plan->profile && plan->ev_used < MAX_PROFILE_EVENTS;
         if (timed) HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used], st));
-        rc = launch_resident(plan, rc_res, in, out, st);
+        rc = launch_resident(plan, rc_res, in, out, st, copy_ring, norm_in_launch ? residual_out_dev : nullptr);
         if (rc) return rc;
         if (timed) {
             HIP_TRY(hipEventRecord(plan->ev[2 * plan->ev_used + 1], st));
             ++plan->ev_used;
         }
-        if (final) *final = (rc_res.nphase & 1) ? out : in;
+        void *result = (rc_res.nphase & 1) ? out : in;
+        if (final) *final = result;
+        if (residual_out_dev && !norm_in_launch) return residual_common(plan, result, residual_out_dev, st);
         return JACOBI_OK;
     }
     const PassChoice first = choose_pass(plan, iters);
@@ -1032,6 +1055,7 @@ static int sweep_common(jacobi_plan *plan, void *in, void *out, int iters, hipSt
     }
     if (carry) *carry = RunCarry{true, halos_current, x_packed};
     if (final) *final = src;
+    if (residual_out_dev) return residual_common(plan, src, residual_out_dev, st);
     return JACOBI_OK;
 }
 
@@ -1200,18 +1224,19 @@ int jacobi_run(jacobi_plan *plan, void *in, void *out, int iters, int residual_e
     RunCarry carry;                  // blocks after the first start from what the one before left in the grids
     while (done < iters) {
         const int n = std::min(residual_every > 0 ? residual_every : iters, iters - done);
+        const bool norm_due = residual_every > 0 && (done + n) % residual_every == 0;
+        const int k = norm_due ? (done + n) / residual_every - 1 : -1;
+        // The norm of the grid a block produces comes from the block's own launch if that is the one-launch
+        // kernel, else from inside the first update of the next block; the last block's from the stand-alone pass.
+        const bool in_launch = norm_due && resident_choice(plan, n, true).ok;
+        const bool stand_alone = norm_due && !in_launch && done + n == iters;
         void *fin = cur;
-        // the norm of the grid a block of iterations produced is taken from the first update of the next block
-        int rc = sweep_common(plan, cur, other, n, st, &fin, pending >= 0 ? residuals_dev + pending : nullptr, &carry);
+        int rc = sweep_common(plan, cur, other, n, st, &fin, pending >= 0 ? residuals_dev + pending : nullptr, &carry,
+                              in_launch || stand_alone ? residuals_dev + k : nullptr);
         if (rc) return rc;
-        pending = -1;
+        pending = norm_due && !in_launch && !stand_alone ? k : -1;
         if (fin != cur) std::swap(cur, other);
         done += n;
-        if (residual_every > 0 && done % residual_every == 0) {
-            const int k = done / residual_every - 1;
-            if (done < iters) pending = k;
-            else if ((rc = residual_common(plan, cur, residuals_dev + k, st))) return rc;   // the last one: stand-alone
-        }
     }
     if (final) *final = cur;
     return JACOBI_OK;

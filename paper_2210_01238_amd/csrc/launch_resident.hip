@@ -8,13 +8,6 @@ static hipError_t resident_dispatch(int nseg, int rows_per_wave, const ResidentL
 {
     const dim3 grid(a.nwg), block(RES_WAVES * WAVE);
     T *ga = (T *)a.in, *gb = (T *)a.out;
-    if (a.nwg > 1) {
-        // the arrival counter and the failure flag start at zero (a fill kernel, not a memset: the pair may be
-        // recorded into a HIP graph)
-        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(WAVE), 0, a.st, a.rp.sync, 2);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
 #define JK_L(NSEG_, RW_) \
     hipLaunchKernelGGL((resident2d_kernel<T, NSEG_, RW_>), grid, block, 0, a.st, a.g, a.rp, ga, gb)
     // two register sets of rows x vectors: 4 rows of 2 vectors would not fit the 128 registers of a 1024-thread workgroup

@@ -109,7 +109,11 @@ struct ResidentParams {
     int nphase;            // phases; the first n_deep of them run depth + 1 iterations, the others depth
     int depth, n_deep;
     unsigned spin_limit;   // polls a workgroup waits at a grid barrier before it gives up
-    unsigned *sync;        // [0]: arrivals, [1]: failure flag (both zeroed before the launch); unused with one workgroup
+    unsigned *sync;        // [0]: arrivals, [1]: failure flag, [2]: workgroups that have finished.  All zero between
+                           // launches (the last workgroup to finish clears them); unused with one workgroup
+    int copy_ring;         // also carry the Dirichlet ring from the source grid to the other one
+    double *partial;       // per-workgroup sums of the residual terms (one per workgroup; unused if residual is null)
+    double *residual;      // if not null: the residual norm of the final grid goes here (then d > deepest phase)
 };
 struct ResidentLaunch {
     unsigned nwg;

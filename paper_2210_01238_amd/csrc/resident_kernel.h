@@ -30,17 +30,19 @@
 // flag stops waiting, and all of them write NaN instead of results, so a launch always drains and a
 // failed one cannot be mistaken for a good one.
 //
+// One launch is the whole call.  The kernel carries the Dirichlet ring to the other grid itself (the ring
+// rows and the cells beside each row are in its registers anyway), it can deliver the residual norm of the
+// grid it produced (one more exchange of border rows; the last workgroup to finish adds the workgroups'
+// partial sums in index order), and that last workgroup also puts the barrier words back to zero for the
+// next launch: a workgroup counts itself as finished after its last barrier and nobody waits for that
+// count, so this needs no further synchronisation and also cleans up after a barrier that gave up.
+//
 // Every value is formed by the single-step expression 0.25*((W+E)+(S+N)): bit-identical to the
 // launch-per-iteration path.  Needs tw a multiple of the vector width and Nx <= NSEG*64 vectors.
 #pragma once
 #include "launchers.h"
 
 namespace jk {
-
-__global__ void zero_words_kernel(unsigned *p, int n)
-{
-    if ((int)threadIdx.x < n) p[threadIdx.x] = 0u;
-}
 
 // All workgroups of the grid wait for each other.  `target` = arrivals expected so far.  Returns false if
 // this workgroup gave up waiting (or saw that another one had).  The cache maintenance that makes one XCD's
@@ -127,6 +129,29 @@ __global__ __launch_bounds__(RES_WAVES * WAVE) void resident2d_kernel(Geo g, Res
     };
 #pragma unroll
     for (int j = 0; j < RW; ++j) load_row(ga, j);
+
+    if (rp.copy_ring) {
+        // the other grid gets the ring: the two ring rows from the workgroups that own the rows next to them,
+        // the cells beside a row (the corners beside the ring rows) from whoever owns or copies that row
+#pragma unroll
+        for (int j = 0; j < RW; ++j) {
+            const int gy = max(0, min(own_lo - rp.d + wave * RW + j, Ny + 1));
+            const bool mine = own_row[j] || (gy == 0 && own_lo == 1) || (gy == Ny + 1 && own_hi == Ny);
+            if (!mine) continue;
+            if (ring_row[j]) {
+#pragma unroll
+                for (int s = 0; s < NSEG; ++s)
+                    if (active[s]) *(V *)(gb + row_off[j] + col_off[s]) = A[j][s];
+            }
+            if (lane == 0) {
+                const int ty = gy == 0 ? 0 : gy == Ny + 1 ? g.Ty - 1 : (gy - 1) / g.th;
+                const int rr = gy - ty * g.th;
+                const long long tile_row = (long long)ty * g.Tx * g.tile_stride;
+                gb[tile_row + xm_off(g, 0, rr)] = edge_w[j];
+                gb[tile_row + (long long)(g.Tx - 1) * g.tile_stride + xp_off(g, 0, rr)] = edge_e[j];
+            }
+        }
+    }
 
     const int wave_up = max(wave - 1, 0), wave_dn = min(wave + 1, RES_WAVES - 1);
 
@@ -220,6 +245,68 @@ __global__ __launch_bounds__(RES_WAVES * WAVE) void resident2d_kernel(Geo g, Res
             healthy = resident_grid_barrier(rp.sync, (unsigned)(ph + 1) * gridDim.x, rp.spin_limit, &barrier_ok) && healthy;
         T *t = src; src = dst; dst = t;
     }
+    if (single && !rp.residual) return;
+
+    // ---- residual norm of the grid just produced (A): sum over the owned rows of (W+E+S+N - 4u)^2.  The rows
+    // next to the owned ones are exact: the host gives d one more than the deepest phase when it asks for this.
+    __shared__ double red[RES_WAVES];
+    double tot = 0.0;
+    if (rp.residual) {
+        __syncthreads();                            // the last iteration's border rows have been read
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s) {
+            xch[0][wave][0][s][lane] = A[0][s];
+            xch[0][wave][1][s][lane] = A[RW - 1][s];
+        }
+        __syncthreads();
+        double acc = 0.0;
+#pragma unroll
+        for (int j = 0; j < RW; ++j) {
+            if (!own_row[j]) continue;              // wave-uniform
+            const T left = from_prev_lane(A[j][NSEG - 1][NV - 1], edge_w[j]);
+            const T right = from_next_lane(A[j][0][0], edge_e[j]);
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                const V up = j == 0 ? xch[0][wave_up][1][s][lane] : A[j == 0 ? 0 : j - 1][s];
+                const V dn = j == RW - 1 ? xch[0][wave_dn][0][s][lane] : A[j == RW - 1 ? j : j + 1][s];
+#pragma unroll
+                for (int e = 0; e < NV; ++e) {
+                    const T w = e > 0 ? A[j][s][e - 1] : s > 0 ? A[j][s > 0 ? s - 1 : 0][NV - 1] : left;
+                    T ea = e < NV - 1 ? A[j][s][e + 1] : s < NSEG - 1 ? A[j][s < NSEG - 1 ? s + 1 : s][0] : right;
+                    if (e == NV - 1) ea = has_last[s] ? edge_e[j] : ea;
+                    const T res = ((w + ea) + (up[e] + dn[e])) - Coef<T>::four * A[j][s][e];
+                    const double rd = (double)res;
+                    if (active[s]) acc += rd * rd;
+                }
+            }
+        }
+        tot = wg_sum(acc, red);                     // valid in thread 0
+    }
+    if (single) {
+        if (threadIdx.x == 0) *rp.residual = sqrt(tot);
+        return;
+    }
+    // ---- this workgroup has finished; the last one to say so closes the launch
+    if (threadIdx.x == 0) {
+        if (rp.residual) {
+            __hip_atomic_store(&rp.partial[blockIdx.x], healthy ? tot : __builtin_nan(""), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        }
+        const unsigned before = __hip_atomic_fetch_add(&rp.sync[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = before == gridDim.x - 1;
+        if (last && rp.residual) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // before the others' sums are read
+        barrier_ok = last ? 1 : 0;
+    }
+    __syncthreads();
+    if (!barrier_ok) return;
+    if (rp.residual) {
+        double v = 0.0;
+        for (unsigned i = threadIdx.x; i < gridDim.x; i += blockDim.x)
+            v += __hip_atomic_load(&rp.partial[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const double sum = wg_sum(v, red);
+        if (threadIdx.x == 0) *rp.residual = sqrt(sum);
+    }
+    if (threadIdx.x < 3) __hip_atomic_store(&rp.sync[threadIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace jk

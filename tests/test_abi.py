@@ -188,8 +188,8 @@ def test_pass_schedule_host_logic(J):
 
 def test_scratch_size_covers_every_option_setting(J):
     """jacobi_scratch_bytes (host only): one double per workgroup of the finest-grained residual launch
-    (strips of one row or plane, one row per wavefront), plus the host-result slot and 16 bytes of barrier
-    words; independent of the
+    (strips of one row or plane, one row per wavefront; 2-D: at least the 1024 the all-iterations-in-one-launch
+    kernel may use), plus the host-result slot and 16 bytes of barrier words; independent of the
     option values, so jacobi_prepare's allocation never has to grow."""
     def nbytes(dims, tiles, dtype=0, **opts):
         p = J.jacobi_create(dims, tiles, dtype)
@@ -209,7 +209,9 @@ def test_scratch_size_covers_every_option_setting(J):
     assert nbytes((512, 512, 512), (4, 4, 4), rows_per_wave=4, cooperative=0) == nbytes((512, 512, 512), (4, 4, 4))
     # fp32 rows of 128 cells use 8-byte lanes only with 4 rows per wavefront; finest is still 1 row per strip
     assert nbytes((512, 512, 512), (4, 4, 4), 1) == 8 * (64 * 128 * 128 // 4 + 1) + 16
-    assert nbytes((1, 1), (1, 1)) == 32
+    # small 2-D plans: the one-launch kernel's per-workgroup sums (at most 1024 workgroups)
+    assert nbytes((1, 1), (1, 1)) == 8 * (1024 + 1) + 16
+    assert nbytes((1, 1, 1), (1, 1, 1)) == 32
     assert J.jacobi_scratch_bytes(None) == 0
     with pytest.raises(J.JacobiError):
         J.jacobi_prepare(None)

@@ -48,6 +48,63 @@ def test_resident_fp64_bit_exact(H, oracle_mod, dims, tiles, iters, every):
     check(*run_case(H, oracle_mod, a, tiles, iters, every, resident=1))
 
 
+def run_in_one_call(H, a, tiles, iters, every, **opts):
+    r = H.JacobiRun([n - 2 for n in a.shape], tiles, a.dtype, **opts)
+    try:
+        r.load(a)
+        res = r.run(iters, every, fuse_residual=True)
+        return r.fetch(), res
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("dims,tiles,iters,every", CASES)
+def test_resident_run_takes_its_residuals_from_the_launches(H, oracle_mod, dims, tiles, iters, every):
+    """jacobi_run on these shapes: every block of iterations is one launch that also delivers the norm of the
+    grid it produced (the rows next to a workgroup's own must then still be exact after the deepest phase)."""
+    a = random_padded(dims, seed=sum(dims) + iters + 1)
+    ref, ref_res = oracle_mod.run(a, iters, every)
+    out, res = run_in_one_call(H, a, tiles, iters, every, resident=1)
+    check(out, res, ref, ref_res)
+    out2, res2 = run_in_one_call(H, a, tiles, iters, every, resident=1)
+    assert res2 == res and np.array_equal(out2, out)                 # same bits on every run
+
+
+@pytest.mark.parametrize("opts", [
+    dict(resident_depth=1), dict(resident_depth=2, resident_rows=1), dict(resident_depth=6, resident_rows=1),
+    dict(resident_depth=7, resident_rows=1), dict(resident_depth=23), dict(resident_depth=31, resident_rows=2),
+    dict(resident_rows=4), dict(),
+])
+def test_resident_run_with_every_phase_geometry(H, oracle_mod, opts):
+    for dims, tiles, dtype in (((256, 256), (2, 2), np.float64), ((130, 100), (5, 5), np.float64),
+                               ((300, 512), (3, 4), np.float32)):
+        a = random_padded(dims, dtype=dtype, seed=21)
+        ref, ref_res = oracle_mod.run(a, 46, 23)
+        out, res = run_in_one_call(H, a, tiles, 46, 23, resident=1, **opts)
+        check(out, res, ref, ref_res)
+
+
+def test_resident_launch_carries_the_whole_ring_to_the_other_grid(H, oracle_mod):
+    """The launch itself copies the Dirichlet ring (rows, columns, corners) to the grid it does not start from:
+    that grid is filled with NaN first, and after an odd number of phases it holds the result."""
+    import torch
+    for dims, tiles, iters in (((256, 256), (1, 1), 20), ((40, 36), (4, 3), 3), ((700, 130), (7, 1), 15),
+                               ((1, 2), (1, 1), 1)):
+        a = random_padded(dims, seed=31)
+        r = H.JacobiRun(dims, tiles, resident=1)
+        try:
+            assert len(H.B.jacobi_pass_schedule(r.plan, iters)) == 1
+            r.load(a)
+            r.other().view(torch.float64).fill_(float("nan"))
+            r.sweep(iters)
+            assert r.cur is r.b
+            out = r.fetch()
+        finally:
+            r.close()
+        ref, _ = oracle_mod.run(a, iters)
+        assert np.array_equal(out, ref), dims
+
+
 @pytest.mark.parametrize("dims,tiles,iters,every", [
     ((256, 256), (1, 1), 30, 10), ((256, 512), (2, 2), 30, 10), ((100, 300), (5, 3), 17, 17), ((40, 8), (2, 2), 9, 3),
 ])
@@ -117,7 +174,7 @@ def test_resident_selection_and_schedule(H):
 
 
 def test_resident_inside_a_hip_graph(H, oracle_mod):
-    """The pair (zero the barrier words, resident kernel) recorded into a HIP graph and replayed."""
+    """The launch recorded into a HIP graph and replayed: it leaves its barrier words zeroed for the next one."""
     import torch
     w = gen.WORKLOADS["C1"]
     a = gen.generate(w)
@@ -152,7 +209,8 @@ def test_resident_barrier_gives_up_instead_of_hanging(H, oracle_mod):
     """The grid barrier's wait is bounded.  With a spin limit of ZERO polls beyond the first, a workgroup that
     finds the others not yet arrived gives up at once: the launch must still drain, and what it then writes is
     NaN (or, if every workgroup happened to arrive in time, the right answer) - never a plausible wrong value.
-    The next call, with the default limit, is correct again: the barrier words are re-zeroed per launch."""
+    The next call, with the default limit, is correct again: the last workgroup to finish clears the barrier
+    words, also after a barrier that gave up."""
     a = random_padded((256, 256), seed=9)
     ref, _ = oracle_mod.run(a, 40)
     r = H.JacobiRun((256, 256), (1, 1), resident=1, resident_spin_limit=1)
@@ -161,9 +219,19 @@ def test_resident_barrier_gives_up_instead_of_hanging(H, oracle_mod):
         r.sweep(40)
         out = r.fetch()
         assert np.array_equal(out, ref) or np.isnan(out[1:-1, 1:-1]).any()
+        # the norm delivered by a launch that gave up is NaN as well
+        r.load(a)
+        res = r.run(40, 40, fuse_residual=True)
+        out = r.fetch()
+        ok = np.array_equal(out, ref)
+        assert ok or np.isnan(out[1:-1, 1:-1]).any()
+        assert np.isnan(res[0]) or (ok and abs(res[0] - oracle_mod.residual(ref)) <= 1e-12 * res[0])
         r.set_option("resident_spin_limit", 0)
         r.load(a)
         r.sweep(40)
         assert np.array_equal(r.fetch(), ref)
+        r.load(a)
+        res = r.run(40, 40, fuse_residual=True)
+        assert np.array_equal(r.fetch(), ref) and abs(res[0] - oracle_mod.residual(ref)) <= 1e-12 * res[0]
     finally:
         r.close()
