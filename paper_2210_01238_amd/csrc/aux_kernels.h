@@ -147,40 +147,48 @@ __global__ __launch_bounds__(WG) void halo_exchange_kernel(Geo g, T *grid, int c
 
 // ------------------------------------------------------------------------------------
 // Scatter / gather between a padded global array and the tile-major grid.
-// Work item = (tile, padded plane, padded row, chunk of WG columns); one thread per padded
-// cell, column index cc in [-1, tw].  Workgroups stride over the item list.
+// Work item = (padded row of a tile: tile, plane, row; chunk of 64*Q padded columns), one per WAVEFRONT.  A lane
+// moves Q cells 64 columns apart - column index cc in [-1, tw]: the two x halo cells live in the dense arrays -
+// and issues its Q loads before its Q stores.  Consecutive lanes move consecutive cells on both sides.
 // ------------------------------------------------------------------------------------
-template <typename T, bool GATHER>
+template <typename T, bool GATHER, int Q>
 __global__ __launch_bounds__(WG) void scatter_gather_kernel(Geo g, const T *__restrict__ from, T *__restrict__ to,
-                                                            long long GP, long long GQ, int chunks_per_row,
-                                                            long long nitems)
+                                                            long long GP, long long GQ, unsigned nchunks,
+                                                            unsigned nitems)
 {
-    for (long long item = blockIdx.x; item < nitems; item += gridDim.x) {
-        const int chunk = (int)(item % chunks_per_row);
-        long long rest = item / chunks_per_row;
-        const int i = (int)(rest % g.rows);
-        rest /= g.rows;
-        const int k = (int)(rest % g.nplanes), t = (int)(rest / g.nplanes);
-        const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
-        const int cc = chunk * WG + (int)threadIdx.x - 1;
-        if (cc > g.tw) continue;
-        const long long toff = (long long)t * g.tile_stride +
-                               (cc < 0 ? xm_off(g, k, i) : cc == g.tw ? xp_off(g, k, i) : main_off(g, k, i, cc));
-        const long long gk = g.ndim == 3 ? (long long)tz * g.td + k : 0;
-        const long long gi = (long long)ty * g.th + i, gj = (long long)tx * g.tw + cc + 1;
-        const long long goff = gk * GQ + gi * GP + gj;
-        if constexpr (!GATHER) {
-            to[toff] = from[goff];
-        } else {
-            // a padded cell of the tile is written back if it is interior to the tile, or lies on
-            // the domain boundary; copies of neighbouring tiles' cells are skipped
-            const bool in_k = g.ndim == 2 || (k >= 1 && k <= g.td) || (k == 0 && tz == 0) ||
-                              (k == g.td + 1 && tz == g.Tz - 1);
-            const bool in_i = (i >= 1 && i <= g.th) || (i == 0 && ty == 0) || (i == g.th + 1 && ty == g.Ty - 1);
-            const bool in_c = (cc >= 0 && cc < g.tw) || (cc < 0 && tx == 0) || (cc == g.tw && tx == g.Tx - 1);
-            if (in_k && in_i && in_c) to[goff] = from[toff];
-        }
+    const unsigned w = blockIdx.x * WAVES_PER_WG + threadIdx.x / WAVE;      // the host keeps nitems below 2^32 - 4
+    if (w >= nitems) return;
+    const unsigned chunk = w % nchunks;
+    const unsigned item = w / nchunks;                   // (tile, plane, row)
+    const int i = (int)(item % (unsigned)g.rows);
+    const unsigned rest = item / (unsigned)g.rows;
+    const int k = (int)(rest % (unsigned)g.nplanes), t = (int)(rest / (unsigned)g.nplanes);
+    const int tz = t / (g.Ty * g.Tx), ty = (t / g.Tx) % g.Ty, tx = t % g.Tx;
+    const long long tbase = (long long)t * g.tile_stride;
+    const long long row = tbase + main_off(g, k, i, 0), xm = tbase + xm_off(g, k, i), xp = tbase + xp_off(g, k, i);
+    const long long gk = g.ndim == 3 ? (long long)tz * g.td + k : 0;
+    const long long grow = gk * GQ + ((long long)ty * g.th + i) * GP + (long long)tx * g.tw + 1;   // of tile column 0
+    // gather: a padded cell of the tile is written back if it is interior to the tile or lies on the domain
+    // boundary; the tile's copies of neighbouring tiles' cells are skipped
+    const bool in_k = g.ndim == 2 || (k >= 1 && k <= g.td) || (k == 0 && tz == 0) || (k == g.td + 1 && tz == g.Tz - 1);
+    const bool in_i = (i >= 1 && i <= g.th) || (i == 0 && ty == 0) || (i == g.th + 1 && ty == g.Ty - 1);
+    if (GATHER && !(in_k && in_i)) return;
+    T v[Q];
+    long long dst[Q];
+    bool ok[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int cc = ((int)chunk * Q + q) * WAVE + (int)(threadIdx.x % WAVE) - 1;
+        ok[q] = cc <= g.tw;
+        const long long toff = cc < 0 ? xm : cc == g.tw ? xp : row + cc;
+        const long long goff = grow + cc;
+        if (GATHER) ok[q] = ok[q] && ((cc >= 0 && cc < g.tw) || (cc < 0 && tx == 0) || (cc == g.tw && tx == g.Tx - 1));
+        dst[q] = GATHER ? goff : toff;
+        v[q] = ok[q] ? from[GATHER ? toff : goff] : T(0);
     }
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        if (ok[q]) to[dst[q]] = v[q];
 }
 
 // Plain streaming copy, 16 bytes per lane, one element per thread, workgroups in memory

@@ -674,11 +674,24 @@ int launch_sg_t(jacobi_plan *p, const T *from, T *to, hipStream_t st)
 {
     const Geo &g = p->geo;
     const long long GP = p->lay.dims[2] + 2, GQ = (p->lay.dims[1] + 2) * GP;
-    const int chunks = (int)ceil_div((int64_t)g.tw + 2, jk::WG);
-    const int64_t nitems = (int64_t)g.ntiles * g.nplanes * g.rows * chunks;
-    const int64_t nblk = nitems < MAX_COPY_BLOCKS ? nitems : MAX_COPY_BLOCKS;
-    hipLaunchKernelGGL((jk::scatter_gather_kernel<T, GATHER>), dim3((unsigned)nblk), dim3(jk::WG), 0, st, g, from, to,
-                       GP, GQ, chunks, (long long)nitems);
+    const int64_t nrows = (int64_t)g.ntiles * g.nplanes * g.rows;
+    if (nrows > 0x7fffffffLL) return fail(JACOBI_EINVAL, "too many tile rows for one scatter / gather launch");
+    const int cols = g.tw + 2;
+    // a wavefront per row and chunk of up to 256 cells, four per lane in flight (fewer for narrower tiles)
+    const int q = (int)std::min<int64_t>(4, ceil_div(cols, jk::WAVE));
+    const int64_t nchunks = ceil_div(cols, q * jk::WAVE), nitems = nrows * nchunks;
+    const int64_t nwg = ceil_div(nitems, jk::WAVES_PER_WG);
+    if (nitems > 0xfffffff0LL) return fail(JACOBI_EINVAL, "too many row chunks for one scatter / gather launch");
+#define JK_SG(Q_) \
+    hipLaunchKernelGGL((jk::scatter_gather_kernel<T, GATHER, Q_>), dim3((unsigned)nwg), dim3(jk::WG), 0, st, g, from, to, \
+                       GP, GQ, (unsigned)nchunks, (unsigned)nitems)
+    switch (q) {
+    case 1: JK_SG(1); break;
+    case 2: JK_SG(2); break;
+    case 3: JK_SG(3); break;
+    default: JK_SG(4); break;
+    }
+#undef JK_SG
     HIP_TRY(hipGetLastError());
     return JACOBI_OK;
 }
