@@ -336,7 +336,7 @@ def main() -> int:
         "roofline": {
             "bound": "hbm",
             "kernel": ("sweep2d_kernel<double, update>" if len(w.dims) == 2 else "sweep3d_kernel<double, update>")
-                      + " (the launches timed include each call's first update, which reads the neighbouring tiles' edge "
+                      + " (the launches timed include the first update of the run, which reads the neighbouring tiles' edge "
                         "cells instead of halo cells, and each step's first, which also accumulates the residual)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
