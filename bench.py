@@ -44,7 +44,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # counter reads for the plain copy kernel of known size), from profiles/sweep2d_update_C3.md,
 # profiles/sweep3d_update_C4.md and profiles/sweep3d_update_P1.md.  Valid only for the library's default options on that
 # workload; otherwise reported as null.
-MEASURED_TRAFFIC_BYTES = {"C3": 4585730811, "C4": 2411994870, "P1": 14459791159}
+MEASURED_TRAFFIC_BYTES = {"C3": 4589190778, "C4": 2412187863, "P1": 14467560021}
 TRAFFIC_SOURCE = {"C3": "profiles/sweep2d_update_C3.md", "C4": "profiles/sweep3d_update_C4.md",
                   "P1": "profiles/sweep3d_update_P1.md"}
 
