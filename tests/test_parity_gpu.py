@@ -602,6 +602,45 @@ def test_task_execution_is_bit_identical(H, oracle_mod, dims, tiles, group, stre
         check(out, res, ref, ref_res)
 
 
+def test_whole_schedule_can_be_captured_in_a_hip_graph(H, oracle_mod):
+    """jacobi_run - scatter, every block of iterations and every residual norm of a schedule - recorded into ONE
+    HIP graph on a prepared plan and replayed with eager work on the same plan in between: every replay must
+    give the grid and the norms of the eager run.  Launch-per-pass kernels (2-D and 3-D, single steps and
+    blocked passes) and the path that runs a block of iterations in one launch."""
+    import torch
+    cases = [((192, 256), (3, 2), dict(resident=0), 12, 4), ((192, 256), (3, 2), dict(resident=0, tblock=4), 14, 7),
+             ((24, 20, 36), (2, 2, 3), dict(), 9, 3), ((24, 20, 36), (2, 2, 3), dict(tblock=2), 8, 4),
+             ((256, 256), (1, 1), dict(resident=1), 60, 20), ((40, 64), (2, 2), dict(resident=1), 30, 10)]
+    for n, (dims, tiles, opts, iters, every) in enumerate(cases):
+        a = random_padded(dims, seed=300 + n)
+        exp, exp_res = oracle_mod.run(a, iters, every)
+        r = H.JacobiRun(dims, tiles, **opts)
+        try:
+            H.B.jacobi_prepare(r.plan)
+            g_dev = torch.from_numpy(a).cuda()
+            res = torch.zeros(iters // every, dtype=torch.float64, device="cuda")
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s):
+                st = int(torch.cuda.current_stream().cuda_stream)
+                H.B.jacobi_scatter(r.plan, g_dev.data_ptr(), r.a.data_ptr(), st)
+                fin = H.B.jacobi_run(r.plan, r.a.data_ptr(), r.b.data_ptr(), iters, every, res.data_ptr(), st)
+            for k in range(3):
+                res.zero_()
+                graph.replay()
+                torch.cuda.synchronize()
+                r.cur = r.a if fin == r.a.data_ptr() else r.b
+                check(r.fetch(), res.cpu().tolist(), exp, exp_res)
+                # eager work on the same plan between the replays: other kernels, the same scratch
+                r.load(a)
+                r.sweep(k + 1)
+                r.residual()
+        finally:
+            r.close()
+
+
 @pytest.mark.skip(reason="ending the capture of the multi-stream fork/join crashed inside the HIP runtime "
                          "(host segmentation fault in hipStreamEndCapture, cause not found); "
                          "jacobi_sweep_tasks now refuses a capturing stream")
