@@ -117,13 +117,14 @@ int jacobi_create(jacobi_plan **plan, int ndim, const int64_t *dims, const int64
  * jacobi_prepare: the plan's one-time device set-up, on the current device: reads the device's
  * CU count and LDS size and allocates the plan-owned scratch of the residual reduction (one
  * double per workgroup of the largest launch ANY option setting can ask for, so it never has
- * to grow: 8 bytes per 4 one-row strips of about 100 cells at most, 5 MiB for 16384^2).
+ * to grow: 8 bytes per 4 one-row strips of about 100 cells at most, 5 MiB for 16384^2; behind
+ * it the 16 bytes of the one-launch kernel's barrier words, set to zero here once).
  * This is the only device allocation the library ever makes for a plan (the paper's runtime
  * keeps such buffers in a pre-allocated device memory pool for the same reason, Sec. VI-A).
  * jacobi_scatter, jacobi_sweep, jacobi_sweep_residual, jacobi_sweep_tasks, residual_norm and
  * residual_norm_host call it themselves if the caller has not; after it has run once, none of
- * jacobi_sweep, jacobi_sweep_residual, halo_exchange and residual_norm allocates, frees or
- * synchronises anything, whatever options are changed in between, so they can be recorded
+ * jacobi_sweep, jacobi_sweep_residual, jacobi_run, halo_exchange and residual_norm allocates,
+ * frees or synchronises anything, whatever options are changed in between, so they can be recorded
  * into a HIP graph (the call that runs the set-up cannot: do it before the capture starts).
  * Idempotent.  Errors: EINVAL (NULL), ENOMEM, EHIP.
  */
@@ -211,7 +212,9 @@ int jacobi_sweep_residual(jacobi_plan *plan, void *in, void *out, int iters, voi
  * iters / residual_every doubles; may be NULL if that is 0; residual_every = 0: no norms).
  * Equivalent to blocks of jacobi_sweep(residual_every) each followed by residual_norm, but each norm
  * except the last is taken from inside the first update of the NEXT block (jacobi_sweep_residual), so
- * it costs no pass over memory of its own; values agree up to summation order.  The blocks after the
+ * it costs no pass over memory of its own (on small 2-D grids, where a block is one launch - option
+ * "resident" -, that launch delivers the norm of its own result); values agree up to summation order.
+ * The blocks after the
  * first also start from what the block before left in the two grids (the Dirichlet ring in both, the
  * halo cells its last update pushed), where separate calls would copy the ring and fetch the
  * neighbours' edge cells again.  in / out / final as for jacobi_sweep (the buffers swap roles once per
@@ -345,7 +348,9 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *   "resident"       0 | 1   small 2-D grids: run ALL iterations of a jacobi_sweep call inside ONE kernel
  *                    launch (default 1).  Taken when the grid is 2-D, a row of the domain is at most
  *                    2 KiB (256 fp64 / 512 fp32 columns), the tile width is a multiple of 16 bytes, and
- *                    the rows fit one workgroup per CU (about 34 rows each by default: up to ~8000 rows).
+ *                    the rows fit one workgroup per CU (a workgroup owns what its 48 or 64 rows leave
+ *                    after the ghost rows - 8 of 48 with 20 per side; taller grids get shallower phases,
+ *                    up to ~12000 rows).
  *                    Such grids are updated in about a microsecond, so the launch-per-iteration sequence
  *                    is bound by launch latency (3.5 us per iteration); here the grid stays in registers,
  *                    the wavefronts of a workgroup pass each other their border rows through LDS, and
@@ -362,7 +367,8 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    Ignores "tblock"; inter-tile halo cells of the result are left alone.
  *   "resident_depth" 0 | 1..31  iterations between two barriers of that kernel (0 = choose: 20, evened
  *                    out over the call)
- *   "resident_rows"  0 | 1..4   rows each of its wavefronts keeps (0 = choose: 4, or just enough for a
+ *   "resident_rows"  0 | 1..4   rows each of its wavefronts keeps (0 = choose: as many as fit the
+ *                    registers - 4, or 3 where a lane holds two vectors of a row -, or just enough for a
  *                    grid that fits one workgroup)
  *   "resident_spin_limit"  0 | n  polls a workgroup waits at that barrier before giving up: n - 1
  *                    beyond the first (0 = default, about 4 million: seconds)
