@@ -30,6 +30,20 @@ def test_header_and_exports_agree(J):
         assert hasattr(raw, name), name
 
 
+def test_header_is_plain_c_and_the_library_links_from_c(J, tmp_path):
+    """include/jacobi.h compiled as strict C99 by gcc, a small C program linked against the built library and
+    run: plan creation, layout, options, pass planning and argument errors, none of which touches a device."""
+    import subprocess
+    src = os.path.join(ROOT, "tests", "c_client", "client.c")
+    exe = str(tmp_path / "client")
+    libdir = os.path.dirname(J.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    src, "-o", exe, "-L", libdir, "-l:" + os.path.basename(J.LIB_PATH), "-Wl,-rpath," + libdir],
+                   check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and out.stdout.strip().endswith("c client ok"), out.stdout + out.stderr
+
+
 def test_core_entry_points_present(J):
     for name in ("jacobi_create", "jacobi_sweep", "halo_exchange", "residual_norm"):
         assert name in J.EXPORTS
