@@ -377,8 +377,9 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    instead of loading them again (0 = choose: 8 on tiles of 1024 rows and more, else
  *                    4; 1 = off: every wavefront loads its own border rows; default 0).  Only with
  *                    "rows_per_strip" = 0 and "unroll" = 0, and tiles at least one band high.
- *   "cu_lds"         0 | 65536..2^20  LDS bytes of a CU that the workgroup limits of large-grid launches are
- *                    computed from (0 = the device's figure, read by jacobi_prepare; default 0).  Those
+ *   "cu_lds"         0..2^20  LDS bytes of a CU that the workgroup limits of large-grid launches are
+ *                    computed from (0 = the device's figure, read by jacobi_prepare; default 0; below
+ *                    65536: no limits are requested).  Those
  *                    launches request (cu_lds / n - 4096) bytes of LDS they never touch so that at most
  *                    n workgroups share a CU (n = 1: 3-D update of fp64 grids of 1 GiB and more; n = 2:
  *                    2-D blocked passes on such grids).  Before a kernel variant uses the request for the

@@ -801,23 +801,36 @@ bool grids_overlap(const jacobi_plan *p, const void *a, const void *b)
     return d < (uintptr_t)p->lay.grid_bytes;
 }
 
-int64_t *option_slot(jacobi_plan *p, const char *key)
+// The settable options: where the value lives, its range, and - where only a few values inside the range are
+// meaningful - those values (zero-terminated list after the always-allowed 0).
+struct OptionSpec {
+    const char *key;
+    int64_t jacobi_plan::*field;
+    int64_t lo, hi;
+    int64_t only[6];        // if only[0] != 0: the value must be 0 or one of these
+};
+const OptionSpec OPTIONS[] = {
+    {"fused", &jacobi_plan::fused, 0, 1, {}},
+    {"rows_per_strip", &jacobi_plan::rows_per_strip, 0, 4096, {}},
+    {"nontemporal", &jacobi_plan::nontemporal, 0, 2, {}},
+    {"profile", &jacobi_plan::profile, 0, 1, {}},
+    {"unroll", &jacobi_plan::unroll, 0, 16, {1, 2, 4, 8, 16}},
+    {"xcd_chunk", &jacobi_plan::xcd_chunk, 0, 1 << 20, {}},
+    {"rows_per_wave", &jacobi_plan::rows_per_wave, 0, 4, {1, 2, 4}},
+    {"tblock", &jacobi_plan::tblock, 1, jk::TP_MAX, {}},
+    {"cooperative", &jacobi_plan::cooperative, 0, 1, {}},
+    {"resident", &jacobi_plan::resident, 0, 1, {}},
+    {"resident_depth", &jacobi_plan::resident_depth, 0, 31, {}},
+    {"resident_rows", &jacobi_plan::resident_rows, 0, jk::RES_MAX_RW, {}},
+    {"resident_spin_limit", &jacobi_plan::resident_spin_limit, 0, 1LL << 31, {}},
+    {"cu_lds", &jacobi_plan::cu_lds_option, 0, 1LL << 20, {}},
+    {"stack", &jacobi_plan::stack, 0, 8, {1, 4, 8}},
+};
+
+const OptionSpec *find_option(const char *key)
 {
-    if (!strcmp(key, "fused")) return &p->fused;
-    if (!strcmp(key, "rows_per_strip")) return &p->rows_per_strip;
-    if (!strcmp(key, "nontemporal")) return &p->nontemporal;
-    if (!strcmp(key, "profile")) return &p->profile;
-    if (!strcmp(key, "unroll")) return &p->unroll;
-    if (!strcmp(key, "xcd_chunk")) return &p->xcd_chunk;
-    if (!strcmp(key, "rows_per_wave")) return &p->rows_per_wave;
-    if (!strcmp(key, "tblock")) return &p->tblock;
-    if (!strcmp(key, "cooperative")) return &p->cooperative;
-    if (!strcmp(key, "resident")) return &p->resident;
-    if (!strcmp(key, "resident_depth")) return &p->resident_depth;
-    if (!strcmp(key, "resident_rows")) return &p->resident_rows;
-    if (!strcmp(key, "resident_spin_limit")) return &p->resident_spin_limit;
-    if (!strcmp(key, "cu_lds")) return &p->cu_lds_option;
-    if (!strcmp(key, "stack")) return &p->stack;
+    for (const OptionSpec &o : OPTIONS)
+        if (!strcmp(key, o.key)) return &o;
     return nullptr;
 }
 
@@ -1321,18 +1334,25 @@ int residual_norm_host(jacobi_plan *plan, void *grid, double *result_host, void 
 int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value)
 {
     if (!plan || !key) return fail(JACOBI_EINVAL, "NULL argument");
-    int64_t *slot = option_slot(plan, key);
-    if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    const int64_t hi = slot == &plan->rows_per_strip ? 4096 : slot == &plan->unroll ? 16 : slot == &plan->nontemporal ? 2 : slot == &plan->xcd_chunk ? (1 << 20) : slot == &plan->rows_per_wave ? 4 : slot == &plan->tblock ? jk::TP_MAX : slot == &plan->resident_depth ? 31 : slot == &plan->resident_rows ? jk::RES_MAX_RW : slot == &plan->resident_spin_limit ? (1LL << 31) : slot == &plan->cu_lds_option ? (1LL << 20) : slot == &plan->stack ? 8 : 1;
-    if (value < 0 || value > hi) return fail(JACOBI_EINVAL, "option value out of range");
-    if (slot == &plan->unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
-        return fail(JACOBI_EINVAL, "unroll must be 0, 1, 2, 4, 8 or 16");
-    if (slot == &plan->stack && value != 0 && value != 1 && value != 4 && value != 8)
-        return fail(JACOBI_EINVAL, "stack must be 0, 1, 4 or 8");
-    if (slot == &plan->tblock && value < 1) return fail(JACOBI_EINVAL, "tblock must be 1..12");
-    if (slot == &plan->rows_per_wave && value != 0 && value != 1 && value != 2 && value != 4)
-        return fail(JACOBI_EINVAL, "rows_per_wave must be 0, 1, 2 or 4");
-    *slot = value;
+    const OptionSpec *o = find_option(key);
+    if (!o) return fail(JACOBI_EINVAL, "unknown option");
+    bool ok = value >= o->lo && value <= o->hi;
+    if (ok && value != 0 && o->only[0] != 0) {
+        ok = false;
+        for (int64_t allowed : o->only) ok = ok || (allowed != 0 && value == allowed);
+    }
+    if (!ok) {
+        std::string msg = std::string("option ") + key + ": value out of range (" + std::to_string(o->lo) + ".." +
+                          std::to_string(o->hi);
+        if (o->only[0] != 0) {
+            msg += "; 0";
+            for (int64_t allowed : o->only)
+                if (allowed != 0) msg += ", " + std::to_string(allowed);
+            msg += " only";
+        }
+        return fail(JACOBI_EINVAL, (msg + ")").c_str());
+    }
+    plan->*(o->field) = value;
     return JACOBI_OK;
 }
 
@@ -1344,9 +1364,9 @@ int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value)
     if (!strcmp(key, "lds_request_1")) { *value = lds_to_limit_workgroups(plan, 1); return JACOBI_OK; }
     if (!strcmp(key, "lds_request_2")) { *value = lds_to_limit_workgroups(plan, 2); return JACOBI_OK; }
     if (!strcmp(key, "num_cu")) { *value = plan->num_cu; return JACOBI_OK; }
-    int64_t *slot = option_slot(const_cast<jacobi_plan *>(plan), key);
-    if (!slot) return fail(JACOBI_EINVAL, "unknown option");
-    *value = *slot;
+    const OptionSpec *o = find_option(key);
+    if (!o) return fail(JACOBI_EINVAL, "unknown option");
+    *value = plan->*(o->field);
     return JACOBI_OK;
 }
 
