@@ -204,7 +204,7 @@ def main() -> int:
     ap.add_argument("--option", action="append", default=[], help="key=value passed to jacobi_set_option")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (tiles of one device stand in for a node's share "
+        print("bench.py: the library runs on ONE GPU (tiles of one device stand in for a node's share "
               "of blocks); --gpus N with N > 1 is not supported", file=sys.stderr)
         return 2
 
