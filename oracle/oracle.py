@@ -15,8 +15,10 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "jacobi_oracle.c")
-_LIB = os.path.join(_HERE, "libjacobi_oracle.so")
+# JACOBI_ORACLE_SRC: build and load another source file instead (the mutation test plants mistakes in a COPY
+# of jacobi_oracle.c and checks that the pins notice each of them); the library is built next to that file.
+_SRC = os.environ.get("JACOBI_ORACLE_SRC") or os.path.join(_HERE, "jacobi_oracle.c")
+_LIB = (os.path.splitext(_SRC)[0] + ".so") if os.environ.get("JACOBI_ORACLE_SRC") else os.path.join(_HERE, "libjacobi_oracle.so")
 _lib: Optional[ctypes.CDLL] = None
 
 _SUF = {np.dtype(np.float64): "f64", np.dtype(np.float32): "f32"}
