@@ -255,6 +255,20 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
                        int nstreams, void *stream, void **final);
 
 /*
+ * jacobi_task_dependencies: the dependency graph jacobi_sweep_tasks executes (paper Sec. IV-A: a task's
+ * dependencies follow from the data it reads and writes), for inspection or for a caller that wants to
+ * schedule the tasks itself.  Task t of an iteration is the update of tiles [t*tiles_per_task,
+ * (t+1)*tiles_per_task) (the last task may be shorter).  It reads its tiles' interiors and halo cells of the
+ * grid the previous iteration wrote, so it depends on the tasks OF THE PREVIOUS ITERATION that own one of
+ * its tiles or a face neighbour of one - itself included; the same edges order the reuse of the two
+ * ping-pong grids.  The first min(*ndeps, capacity) entries of deps[] receive those task indices (no
+ * particular order, no duplicates), *ndeps their number, *ntasks (nullable) the number of tasks per
+ * iteration.  Host-only: no device call.  Errors: EINVAL (NULL, tiles_per_task < 1, task out of range).
+ */
+int jacobi_task_dependencies(jacobi_plan *plan, int tiles_per_task, int task, int *deps, int capacity,
+                             int *ndeps, int *ntasks);
+
+/*
  * halo_exchange: for every pair of face-adjacent tiles, copy each tile's edge cells
  * into the other's halo cells, in place in `grid` (paper Sec. VI-C: pack, transfer,
  * unpack - on one device the three collapse into one gather-scatter copy).

@@ -12,7 +12,7 @@ import importlib
 _API = (
     "JacobiError", "JacobiLayout", "jacobi_create", "jacobi_prepare", "jacobi_scratch_bytes", "jacobi_destroy", "jacobi_grid_bytes",
     "jacobi_get_layout", "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_run", "jacobi_sweep_tasks",
-    "jacobi_pass_schedule", "halo_exchange",
+    "jacobi_task_dependencies", "jacobi_pass_schedule", "halo_exchange",
     "residual_norm", "residual_norm_host", "residual_norm_noalloc", "jacobi_set_option", "jacobi_get_option",
     "jacobi_profile_read", "jacobi_last_error", "jacobi_stream_copy", "JACOBI_F64", "JACOBI_F32",
     "EXPORTS", "LIB_PATH",

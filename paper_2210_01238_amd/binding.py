@@ -20,7 +20,7 @@ JACOBI_OK, JACOBI_EINVAL, JACOBI_ENOTDIV, JACOBI_ENOMEM, JACOBI_EHIP = 0, 1, 2, 
 
 EXPORTS = (
     "jacobi_create", "jacobi_prepare", "jacobi_scratch_bytes", "jacobi_destroy", "jacobi_grid_bytes", "jacobi_get_layout",
-    "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_run", "jacobi_sweep_tasks", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
+    "jacobi_scatter", "jacobi_gather", "jacobi_sweep", "jacobi_sweep_residual", "jacobi_run", "jacobi_sweep_tasks", "jacobi_task_dependencies", "jacobi_pass_schedule", "halo_exchange", "residual_norm",
     "residual_norm_host", "residual_norm_noalloc", "jacobi_set_option", "jacobi_get_option", "jacobi_profile_read",
     "jacobi_last_error", "jacobi_stream_copy",
 )
@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
     lib.jacobi_sweep_residual.argtypes = [vp, vp, vp, ci, vp, P(vp), vp]
     lib.jacobi_run.argtypes = [vp, vp, vp, ci, ci, vp, vp, P(vp)]
     lib.jacobi_sweep_tasks.argtypes = [vp, vp, vp, ci, ci, ci, vp, P(vp)]
+    lib.jacobi_task_dependencies.argtypes = [vp, ci, ci, P(ci), ci, P(ci), P(ci)]
     lib.jacobi_pass_schedule.argtypes = [vp, ci, P(ci), ci, P(ci)]
     lib.halo_exchange.argtypes = [vp, vp, vp]
     lib.residual_norm.argtypes = [vp, vp, vp, vp]
@@ -159,6 +160,20 @@ def jacobi_pass_schedule(plan: int, iters: int) -> list:
     buf = (ctypes.c_int * max(n.value, 1))()
     _check(lib.jacobi_pass_schedule(plan, int(iters), buf, n.value, ctypes.byref(n)))
     return list(buf[:n.value])
+
+
+def jacobi_task_dependencies(plan: int, tiles_per_task: int) -> list:
+    """For every task of an iteration (groups of tiles_per_task consecutive tiles): the tasks of the previous
+    iteration it depends on, as jacobi_sweep_tasks orders them."""
+    n, nt = ctypes.c_int(), ctypes.c_int()
+    _check(lib.jacobi_task_dependencies(plan, int(tiles_per_task), 0, None, 0, ctypes.byref(n), ctypes.byref(nt)))
+    out = []
+    for t in range(nt.value):
+        _check(lib.jacobi_task_dependencies(plan, int(tiles_per_task), t, None, 0, ctypes.byref(n), None))
+        buf = (ctypes.c_int * max(n.value, 1))()
+        _check(lib.jacobi_task_dependencies(plan, int(tiles_per_task), t, buf, n.value, ctypes.byref(n), None))
+        out.append(sorted(buf[:n.value]))
+    return out
 
 
 def jacobi_sweep_residual(plan: int, grid_in: int, grid_out: int, iters: int, residual_in_dev: int,

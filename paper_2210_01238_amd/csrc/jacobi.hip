@@ -1199,6 +1199,22 @@ int jacobi_sweep_tasks(jacobi_plan *plan, void *in, void *out, int iters, int ti
     return JACOBI_OK;
 }
 
+int jacobi_task_dependencies(jacobi_plan *plan, int tiles_per_task, int task, int *deps, int capacity, int *ndeps,
+                             int *ntasks)
+{
+    if (!plan || !ndeps || (capacity > 0 && !deps)) return fail(JACOBI_EINVAL, "NULL argument");
+    if (tiles_per_task < 1 || capacity < 0) return fail(JACOBI_EINVAL, "tiles_per_task must be >= 1 and capacity >= 0");
+    const int group = tiles_per_task > plan->geo.ntiles ? plan->geo.ntiles : tiles_per_task;
+    const int n = (int)ceil_div(plan->geo.ntiles, group);
+    if (ntasks) *ntasks = n;
+    if (task < 0 || task >= n) return fail(JACOBI_EINVAL, "task index out of range");
+    if (plan->task_group != group) build_task_deps(plan, group);
+    const std::vector<int> &d = plan->task_deps[task];
+    for (int i = 0; i < (int)d.size() && i < capacity; ++i) deps[i] = d[i];
+    *ndeps = (int)d.size();
+    return JACOBI_OK;
+}
+
 int jacobi_pass_schedule(const jacobi_plan *plan, int iters, int *depths, int capacity, int *npasses)
 {
     if (!plan || !npasses || (capacity > 0 && !depths)) return fail(JACOBI_EINVAL, "NULL argument");

@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -252,6 +253,65 @@ def test_workgroup_limit_request_arithmetic(J):
                 bad()
         J.jacobi_set_option(p, "cu_lds", 1000)             # below 64 KiB: no limits
         assert J.jacobi_get_option(p, "lds_request_1") == 0
+    finally:
+        J.jacobi_destroy(p)
+
+
+def access_sets(dims, tiles, task_tiles):
+    """Cells (as padded global indices) a task of tiles `task_tiles` READS from the grid the previous iteration
+    wrote - every interior cell of its tiles and the face-neighbour cells beyond them that lie inside the
+    domain - and the cells it WRITES: its tiles' interiors."""
+    import itertools
+    tile = [d // t for d, t in zip(dims, tiles)]
+    reads, writes = set(), set()
+    for t in task_tiles:
+        idx = list(np.unravel_index(t, tiles))
+        lo = [i * s + 1 for i, s in zip(idx, tile)]
+        for cell in itertools.product(*[range(l, l + s) for l, s in zip(lo, tile)]):
+            writes.add(cell)
+            reads.add(cell)
+            for d in range(len(dims)):
+                for step in (-1, 1):
+                    nb = list(cell); nb[d] += step
+                    if 1 <= nb[d] <= dims[d]:
+                        reads.add(tuple(nb))
+    return reads, writes
+
+
+@pytest.mark.parametrize("dims,tiles,group", [
+    ((8, 12), (4, 3), 1), ((8, 12), (4, 3), 2), ((8, 12), (4, 3), 5), ((8, 12), (4, 3), 12), ((8, 12), (4, 3), 100),
+    ((6, 6), (1, 6), 1), ((6, 6), (6, 1), 4), ((5, 5), (1, 1), 1),
+    ((4, 6, 4), (2, 3, 2), 1), ((4, 6, 4), (2, 3, 2), 3), ((4, 6, 4), (2, 3, 2), 7), ((2, 2, 6), (1, 1, 3), 2),
+])
+def test_task_dependencies_follow_from_read_and_write_sets(J, dims, tiles, group):
+    """The dependency lists jacobi_sweep_tasks uses against lists derived here from what the tasks touch: task a
+    of iteration k+1 depends on task b of iteration k exactly if a reads a cell that b writes (paper Sec. IV-A)."""
+    p = J.jacobi_create(dims, tiles)
+    try:
+        got = J.jacobi_task_dependencies(p, group)
+    finally:
+        J.jacobi_destroy(p)
+    ntiles = int(np.prod(tiles))
+    g = min(group, ntiles)
+    tasks = [list(range(s, min(s + g, ntiles))) for s in range(0, ntiles, g)]
+    sets = [access_sets(dims, tiles, tt) for tt in tasks]
+    want = [sorted(b for b in range(len(tasks)) if sets[a][0] & sets[b][1]) for a in range(len(tasks))]
+    assert got == want
+    # the relation is symmetric (face adjacency) and reflexive, so the same edges cover write-after-read on the ping-pong grids
+    for a, deps in enumerate(got):
+        assert a in deps and all(a in got[b] for b in deps)
+
+
+def test_task_dependencies_argument_errors(J):
+    p = J.jacobi_create((8, 12), (4, 3))
+    try:
+        n, nt = ctypes.c_int(), ctypes.c_int()
+        raw = J.binding.lib
+        assert raw.jacobi_task_dependencies(p, 2, 0, None, 0, ctypes.byref(n), ctypes.byref(nt)) == 0 and nt.value == 6
+        assert raw.jacobi_task_dependencies(p, 2, 6, None, 0, ctypes.byref(n), None) == 1       # task out of range
+        assert raw.jacobi_task_dependencies(p, 0, 0, None, 0, ctypes.byref(n), None) == 1
+        assert raw.jacobi_task_dependencies(p, 2, 0, None, 3, ctypes.byref(n), None) == 1       # capacity without a buffer
+        assert raw.jacobi_task_dependencies(None, 2, 0, None, 0, ctypes.byref(n), None) == 1
     finally:
         J.jacobi_destroy(p)
 
