@@ -323,7 +323,7 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    up to 128 rows / the tile depth for blocked passes (default 0)
  *   "nontemporal"    0 | 1 | 2   how single-step updates store their results: 2 = streaming
  *                    (non-temporal) stores, 0 = plain stores, 1 = choose (default): plain when both
- *                    grids fit the Infinity Cache (grids of at most 64 MiB: the next iteration then
+ *                    grids fit the Infinity Cache (grids of at most 124 MiB: the next iteration then
  *                    loads them from the cache), streaming beyond.  Streaming loads were measured
  *                    slower (border rows are re-read from cache) and are not offered.  Blocked passes
  *                    always stream.
@@ -334,8 +334,9 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *   "rows_per_wave"  0 | 1 | 2 | 4  3-D: rows of a plane one wavefront keeps in registers
  *                    (0 = 4 where the tile allows; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
- *                    takes G consecutive ones (1 = hardware order; 0 = choose: 8, or 16 for the
- *                    launches that run one workgroup per CU; default 0)
+ *                    takes G consecutive ones (1 = hardware order; 0 = choose: 8, 16 for the
+ *                    launches that run one workgroup per CU, 32 for the 2-D update of cache-resident
+ *                    grids of 24 MiB and more; default 0)
  *   "tblock"         1..12   temporal blocking depth: jacobi_sweep advances up to this many
  *                    iterations per pass over memory (3-D: at most 4 in fp64, 3 in fp32).  The
  *                    iterations of a call are cut into equally deep passes: in 2-D as many as fit

@@ -42,7 +42,13 @@ constexpr int MAX_TASK_STREAMS = 16;
 constexpr int MAX_PROFILE_EVENTS = 8192;
 constexpr int MAX_COPY_BLOCKS = 1 << 20;
 constexpr int64_t LARGE_GRID_BYTES = 1LL << 30;   // grids from this size on get the workgroup-per-CU limits
-constexpr int64_t CACHED_GRID_BYTES = 64LL << 20; // two grids of at most this size each stay in the 256 MB Infinity Cache
+// Two grids of at most this size each fit the 256 MiB Infinity Cache with room to spare (a plain copy of 135 MB
+// to another 135 MB still runs at 7.7 TB/s, of 160 MB at 6.1).  Measured on the update: plain stores win clearly up
+// to 240^3 (120 MiB: 54.0 -> 47.0 us) and 3584^2 (99 MiB: 37.2 -> 33.6); at 4096^2 (2 x 128.8 MiB, just over the
+// cache) the outcome depends on where the two buffers happen to lie (42 - 48 us against 47.4 with streaming
+// stores), at 4224^2 (137 MiB) they are level, and from 256^3 (136 MiB: 53.7 -> 58.5) and 4352^2 on they lose.
+constexpr int64_t CACHED_GRID_BYTES = 124LL << 20;
+constexpr int64_t CACHED_CHUNK_BYTES = 24LL << 20;  // cache-resident 2-D grids from this size on: XCD chunks of 32
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -92,8 +98,9 @@ struct SweepConfig {
 
 // Store flavour of the single-step updates (bit 2 of the kernels' NT argument: streaming stores): the option, or,
 // left to the library (1), streaming unless both grids fit the Infinity Cache - there a plain store keeps the
-// result on-chip for the next iteration's loads (2048^2: 15.5 -> 11.3 us per iteration), while on grids beyond
-// it plain stores lose (6144^2: 102 -> 110 us) because the written lines push out what is still to be read.
+// result on-chip for the next iteration's loads (2048^2: 15.5 -> 11.3 us per iteration, 3072^2: 28.5 -> 24.9,
+// 224^3: 45.6 -> 39.4), while on grids beyond it plain stores lose (6144^2: 102 -> 110 us) because the written
+// lines push out what is still to be read.
 int store_flavour(const jacobi_plan *p)
 {
     if (p->nontemporal != 1) return (int)p->nontemporal;
@@ -151,8 +158,10 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
         // mid-sized 2-D grids: at 8 rows a 4096^2 grid gives each CU only ~3 rounds of workgroups
         // and the last round runs half empty; 4-row strips measure 8 % faster there
         if (!d3 && mode != jk::MODE_RESIDUAL && (int64_t)ceil_div(extent, R) * lanes_of_work < 24576) R = 4;
-        // (3-D: 16-plane strips until fewer than 2048 would be left: 256^3 in 128^3 tiles 57.4 -> 53.9 us with 16 instead of 8)
-        while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < (d3 ? 2048 : 4096)) R /= 2;
+        // (3-D prefers few long strips even on small grids - 16 planes until fewer than 512 strips would be left:
+        // 256^3 in 128^3 tiles 57.4 -> 53.9 us with 16 planes instead of 8, 224^3 39.4 -> 34.6, one 128^3 tile
+        // 14.6 us with 2048 strips of 2 planes, 11.8 with 512 of 8)
+        while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < (d3 ? 512 : 4096)) R /= 2;
     }
     if (R > extent) R = extent;
     sp.R = R;
@@ -166,6 +175,11 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     c.whole_cu = d3 && mode != jk::MODE_RESIDUAL && p->esize == 8 && g.pitch >= jk::WAVE * nv &&
                  p->lay.grid_bytes >= LARGE_GRID_BYTES;
     sp.xcd_chunk = xcd_chunk_of(p, c.whole_cu);
+    // 2-D updates of cache-resident grids: longer runs per XCD (2048^2: 11.8 -> 11.3 us, 3072^2: 24.6 -> 23.2;
+    // below 2048^2 the hardware's own order is as good or better)
+    if (!d3 && mode != jk::MODE_RESIDUAL && p->xcd_chunk <= 0 && store_flavour(p) == 0 &&
+        p->lay.grid_bytes >= CACHED_CHUNK_BYTES)
+        sp.xcd_chunk = 32;
     if (d3) {
         if (u <= 0) u = c.whole_cu ? 1 : 2;     // planes per trip of the pipeline
         if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
