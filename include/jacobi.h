@@ -319,7 +319,8 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  * Options (all int64).  Unknown key or out-of-range value -> EINVAL.
  *   "fused"          0 | 1   update kernel pushes edge cells to neighbour halos (default 1)
  *   "rows_per_strip" 0 | 1..4096  rows (2-D) or planes (3-D) one wavefront marches
- *                    through; 0 = choose from the shape: 8 rows / 16 planes for single steps,
+ *                    through; 0 = choose from the shape: 8 rows / 16 planes for single steps
+ *                    (fewer on small grids, so that there are about a thousand wavefronts),
  *                    up to 128 rows / the tile depth for blocked passes (default 0)
  *   "nontemporal"    0 | 1 | 2   how single-step updates store their results: 2 = streaming
  *                    (non-temporal) stores, 0 = plain stores, 1 = choose (default): plain when both
@@ -329,14 +330,15 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    always stream.
  *   "unroll"         0 | 1 | 2 | 4 | 8  rows (planes) whose loads a wavefront issues back to
  *                    back before computing (3-D: planes per trip of the load pipeline); 0 = choose:
- *                    2-D the whole strip, up to 8; 3-D 2, or 1 on fp64 grids of 1 GiB and more
- *                    (3-D accepts at most 4) (default 0)
+ *                    2-D the whole strip, up to 8; 3-D 1 on grids below 320 MiB and on fp64 grids of
+ *                    1 GiB and more, else 2 (3-D accepts at most 4) (default 0)
  *   "rows_per_wave"  0 | 1 | 2 | 4  3-D: rows of a plane one wavefront keeps in registers
- *                    (0 = 4 where the tile allows; default 0)
+ *                    (0 = choose: 4 where the tile allows; 2 for updates of grids of at most 64 MiB,
+ *                    1 on tiny ones, which want more and smaller wavefronts; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
- *                    takes G consecutive ones (1 = hardware order; 0 = choose: 8, 16 for the
- *                    launches that run one workgroup per CU, 32 for the 2-D update of cache-resident
- *                    grids of 24 MiB and more; default 0)
+ *                    takes G consecutive ones (1 = hardware order; 0 = choose: 8; 3-D updates 16,
+ *                    or 1 on grids below 24 MiB; 32 for the 2-D update of cache-resident grids of
+ *                    24 MiB and more; default 0)
  *   "tblock"         1..12   temporal blocking depth: jacobi_sweep advances up to this many
  *                    iterations per pass over memory (3-D: at most 4 in fp64, 3 in fp32).  The
  *                    iterations of a call are cut into equally deep passes: in 2-D as many as fit

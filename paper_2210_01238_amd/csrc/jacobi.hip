@@ -136,19 +136,40 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     SweepConfig c;
     StripParams &sp = c.sp;
     c.rows_per_wave = 1;
+    // 3-D updates of grids that are not large (below 1 GiB the march is not limited to one workgroup per CU): what
+    // the sizes from 32^3 to 384^3 measured best with - see the notes at the choices below
+    const bool d3_small_update = d3 && mode != jk::MODE_RESIDUAL && p->lay.grid_bytes < LARGE_GRID_BYTES;
+    const bool narrow_f32 = d3 && p->esize == 4 && g.pitch <= 2 * jk::WAVE;
     if (d3) {
         int rw = (int)p->rows_per_wave;
-        if (rw <= 0) rw = g.th >= 4 ? 4 : g.th >= 2 ? 2 : 1;
+        if (rw <= 0) {
+            rw = g.th >= 4 ? 4 : g.th >= 2 ? 2 : 1;
+            // grids that live in the caches want more, smaller wavefronts: 2 rows each (128^3 11.8 -> 8.5 us per
+            // iteration, 160^3 18.3 -> 15.8, 192^3 28.0 -> 24.0; from 256^3 on 4 rows are better again).  fp32 rows of
+            // 128 cells keep 4: only that variant has the 8-byte lanes they need.
+            if (rw == 4 && d3_small_update && !narrow_f32 && p->lay.grid_bytes <= (64LL << 20)) rw = 2;
+        }
         c.rows_per_wave = rw;
     }
     // fp32 rows of at most 128 elements would leave half of a wavefront's 16-byte lanes idle: 8-byte lanes
-    c.lane_elems = (d3 && p->esize == 4 && g.pitch <= 2 * jk::WAVE && c.rows_per_wave == 4) ? 2 : nv;
+    c.lane_elems = (narrow_f32 && c.rows_per_wave == 4) ? 2 : nv;
     sp.nseg = (int)ceil_div(g.pitch, (int64_t)jk::WAVE * c.lane_elems);
     const int extent = d3 ? g.td : g.th;       // marching direction
-    const int64_t lanes_of_work =
+    int64_t lanes_of_work =
         (int64_t)g.ntiles * sp.nseg * (d3 ? ceil_div(g.th, c.rows_per_wave) : 1);
     int R = (int)p->rows_per_strip;
-    if (R <= 0) {
+    if (R <= 0 && d3_small_update) {
+        // 16 planes per strip, fewer until there are about a thousand wavefronts (64^3: 7.4 -> 4.5 us per iteration
+        // with 1024 strips of 2 planes x 2 rows; 128^3 in 64^3 tiles 18.9 -> 10.1); tiny grids go down to one row
+        // per wavefront as well (32^3: 6.3 -> 4.0)
+        R = 16;
+        while (R > 2 && (int64_t)ceil_div(extent, R) * lanes_of_work < 1024) R /= 2;
+        if (p->rows_per_wave <= 0 && c.rows_per_wave > 1 && !narrow_f32 &&
+            (int64_t)ceil_div(extent, R) * lanes_of_work < 512) {
+            c.rows_per_wave = 1;
+            lanes_of_work = (int64_t)g.ntiles * sp.nseg * g.th;
+        }
+    } else if (R <= 0) {
         // Short strips whose loads are all issued at once stream best (the chip then walks
         // through memory as one narrow front); 8 rows keeps the border re-read at 2 rows in 10.
         // Small problems get shorter strips so that there are enough wavefronts to fill the chip.
@@ -158,9 +179,7 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
         // mid-sized 2-D grids: at 8 rows a 4096^2 grid gives each CU only ~3 rounds of workgroups
         // and the last round runs half empty; 4-row strips measure 8 % faster there
         if (!d3 && mode != jk::MODE_RESIDUAL && (int64_t)ceil_div(extent, R) * lanes_of_work < 24576) R = 4;
-        // (3-D prefers few long strips even on small grids - 16 planes until fewer than 512 strips would be left:
-        // 256^3 in 128^3 tiles 57.4 -> 53.9 us with 16 planes instead of 8, 224^3 39.4 -> 34.6, one 128^3 tile
-        // 14.6 us with 2048 strips of 2 planes, 11.8 with 512 of 8)
+        // (3-D: 16-plane strips until fewer than 512 strips would be left)
         while (R > 1 && (int64_t)ceil_div(extent, R) * lanes_of_work < (d3 ? 512 : 4096)) R /= 2;
     }
     if (R > extent) R = extent;
@@ -175,13 +194,17 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     c.whole_cu = d3 && mode != jk::MODE_RESIDUAL && p->esize == 8 && g.pitch >= jk::WAVE * nv &&
                  p->lay.grid_bytes >= LARGE_GRID_BYTES;
     sp.xcd_chunk = xcd_chunk_of(p, c.whole_cu);
+    // 3-D updates below 1 GiB: the hardware's own order on small grids (64^3 5.1 -> 4.5 us), runs of 16 from 24 MiB on
+    if (d3_small_update && p->xcd_chunk <= 0) sp.xcd_chunk = p->lay.grid_bytes < CACHED_CHUNK_BYTES ? 1 : 16;
     // 2-D updates of cache-resident grids: longer runs per XCD (2048^2: 11.8 -> 11.3 us, 3072^2: 24.6 -> 23.2;
     // below 2048^2 the hardware's own order is as good or better)
     if (!d3 && mode != jk::MODE_RESIDUAL && p->xcd_chunk <= 0 && store_flavour(p) == 0 &&
         p->lay.grid_bytes >= CACHED_CHUNK_BYTES)
         sp.xcd_chunk = 32;
     if (d3) {
-        if (u <= 0) u = c.whole_cu ? 1 : 2;     // planes per trip of the pipeline
+        // planes per trip of the pipeline: 1 with one workgroup per CU, and on grids up to ~300 MiB (160^3 15.7 ->
+        // 14.5 us, 320^3 109.6 -> 105.9; 384^3, 460 MiB: 179.3 with 1, 174.6 with 2)
+        if (u <= 0) u = c.whole_cu || (d3_small_update && p->lay.grid_bytes < (320LL << 20)) ? 1 : 2;
         if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
     } else if (u <= 0) {
         u = R >= 16 ? 16 : R >= 8 ? 8 : R >= 4 ? 4 : R >= 2 ? 2 : 1;   // all of a short strip at once
