@@ -139,6 +139,7 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     // 3-D updates of grids that are not large (below 1 GiB the march is not limited to one workgroup per CU): what
     // the sizes from 32^3 to 384^3 measured best with - see the notes at the choices below
     const bool d3_small_update = d3 && mode != jk::MODE_RESIDUAL && p->lay.grid_bytes < LARGE_GRID_BYTES;
+    const bool d3_small_residual = d3 && mode == jk::MODE_RESIDUAL && p->lay.grid_bytes < LARGE_GRID_BYTES;
     const bool narrow_f32 = d3 && p->esize == 4 && g.pitch <= 2 * jk::WAVE;
     if (d3) {
         int rw = (int)p->rows_per_wave;
@@ -148,6 +149,8 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
             // iteration, 160^3 18.3 -> 15.8, 192^3 28.0 -> 24.0; from 256^3 on 4 rows are better again).  fp32 rows of
             // 128 cells keep 4: only that variant has the 8-byte lanes they need.
             if (rw == 4 && d3_small_update && !narrow_f32 && p->lay.grid_bytes <= (64LL << 20)) rw = 2;
+            // the read-only pass likes them up to 1 GiB (192^3 24.2 -> 18.6 us, 256^3 30.3 -> 26.3)
+            if (rw == 4 && d3_small_residual && !narrow_f32) rw = 2;
         }
         c.rows_per_wave = rw;
     }
@@ -204,7 +207,7 @@ SweepConfig make_config(const jacobi_plan *p, int mode)
     if (d3) {
         // planes per trip of the pipeline: 1 with one workgroup per CU, and on grids up to ~300 MiB (160^3 15.7 ->
         // 14.5 us, 320^3 109.6 -> 105.9; 384^3, 460 MiB: 179.3 with 1, 174.6 with 2)
-        if (u <= 0) u = c.whole_cu || (d3_small_update && p->lay.grid_bytes < (320LL << 20)) ? 1 : 2;
+        if (u <= 0) u = c.whole_cu || d3_small_residual || (d3_small_update && p->lay.grid_bytes < (320LL << 20)) ? 1 : 2;
         if (u > 4) u = 4;                       // 3-D variants are compiled for 1, 2, 4
     } else if (u <= 0) {
         u = R >= 16 ? 16 : R >= 8 ? 8 : R >= 4 ? 4 : R >= 2 ? 2 : 1;   // all of a short strip at once
