@@ -333,8 +333,9 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  *                    2-D the whole strip, up to 8; 3-D 1 on grids below 320 MiB and on fp64 grids of
  *                    1 GiB and more, else 2 (3-D accepts at most 4) (default 0)
  *   "rows_per_wave"  0 | 1 | 2 | 4  3-D: rows of a plane one wavefront keeps in registers
- *                    (0 = choose: 4 where the tile allows; 2 for updates of grids of at most 64 MiB,
- *                    1 on tiny ones, which want more and smaller wavefronts; default 0)
+ *                    (0 = choose: 4 where the tile allows; 2 for updates of grids of at most 64 MiB -
+ *                    1 on tiny ones - and for the residual pass below 1 GiB, which want more and
+ *                    smaller wavefronts; default 0)
  *   "xcd_chunk"      0..2^20  G: within every 8*G consecutive workgroups, each of the 8 XCDs
  *                    takes G consecutive ones (1 = hardware order; 0 = choose: 8; 3-D updates 16,
  *                    or 1 on grids below 24 MiB; 32 for the 2-D update of cache-resident grids of
