@@ -409,7 +409,11 @@ int residual_norm_noalloc(jacobi_plan *plan, void *grid, double *result_dev, voi
  * None of the options changes any result bit.
  * jacobi_get_option also reads these figures (not settable): "lds_limit_failed" (see "cu_lds"),
  * "lds_request_1" / "lds_request_2" (the LDS bytes requested to keep 1 / 2 workgroups per CU; 0 while
- * the LDS size is unknown), "num_cu" (compute units; 256 until jacobi_prepare has asked the device).
+ * the LDS size is unknown), "num_cu" (compute units; 256 until jacobi_prepare has asked the device),
+ * and what a single-step launch will run with under the current options (host-only, the choices the
+ * 0 = "choose" settings resolve to): "update_rows_per_strip", "update_rows_per_wave", "update_unroll",
+ * "update_xcd_chunk", "update_strips" (wavefronts of work), "update_one_workgroup_per_cu",
+ * "update_streaming_stores", and the same with "residual_" for the stand-alone residual pass.
  */
 int jacobi_set_option(jacobi_plan *plan, const char *key, int64_t value);
 int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value);

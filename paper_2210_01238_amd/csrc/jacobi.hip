@@ -1420,6 +1420,23 @@ int jacobi_get_option(const jacobi_plan *plan, const char *key, int64_t *value)
     if (!strcmp(key, "lds_request_1")) { *value = lds_to_limit_workgroups(plan, 1); return JACOBI_OK; }
     if (!strcmp(key, "lds_request_2")) { *value = lds_to_limit_workgroups(plan, 2); return JACOBI_OK; }
     if (!strcmp(key, "num_cu")) { *value = plan->num_cu; return JACOBI_OK; }
+    // what the single-step launches will run with under the current options: "update_..." for the update,
+    // "residual_..." for the stand-alone residual pass (the strip-per-wavefront kernel)
+    for (const char *prefix : {"update_", "residual_"}) {
+        const size_t n = strlen(prefix);
+        if (strncmp(key, prefix, n)) continue;
+        const int mode = prefix[0] == 'u' ? jk::MODE_UPDATE : jk::MODE_RESIDUAL;
+        const SweepConfig c = make_config(plan, mode);
+        const char *what = key + n;
+        if (!strcmp(what, "rows_per_strip")) { *value = c.sp.R; return JACOBI_OK; }
+        if (!strcmp(what, "rows_per_wave")) { *value = c.rows_per_wave; return JACOBI_OK; }
+        if (!strcmp(what, "unroll")) { *value = c.unroll; return JACOBI_OK; }
+        if (!strcmp(what, "xcd_chunk")) { *value = c.sp.xcd_chunk; return JACOBI_OK; }
+        if (!strcmp(what, "strips")) { *value = c.sp.nstrips; return JACOBI_OK; }
+        if (!strcmp(what, "one_workgroup_per_cu")) { *value = c.whole_cu ? 1 : 0; return JACOBI_OK; }
+        if (!strcmp(what, "streaming_stores")) { *value = store_flavour(plan) == 2 ? 1 : 0; return JACOBI_OK; }
+        return fail(JACOBI_EINVAL, "unknown option");
+    }
     const OptionSpec *o = find_option(key);
     if (!o) return fail(JACOBI_EINVAL, "unknown option");
     *value = plan->*(o->field);

@@ -316,6 +316,46 @@ def test_task_dependencies_argument_errors(J):
         J.jacobi_destroy(p)
 
 
+def test_launch_configuration_of_the_workloads_is_what_was_measured(J):
+    """The settings the 0 = "choose" options resolve to (host-only figures): the configured workloads must keep
+    the launch configuration their measurements and profiles were taken with, whatever is tuned for other sizes."""
+    import jacobi_inputs as gen
+    keys = ("rows_per_strip", "rows_per_wave", "unroll", "xcd_chunk", "strips", "one_workgroup_per_cu", "streaming_stores")
+
+    def chosen(dims, tiles, prefix="update_", dtype=0, **opts):
+        p = J.jacobi_create(dims, tiles, dtype)
+        try:
+            for k, v in opts.items():
+                J.jacobi_set_option(p, k, v)
+            return [J.jacobi_get_option(p, prefix + k) for k in keys]
+        finally:
+            J.jacobi_destroy(p)
+
+    W = gen.WORKLOADS
+    # 2-D: strips of 8 rows with all loads in flight, XCD chunks of 8, streaming stores beyond the Infinity Cache
+    assert chosen(W["C3"].dims, W["C3"].tiles) == [8, 1, 8, 8, 64 * 16 * 256, 0, 1]
+    assert chosen(W["C5"].dims, W["C5"].tiles) == [8, 1, 8, 8, 4096 * 16, 0, 1]
+    assert chosen(W["C2"].dims, W["C2"].tiles) == [4, 1, 4, 8, 16 * 8 * 256, 0, 1]          # 2 x 128.8 MiB: left streaming
+    # 3-D grids of 1 GiB and more: 16 planes x 4 rows, one plane per trip, one workgroup per CU, chunks of 16
+    assert chosen(W["C4"].dims, W["C4"].tiles) == [16, 4, 1, 16, 64 * 32 * 8, 1, 1]
+    assert chosen(W["P1"].dims, W["P1"].tiles) == [16, 4, 1, 16, 384 * 32 * 8, 1, 1]
+    # their stand-alone residual passes
+    assert chosen(W["C4"].dims, W["C4"].tiles, "residual_") == [16, 4, 2, 8, 64 * 32 * 8, 0, 1]
+    # explicit options win
+    assert chosen(W["C3"].dims, W["C3"].tiles, rows_per_strip=16, unroll=4, xcd_chunk=3, nontemporal=0)[:4] + [0] == [16, 1, 4, 3, 0]
+    # cache-resident grids: plain stores; 2-D from 24 MiB on in XCD chunks of 32; small 3-D grids get about a
+    # thousand wavefronts of 2 rows (1 on tiny ones), one plane per trip, the hardware's order
+    assert chosen((3072, 3072), (4, 4)) == [4, 1, 4, 32, 18432, 0, 0]
+    assert chosen((1024, 1024), (2, 2))[3:] == [8, 4096, 0, 0]
+    assert chosen((64, 64, 64), (1, 1, 1)) == [2, 2, 1, 1, 1024, 0, 0]
+    assert chosen((32, 32, 32), (1, 1, 1)) == [2, 1, 1, 1, 512, 0, 0]
+    assert chosen((192, 192, 192), (2, 2, 2)) == [16, 2, 1, 16, 2304, 0, 0]
+    assert chosen((256, 256, 256), (2, 2, 2)) == [16, 4, 1, 16, 2048, 0, 1]                  # 136 MiB: beyond the cache
+    assert chosen((128, 128, 128), (1, 1, 1), dtype=1)[1] == 4                                # fp32 rows of 128 cells: 8-byte lanes
+    with pytest.raises(J.JacobiError):
+        chosen((64, 64), (1, 1), "update_nonsense_")
+
+
 def test_task_execution_argument_errors_without_device(J):
     """Arguments of jacobi_sweep_tasks are checked before any device call."""
     p = J.jacobi_create((48, 48), (48, 48))
